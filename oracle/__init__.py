@@ -1,0 +1,137 @@
+"""CPU oracle for the k-means-quantised matrix product -- TEST INFRASTRUCTURE.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and ``bench.py``'s ``cpu_baseline``
+leg may import this package.  It wraps ``kmq_oracle.cpp`` (plain C++, fp64,
+single-threaded) with numpy marshalling and nothing else; it never touches the
+GPU library and shares no code with it.
+
+The operation is the fused dequantise-multiply of the paper's App. E
+("Kernel implementations"), with per-output-row codebooks and no block scales.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kmq_oracle.cpp")
+_LIB = os.path.join(_HERE, "libkmq_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with the host compiler (no GPU involved)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i64, ci, vp = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p
+        lib.oracle_words_per_row.restype = i64
+        lib.oracle_words_per_row.argtypes = [ci, i64]
+        lib.oracle_pack.restype = ci
+        lib.oracle_pack.argtypes = [vp, i64, i64, ci, vp]
+        lib.oracle_unpack.restype = ci
+        lib.oracle_unpack.argtypes = [vp, i64, i64, ci, vp]
+        lib.oracle_dequant.restype = ci
+        lib.oracle_dequant.argtypes = [vp, vp, i64, i64, ci, vp]
+        lib.oracle_round_bf16.restype = ctypes.c_uint16
+        lib.oracle_round_bf16.argtypes = [ctypes.c_double]
+        lib.oracle_gemm.restype = ci
+        lib.oracle_gemm.argtypes = [vp, vp, vp, i64, i64, ci, i64, i64, i64, vp, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _arr(a, dtype, shape=None):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    if shape is not None and tuple(a.shape) != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {tuple(a.shape)}")
+    return a
+
+
+def words_per_row(bits: int, K: int) -> int:
+    r = _load().oracle_words_per_row(bits, K)
+    if r < 0:
+        raise ValueError("bad bits or K")
+    return int(r)
+
+
+def pack(idx: np.ndarray, bits: int) -> np.ndarray:
+    """uint8 idx[N][K] -> uint32 packed[N][ceil(K*bits/32)]."""
+    idx = _arr(idx, np.uint8)
+    N, K = idx.shape
+    out = np.empty((N, words_per_row(bits, K)), dtype=np.uint32)
+    rc = _load().oracle_pack(_p(idx), N, K, bits, _p(out))
+    if rc == 2:
+        raise ValueError("index out of range for this bit-width")
+    if rc:
+        raise ValueError("bad argument")
+    return out
+
+
+def unpack(packed: np.ndarray, K: int, bits: int) -> np.ndarray:
+    N = packed.shape[0]
+    packed = _arr(packed, np.uint32, (N, words_per_row(bits, K)))
+    out = np.empty((N, K), dtype=np.uint8)
+    if _load().oracle_unpack(_p(packed), N, K, bits, _p(out)):
+        raise ValueError("bad argument")
+    return out
+
+
+def dequant(packed: np.ndarray, codebook: np.ndarray, K: int, bits: int) -> np.ndarray:
+    """bf16 bit patterns (uint16) of the dequantised weights, N x K."""
+    N = packed.shape[0]
+    packed = _arr(packed, np.uint32, (N, words_per_row(bits, K)))
+    codebook = _arr(codebook, np.uint16, (N, 1 << bits))
+    out = np.empty((N, K), dtype=np.uint16)
+    if _load().oracle_dequant(_p(packed), _p(codebook), N, K, bits, _p(out)):
+        raise ValueError("bad argument")
+    return out
+
+
+def round_bf16(y: float) -> int:
+    return int(_load().oracle_round_bf16(float(y)))
+
+
+def gemm(packed: np.ndarray, codebook: np.ndarray, X: np.ndarray, K: int, bits: int,
+         rows: tuple[int, int] | None = None):
+    """Y = X W^T in fp64.  X: uint16 bf16 patterns, shape (M, K) or (K,).
+
+    Returns (Y, A, Ybf16), each M x N (or N for a vector X); with ``rows=(n0, n1)``
+    only those output columns are computed and the rest are NaN / 0.
+    """
+    N = packed.shape[0]
+    packed = _arr(packed, np.uint32, (N, words_per_row(bits, K)))
+    codebook = _arr(codebook, np.uint16, (N, 1 << bits))
+    X = np.ascontiguousarray(X, dtype=np.uint16)
+    vec = X.ndim == 1
+    X2 = X.reshape(1, -1) if vec else X
+    M = X2.shape[0]
+    if X2.shape[1] != K:
+        raise ValueError("X has the wrong K")
+    n0, n1 = (0, N) if rows is None else rows
+    Y = np.full((M, N), np.nan, dtype=np.float64)
+    A = np.full((M, N), np.nan, dtype=np.float64)
+    Yb = np.zeros((M, N), dtype=np.uint16)
+    if _load().oracle_gemm(_p(packed), _p(codebook), _p(X2), N, K, bits, M, n0, n1,
+                           _p(Y), _p(A), _p(Yb)):
+        raise ValueError("bad argument")
+    if vec:
+        return Y[0], A[0], Yb[0]
+    return Y, A, Yb

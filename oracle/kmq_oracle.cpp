@@ -1,0 +1,168 @@
+// kmq_oracle.cpp -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+//
+// A plain, slow, single-threaded CPU statement of what the k-means-quantised
+// matrix product computes, used only to check the GPU library.  Only tests,
+// the smoke check and the benchmark's cpu_baseline leg may call it.  It shares
+// no source, header, table or helper with the GPU library.
+//
+// Operation (paper, App. E "Benchmarking", the fused dequantise-multiply
+// Y^T = dequantize(W~) X^T and its reference routine in "Kernel
+// implementations"; Sec. 2.2 "Nonlinear k-means quantization" for
+// dequantisation = centroid lookup), specialised as the benchmark contract
+// states it: no block scales, one codebook of 2^b bf16 centroids per output
+// row, indices packed b bits each along K.
+//
+//     w[n][k] = real( codebook[n][ idx[n][k] ] )
+//     Y[m][n] = sum_{k=0..K-1} w[n][k] * real( X[m][k] )      (fp64, k ascending)
+//     A[m][n] = sum_{k=0..K-1} | w[n][k] * real( X[m][k] ) |  (tolerance scale)
+//
+// A bf16 x bf16 product has at most 16 significant bits, so every product is
+// exact in fp64 and the fp64 sum of <= 2^14 of them is within ~1e-13*A of the
+// real-number result: the method reaches exactly this value up to rounding
+// order, so the oracle is the definition written out.
+//
+// Packed format (readings of the contract where it is silent are listed in the
+// repository's design notes):
+//   * element k of a row occupies stream bits [k*b, k*b + b) of that row;
+//   * stream bit p lives in 32-bit word p/32 at bit position p%32 (LSB first);
+//   * for b = 3 a field may straddle two consecutive words;
+//   * every row starts on a fresh word, rows hold ceil(K*b/32) words, pad bits
+//     are zero.
+//
+// Pins (tests/test_oracle_*.py): literal hand-computed words, round trips,
+// brute-force dense products from the unpacked uint8 indices, the 1-bit closed
+// form, one-hot / constant-codebook / scaling / permutation invariants, and the
+// shared-codebook special case that reduces to the paper's byte-LUT routine.
+// Nothing here is "parity unpinned".
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <vector>
+
+namespace {
+
+// bf16 is the upper half of an IEEE binary32 pattern.
+double bf16_to_double(uint16_t h) {
+    uint32_t u = static_cast<uint32_t>(h) << 16;
+    float f;
+    std::memcpy(&f, &u, sizeof f);
+    return static_cast<double>(f);
+}
+
+bool bits_ok(int bits) { return bits >= 1 && bits <= 4; }
+
+int64_t words_per_row(int bits, int64_t K) { return (K * bits + 31) / 32; }
+
+// Read the b-bit field of element k from one row's word stream, one bit at a
+// time: deliberately the slowest and most literal form of the format rule.
+uint32_t read_field(const uint32_t* row, int64_t k, int bits) {
+    uint32_t v = 0;
+    for (int j = 0; j < bits; ++j) {
+        int64_t p = k * bits + j;             // stream bit position
+        uint32_t bit = (row[p / 32] >> (p % 32)) & 1u;
+        v |= bit << j;
+    }
+    return v;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t oracle_words_per_row(int bits, int64_t K) {
+    if (!bits_ok(bits) || K < 0) return -1;
+    return words_per_row(bits, K);
+}
+
+// idx[N][K] (one uint8 per element, value < 2^bits) -> packed[N][wpr].
+// Returns 0, or 1 on a bad argument, or 2 if an index is out of range.
+int oracle_pack(const uint8_t* idx, int64_t N, int64_t K, int bits, uint32_t* packed) {
+    if (!bits_ok(bits) || N < 0 || K < 0) return 1;
+    const int64_t wpr = words_per_row(bits, K);
+    for (int64_t n = 0; n < N; ++n) {
+        uint32_t* row = packed + n * wpr;
+        for (int64_t w = 0; w < wpr; ++w) row[w] = 0u;
+        for (int64_t k = 0; k < K; ++k) {
+            uint32_t v = idx[n * K + k];
+            if (v >= (1u << bits)) return 2;
+            for (int j = 0; j < bits; ++j) {
+                int64_t p = k * bits + j;
+                row[p / 32] |= ((v >> j) & 1u) << (p % 32);
+            }
+        }
+    }
+    return 0;
+}
+
+int oracle_unpack(const uint32_t* packed, int64_t N, int64_t K, int bits, uint8_t* idx) {
+    if (!bits_ok(bits) || N < 0 || K < 0) return 1;
+    const int64_t wpr = words_per_row(bits, K);
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k)
+            idx[n * K + k] = static_cast<uint8_t>(read_field(packed + n * wpr, k, bits));
+    return 0;
+}
+
+// Dequantised weights as bf16 bit patterns: Wd[n][k] = codebook[n][idx[n][k]].
+int oracle_dequant(const uint32_t* packed, const uint16_t* codebook, int64_t N, int64_t K,
+                   int bits, uint16_t* Wd) {
+    if (!bits_ok(bits) || N < 0 || K < 0) return 1;
+    const int64_t wpr = words_per_row(bits, K);
+    const int64_t C = int64_t(1) << bits;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k)
+            Wd[n * K + k] = codebook[n * C + read_field(packed + n * wpr, k, bits)];
+    return 0;
+}
+
+// Round a double to the nearest bf16 (ties to even).  Finite, normal-range
+// inputs only (the synthetic workloads never leave it); NaN/Inf pass through.
+uint16_t oracle_round_bf16(double y) {
+    float f = static_cast<float>(y);
+    uint32_t u;
+    std::memcpy(&u, &f, sizeof u);
+    if (!std::isfinite(f)) return static_cast<uint16_t>(u >> 16);
+    // The two bf16 neighbours that bracket f in magnitude.
+    uint32_t lo = u & 0xFFFF0000u, hi = lo + 0x00010000u;
+    float flo, fhi;
+    std::memcpy(&flo, &lo, sizeof flo);
+    std::memcpy(&fhi, &hi, sizeof fhi);
+    double dlo = std::fabs(y - static_cast<double>(flo));
+    double dhi = std::fabs(y - static_cast<double>(fhi));
+    uint32_t pick;
+    if (dlo < dhi) pick = lo;
+    else if (dhi < dlo) pick = hi;
+    else pick = ((lo >> 16) & 1u) ? hi : lo;   // tie: even mantissa
+    return static_cast<uint16_t>(pick >> 16);
+}
+
+// Rows [n0, n1) of Y = X * W^T.  X is M x K bf16 row-major; Y, A and Ybf16 are
+// M x N row-major and only columns n0..n1-1 are written.  A and Ybf16 may be
+// null.  M = 1 is the matrix-vector product.
+int oracle_gemm(const uint32_t* packed, const uint16_t* codebook, const uint16_t* X,
+                int64_t N, int64_t K, int bits, int64_t M, int64_t n0, int64_t n1,
+                double* Y, double* A, uint16_t* Ybf16) {
+    if (!bits_ok(bits) || N < 0 || K < 0 || M < 0 || n0 < 0 || n1 > N || n0 > n1) return 1;
+    const int64_t wpr = words_per_row(bits, K);
+    const int64_t C = int64_t(1) << bits;
+    std::vector<double> w(static_cast<size_t>(K));
+    for (int64_t n = n0; n < n1; ++n) {
+        for (int64_t k = 0; k < K; ++k)
+            w[k] = bf16_to_double(codebook[n * C + read_field(packed + n * wpr, k, bits)]);
+        for (int64_t m = 0; m < M; ++m) {
+            double y = 0.0, a = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                double t = w[k] * bf16_to_double(X[m * K + k]);
+                y += t;
+                a += std::fabs(t);
+            }
+            Y[m * N + n] = y;
+            if (A) A[m * N + n] = a;
+            if (Ybf16) Ybf16[m * N + n] = oracle_round_bf16(y);
+        }
+    }
+    return 0;
+}
+
+}  // extern "C"
