@@ -1,0 +1,250 @@
+"""Benchmark of the k-means-quantised GEMV hot path on one MI355X.
+
+A step is one call of the whole hot path (index stream load, unpack + codebook
+lookup, multiply-accumulate, K-reduction, bf16 store) on the headline workload
+of the benchmark contract: 2-bit 14336 x 4096 GEMV at batch 1.  Inputs are
+resident in HBM before the timed region.  Calls rotate over enough distinct
+(W, codebook, x, y) instances to exceed the 256 MB last-level cache, and are
+replayed from a HIP graph so that launch overhead from Python is not measured
+(the protocol of the paper's App. E "Micro-benchmarks", adapted to HIP).
+
+Prints ONE JSON line on stdout.  `--table` additionally writes per-shape
+numbers for every contract configuration to gpurun_out/bench_table.json.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak, GB/s
+LLC_BYTES = 256 << 20          # last-level (memory-side) cache
+CALLS_PER_GRAPH = 100
+
+WORKLOADS = {
+    # name: (bits, N, K, M, cfg seed, matrix number, symmetric 1-bit codebook)
+    "cfg2_gateup_b2_14336x4096_m1": (2, 14336, 4096, 1, 2, 0, False),
+    "cfg2_down_b2_4096x14336_m1": (2, 4096, 14336, 1, 2, 1, False),
+    "cfg0_b1_2048x2048_m1": (1, 2048, 2048, 1, 0, 0, True),
+    "cfg1_b4_4096x4096_m1": (4, 4096, 4096, 1, 1, 0, False),
+    "cfg3_b3_4096x4096_m8": (3, 4096, 4096, 8, 3, 0, False),
+    "cfg3_b3_4096x4096_m16": (3, 4096, 4096, 16, 3, 0, False),
+    "cfg3_b3_14336x4096_m8": (3, 14336, 4096, 8, 3, 1, False),
+    "cfg3_b3_14336x4096_m16": (3, 14336, 4096, 16, 3, 1, False),
+    "cfg4_qkv_b1_9216x3072_m1": (1, 9216, 3072, 1, 4, 0, True),
+    "cfg4_o_b1_3072x3072_m1": (1, 3072, 3072, 1, 4, 1, True),
+    "cfg4_gate_b1_8192x3072_m1": (1, 8192, 3072, 1, 4, 2, True),
+    "cfg4_down_b1_3072x8192_m1": (1, 3072, 8192, 1, 4, 4, True),
+    "cfg4_qkv_b1_9216x3072_m4": (1, 9216, 3072, 4, 4, 0, True),
+    "cfg4_qkv_b1_9216x3072_m16": (1, 9216, 3072, 16, 4, 0, True),
+    "cfg4_down_b1_3072x8192_m16": (1, 3072, 8192, 16, 4, 4, True),
+}
+HEADLINE = "cfg2_gateup_b2_14336x4096_m1"
+
+
+def _dev(a):
+    import numpy as np
+    import torch
+    view = {np.dtype(np.uint32): np.int32, np.dtype(np.uint16): np.int16}[a.dtype]
+    return torch.from_numpy(np.ascontiguousarray(a).view(view)).cuda()
+
+
+class Instances:
+    """R rotating device-resident instances of one workload.  Instance 0 follows
+    the seeded recipe exactly (host generator) and is the one checked against the
+    oracle; the others are drawn on the device with the same distributions
+    (uniform index bits, sorted N(0, 0.02) centroids, N(0, 1) activations)."""
+
+    def __init__(self, name, rotate=True):
+        import numpy as np
+        import torch
+
+        from paper_2602_15563_amd import kmq, synth
+        self.name = name
+        self.bits, self.N, self.K, self.M, seed, matrix, sym = WORKLOADS[name]
+        bits, N, K, M = self.bits, self.N, self.K, self.M
+        self.bytes = synth.algorithmic_bytes(N, K, bits, M)
+        self.R = max(2, -(-2 * LLC_BYTES // self.bytes)) if rotate else 1
+        self.R = min(self.R, 2048)
+        self.idx = synth.make_indices(seed, matrix, N, K, bits)
+        self.cb = synth.make_codebook(seed, matrix, N, bits, symmetric=sym)
+        self.X = synth.make_x(seed, matrix, M, K)
+        self.packed = kmq.pack(self.idx, bits)
+        wpr = self.packed.shape[1]
+        g = torch.Generator(device="cuda")
+        g.manual_seed(1234 + seed)
+        self.W, self.C, self.Xd, self.Y = [_dev(self.packed)], [_dev(self.cb)], [_dev(self.X)], []
+        for _ in range(1, self.R):
+            self.W.append(torch.randint(-2**31, 2**31, (N, wpr), dtype=torch.int32, device="cuda", generator=g))
+            if sym:
+                t = (torch.randn(N, device="cuda", generator=g) * 0.02).abs().to(torch.bfloat16)
+                c = torch.stack([-t, t], dim=1)
+            else:
+                c = (torch.randn((N, 1 << bits), device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+                c = torch.sort(c.float(), dim=1).values.to(torch.bfloat16)
+            self.C.append(c.view(torch.int16).contiguous())
+            self.Xd.append(torch.randn((M, K), device="cuda", generator=g).to(torch.bfloat16).view(torch.int16))
+        for _ in range(self.R):
+            self.Y.append(torch.zeros((M, N), dtype=torch.int16, device="cuda"))
+        ws = kmq.workspace_bytes(N, K, bits, M, 0)
+        self.ws = torch.empty(ws, dtype=torch.uint8, device="cuda") if ws else None
+        self.kernel = kmq.kernel_name(N, K, bits, M, 0)
+
+    def call(self, i):
+        from paper_2602_15563_amd import kmq
+        r = i % self.R
+        if self.M == 1:
+            kmq.gemv(self.W[r], self.C[r], self.Xd[r], self.Y[r], self.N, self.K, self.bits, 0, self.ws)
+        else:
+            kmq.gemm_smallbatch(self.W[r], self.C[r], self.Xd[r], self.Y[r], self.N, self.K, self.M,
+                                self.bits, 0, self.ws)
+
+    def check(self):
+        """Instance 0 against the oracle on sampled row blocks; returns max err/A."""
+        import numpy as np
+        import torch
+
+        import oracle
+        from paper_2602_15563_amd import synth
+        self.call(0)
+        torch.cuda.synchronize()
+        yg = synth.bf16_to_f64(self.Y[0].cpu().numpy().view(np.uint16))
+        worst = 0.0
+        rng = np.random.default_rng(0)
+        starts = [0, self.N - 64] + [int(s) for s in rng.integers(0, self.N - 64, size=4)]
+        for n0 in starts:
+            Yo, A, _ = oracle.gemm(self.packed, self.cb, self.X, self.K, self.bits, rows=(n0, n0 + 64))
+            err = np.abs(yg[:, n0:n0 + 64] - Yo[:, n0:n0 + 64])
+            if not np.all(err <= 2e-3 * A[:, n0:n0 + 64]):
+                raise SystemExit(f"bench: {self.name} does not match the oracle in rows {n0}..{n0 + 64}")
+            worst = max(worst, float(np.max(err / np.maximum(A[:, n0:n0 + 64], 1e-300))))
+        return worst
+
+
+def time_workload(inst: Instances, steps: int, warmup: int, use_graph: bool = True):
+    """Returns (seconds for `steps` calls, steps actually timed)."""
+    import torch
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for i in range(max(warmup, 1)):
+            inst.call(i)
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        if use_graph:
+            n_replays = max(1, steps // CALLS_PER_GRAPH)
+            steps = n_replays * CALLS_PER_GRAPH
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for i in range(CALLS_PER_GRAPH):
+                    inst.call(i)
+            graph.replay()                      # untimed first replay
+            stream.synchronize()
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for _ in range(n_replays):
+                graph.replay()
+            e1.record(stream)
+        else:
+            torch.cuda.synchronize()
+            e0.record(stream)
+            for i in range(steps):
+                inst.call(i)
+            e1.record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3, steps
+
+
+def cpu_baseline(inst: Instances):
+    """The oracle, as it stands, single-threaded, on the same matrix."""
+    import oracle
+    best = None
+    n_rows = inst.N
+    oracle.gemm(inst.packed, inst.cb, inst.X, inst.K, inst.bits, rows=(0, min(64, n_rows)))   # warm-up
+    t_total = 0.0
+    runs = 0
+    while runs < 3 or (t_total < 10.0 and runs < 20):
+        t = time.perf_counter()
+        oracle.gemm(inst.packed, inst.cb, inst.X, inst.K, inst.bits)
+        dt = time.perf_counter() - t
+        best = dt if best is None else min(best, dt)
+        t_total += dt
+        runs += 1
+    return {"value": round(inst.bytes / best / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "ms_per_call": round(best * 1e3, 2),
+            "sample": f"the whole {inst.name} matrix ({inst.N}x{inst.K}, batch {inst.M}), best of {runs} calls"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default=HEADLINE, choices=sorted(WORKLOADS))
+    ap.add_argument("--no-graph", action="store_true", help="launch directly instead of replaying a HIP graph")
+    ap.add_argument("--no-rotate", action="store_true", help="reuse one instance (cache-resident, NOT the headline)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--table", action="store_true", help="also time every contract shape -> gpurun_out/bench_table.json")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); "
+                         "the path shards by rows or by K across GPUs but no multi-GPU leg exists here")
+
+    import torch
+
+    from paper_2602_15563_amd import kmq  # noqa: F401  (fails loudly if the HIP library is missing)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    inst = Instances(args.workload, rotate=not args.no_rotate)
+    worst = inst.check()
+    secs, steps = time_workload(inst, args.steps, args.warmup, use_graph=not args.no_graph)
+    us = secs / steps * 1e6
+    gbs = inst.bytes / (secs / steps) / 1e9
+    out = {
+        "metric": "effective HBM GB/s (% of peak) and us/call, 2-bit 14336x4096 GEMV bs=1"
+                  if args.workload == HEADLINE else f"effective HBM GB/s, {args.workload}",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": round(us * 1e-3, 6), "us_per_call": round(us, 3),
+        "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 in/out, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": args.workload, "bits": inst.bits, "N": inst.N, "K": inst.K, "batch": inst.M,
+                   "kernel": inst.kernel, "rotating_instances": inst.R, "hip_graph": not args.no_graph,
+                   "algorithmic_bytes_per_call": inst.bytes, "max_err_over_A_vs_oracle": float(f"{worst:.3e}")},
+        "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "note": "achieved = algorithmic bytes per launch / average launch-to-launch time "
+                             "(HIP events on the launch stream around the timed region)"},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(inst)
+
+    if args.table:
+        rows = []
+        for name in WORKLOADS:
+            it = Instances(name)
+            w = it.check()
+            s, n = time_workload(it, 5000, 100)
+            rows.append({"workload": name, "kernel": it.kernel, "us_per_call": round(s / n * 1e6, 3),
+                         "GBps": round(it.bytes / (s / n) / 1e9, 1),
+                         "pct_peak": round(100 * it.bytes / (s / n) / 1e9 / HBM_PEAK_GBS, 2),
+                         "bytes": it.bytes, "R": it.R, "max_err_over_A": float(f"{w:.3e}")})
+            print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+            del it
+            torch.cuda.empty_cache()
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:
+            json.dump(rows, f, indent=1)
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,134 @@
+/* kmq.h -- C ABI of the k-means-quantised matrix-vector / small-batch matrix
+ * product for AMD MI355X (gfx950).
+ *
+ * The operation is the fused dequantise-multiply of the paper's App. E
+ * ("Benchmarking": Y^T = dequantize(W~) X^T, and the reference routine under
+ * "Kernel implementations"), with dequantisation by centroid lookup as in
+ * Sec. 2.2 ("Nonlinear k-means quantization"), in the benchmark contract's
+ * form: no block scales, one codebook of 2^b bf16 centroids per output row.
+ *
+ *     w[n][k] = codebook[n][ idx[n][k] ]                 (bf16, exact lookup)
+ *     Y[m][n] = sum_k w[n][k] * X[m][k]                  (fp32 accumulation, bf16 out,
+ *                                                         round-to-nearest-even)
+ *
+ * CANONICAL PACKED FORMAT (layout 0).  Row n of W is a little-endian bit
+ * stream: element k occupies stream bits [k*b, k*b+b), stream bit p is bit
+ * (p mod 32) of 32-bit word (p div 32).  For b = 3 a field may straddle two
+ * words.  Every row starts on a fresh word and holds kmq_words_per_row(b, K)
+ * words; pad bits are zero on output of kmq_pack and ignored on input
+ * everywhere.  For b in {1,2,4} the byte view of this stream is the paper's
+ * uint8 element stream `Wq` with an LSB-first byte table.
+ *
+ * General rules.  No function allocates, frees or synchronises.  Device entry
+ * points enqueue on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ * null stream) and return; they are legal under stream capture.  The caller
+ * owns every buffer.  Inputs are never written; outputs are fully overwritten.
+ * The same inputs give bit-identical outputs run to run (no floating-point
+ * atomics).  Every argument is checked before anything is launched; a bad
+ * argument returns an error code and touches nothing.  Nothing throws or aborts.
+ */
+#ifndef KMQ_H
+#define KMQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t kmq_status;
+enum {
+    KMQ_OK = 0,
+    KMQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    KMQ_ERR_BITS = 2,        /* bits not in {1,2,3,4} */
+    KMQ_ERR_SHAPE = 3,       /* N, K < 1, M outside 1..KMQ_MAX_BATCH, or size overflow */
+    KMQ_ERR_ALIGN = 4,       /* pointer alignment (see each function) */
+    KMQ_ERR_INDEX_RANGE = 5, /* kmq_pack: an index >= 2^bits */
+    KMQ_ERR_WORKSPACE = 6,   /* workspace NULL or smaller than kmq_workspace_bytes */
+    KMQ_ERR_LAYOUT = 7,      /* unknown layout id, or layout not valid for this (bits, K) */
+    KMQ_ERR_HIP = 8          /* the HIP runtime refused a launch (hipGetLastError is left set) */
+};
+
+enum {
+    KMQ_LAYOUT_CANONICAL = 0, /* the format above */
+    KMQ_LAYOUT_TILED = 1      /* GPU tile order, see kmq_repack */
+};
+
+#define KMQ_MAX_BATCH 16
+
+/* ceil(K*bits/32): 32-bit words per row of the canonical stream; -1 on bad arguments. */
+int64_t kmq_words_per_row(int bits, int64_t K);
+
+/* Host, offline, integer only.  idx: N*K bytes, one index per element, row-major,
+ * each < 2^bits.  packed: N*kmq_words_per_row words, canonical format, pad bits zero.
+ * Both are host pointers.  KMQ_ERR_INDEX_RANGE leaves `packed` unspecified. */
+kmq_status kmq_pack(const uint8_t* idx, int64_t N, int64_t K, int bits, uint32_t* packed);
+
+/* Inverse of kmq_pack (host pointers).  Pad bits of `packed` are ignored. */
+kmq_status kmq_unpack(const uint32_t* packed, int64_t N, int64_t K, int bits, uint8_t* idx);
+
+/* Host, offline, integer only, reversible: permutes the words of the canonical
+ * stream into the tile order named by `layout` (same number of words in and
+ * out; kmq_unrepack(kmq_repack(P)) == P with pad bits as given).  Motivated by
+ * the paper's remark (App. E, "Micro-benchmarks: Results") that custom code with
+ * an optimised data layout is the route to faster low-bit kernels.
+ *
+ * KMQ_LAYOUT_TILED: rows are grouped in blocks of 16 (the last block may be
+ * short); inside a block the words are stored column-block by column-block, a
+ * column block being 4 consecutive words (16 bytes) of one row:
+ *     tiled[ (rb*wpr4 + cb) * 16*4 + r*4 + j ] = canonical[ (rb*16 + r)*wpr + cb*4 + j ]
+ * with wpr4 = wpr/4; requires wpr % 4 == 0 (else KMQ_ERR_LAYOUT).  A short
+ * last block keeps the stride 16 (unused slots are zero), so `tiled` holds
+ * ceil(N/16)*16*wpr words: size it with kmq_tiled_words(). */
+kmq_status kmq_repack(const uint32_t* canonical, int64_t N, int64_t K, int bits, int layout,
+                      uint32_t* tiled);
+kmq_status kmq_unrepack(const uint32_t* tiled, int64_t N, int64_t K, int bits, int layout,
+                        uint32_t* canonical);
+/* Number of 32-bit words of W in `layout` (canonical: N*wpr); -1 on bad arguments. */
+int64_t kmq_tiled_words(int64_t N, int64_t K, int bits, int layout);
+
+/* Bytes of device workspace kmq_gemv / kmq_gemm_smallbatch need for this
+ * problem (split-K partial sums; 0 when the chosen kernel needs none).
+ * Returns 0 on bad arguments (the compute call then reports the error). */
+size_t kmq_workspace_bytes(int64_t N, int64_t K, int bits, int M, int layout);
+
+/* y = W x.  All pointers are DEVICE pointers.
+ *   W        packed indices in `layout` (16-byte aligned)
+ *   codebook N x 2^bits bf16 bit patterns, row-major (4-byte aligned)
+ *   x        K bf16 (16-byte aligned)
+ *   y        N bf16, overwritten (2-byte aligned)
+ *   workspace, workspace_bytes  >= kmq_workspace_bytes(N,K,bits,1,layout); may be NULL/0 if that is 0
+ * Equivalent to kmq_gemm_smallbatch with M = 1. */
+kmq_status kmq_gemv(const uint32_t* W, const uint16_t* codebook, const uint16_t* x, uint16_t* y,
+                    int64_t N, int64_t K, int bits, int layout,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Y = X W^T for 1 <= M <= KMQ_MAX_BATCH (paper App. D/E: the small-batch,
+ * memory-bound regime; larger batches are better served by kmq_dequant plus a
+ * dense GEMM, App. E "Model benchmarks").  X is M x K bf16 row-major (16-byte
+ * aligned), Y is M x N bf16 row-major, overwritten.  Other arguments as kmq_gemv. */
+kmq_status kmq_gemm_smallbatch(const uint32_t* W, const uint16_t* codebook, const uint16_t* X,
+                               uint16_t* Y, int64_t N, int64_t K, int M, int bits, int layout,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Wdense[n][k] = codebook[n][idx[n][k]] as bf16 bit patterns, N x K row-major,
+ * bit-exact (device pointers).  The separate-dequantise route the paper
+ * suggests for large batches (App. E "Model benchmarks"), and the bit-exactness probe. */
+kmq_status kmq_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wdense,
+                       int64_t N, int64_t K, int bits, int layout, void* hip_stream);
+
+/* Name of the kernel variant the launch heuristic picks for this problem
+ * (static string, never NULL; "invalid" on bad arguments).  For reports. */
+const char* kmq_kernel_name(int64_t N, int64_t K, int bits, int M, int layout);
+
+const char* kmq_status_string(kmq_status s);
+
+/* Text the HIP runtime gave for the last KMQ_ERR_HIP on the calling thread
+ * (static string, "" if there was none). */
+const char* kmq_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KMQ_H */

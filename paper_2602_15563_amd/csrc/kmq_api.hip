@@ -1,0 +1,97 @@
+// C-ABI entry points of the device path: argument checks, launch-shape
+// heuristic, dispatch.  Contract: include/kmq.h.
+#include <hip/hip_runtime.h>
+
+#include "kmq.h"
+#include "kmq_internal.h"
+#include "kmq_launch.h"
+
+namespace kmq {
+
+// Launch-shape heuristic (the paper autotunes chunk shapes per problem, App. E
+// "Kernel implementations"; here the choice is a static function of the shape).
+Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout) {
+    Plan p{kVariantInvalid, -1, 0, "invalid"};
+    if (!bits_valid(bits) || !dims_valid(N, K) || M < 1 || M > KMQ_MAX_BATCH) return p;
+    if (layout != KMQ_LAYOUT_CANONICAL && layout != KMQ_LAYOUT_TILED) return p;
+    if (layout == KMQ_LAYOUT_TILED && words_per_row(bits, K) % kTileColWords) return p;
+    if (M == 1) {
+        const int i = rowsplit_find(K, bits, layout);
+        if (i >= 0) return Plan{kVariantRowsplit, i, 0, rowsplit_name(i)};
+    }
+    return Plan{kVariantGeneric, -1, 0, "generic"};
+}
+
+// Text of the last HIP error a launch reported on this thread ("" if none).
+static thread_local const char* g_last_hip_error = "";
+
+static kmq_status hip_status(hipError_t e) {
+    if (e == hipSuccess) return KMQ_OK;
+    g_last_hip_error = hipGetErrorString(e);
+    return KMQ_ERR_HIP;
+}
+
+static bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+static kmq_status check_and_run(const GemmArgs& a, void* stream) {
+    if (!a.W || !a.codebook || !a.X || !a.Y) return KMQ_ERR_NULL;
+    if (!bits_valid(a.bits)) return KMQ_ERR_BITS;
+    if (!dims_valid(a.N, a.K) || a.M < 1 || a.M > KMQ_MAX_BATCH) return KMQ_ERR_SHAPE;
+    if (a.layout != KMQ_LAYOUT_CANONICAL && a.layout != KMQ_LAYOUT_TILED) return KMQ_ERR_LAYOUT;
+    if (a.layout == KMQ_LAYOUT_TILED && words_per_row(a.bits, a.K) % kTileColWords) return KMQ_ERR_LAYOUT;
+    if (!aligned(a.W, 16) || !aligned(a.X, 16) || !aligned(a.codebook, 4) || !aligned(a.Y, 2)) return KMQ_ERR_ALIGN;
+    const Plan plan = make_plan(a.N, a.K, a.bits, a.M, a.layout);
+    if (plan.variant == kVariantInvalid) return KMQ_ERR_SHAPE;
+    if (plan.workspace_bytes > 0 && (!a.workspace || a.workspace_bytes < plan.workspace_bytes)) return KMQ_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipSuccess;
+    switch (plan.variant) {
+        case kVariantRowsplit: e = launch_rowsplit(plan.table_index, a, s); break;
+        default: e = launch_generic(a, s); break;
+    }
+    return hip_status(e);
+}
+
+}  // namespace kmq
+
+extern "C" {
+
+size_t kmq_workspace_bytes(int64_t N, int64_t K, int bits, int M, int layout) {
+    return kmq::make_plan(N, K, bits, M, layout).workspace_bytes;
+}
+
+const char* kmq_kernel_name(int64_t N, int64_t K, int bits, int M, int layout) {
+    return kmq::make_plan(N, K, bits, M, layout).name;
+}
+
+kmq_status kmq_gemm_smallbatch(const uint32_t* W, const uint16_t* codebook, const uint16_t* X,
+                               uint16_t* Y, int64_t N, int64_t K, int M, int bits, int layout,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const kmq::GemmArgs a{W, codebook, X, Y, N, K, M, bits, layout, workspace, workspace_bytes};
+    return kmq::check_and_run(a, hip_stream);
+}
+
+kmq_status kmq_gemv(const uint32_t* W, const uint16_t* codebook, const uint16_t* x, uint16_t* y,
+                    int64_t N, int64_t K, int bits, int layout,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const kmq::GemmArgs a{W, codebook, x, y, N, K, 1, bits, layout, workspace, workspace_bytes};
+    return kmq::check_and_run(a, hip_stream);
+}
+
+kmq_status kmq_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wdense,
+                       int64_t N, int64_t K, int bits, int layout, void* hip_stream) {
+    if (!W || !codebook || !Wdense) return KMQ_ERR_NULL;
+    if (!kmq::bits_valid(bits)) return KMQ_ERR_BITS;
+    if (!kmq::dims_valid(N, K)) return KMQ_ERR_SHAPE;
+    if (layout != KMQ_LAYOUT_CANONICAL && layout != KMQ_LAYOUT_TILED) return KMQ_ERR_LAYOUT;
+    if (layout == KMQ_LAYOUT_TILED && kmq::words_per_row(bits, K) % kmq::kTileColWords) return KMQ_ERR_LAYOUT;
+    if ((reinterpret_cast<uintptr_t>(W) & 15) || (reinterpret_cast<uintptr_t>(codebook) & 3) ||
+        (reinterpret_cast<uintptr_t>(Wdense) & 1)) return KMQ_ERR_ALIGN;
+    const hipError_t e = kmq::launch_dequant(W, codebook, Wdense, N, K, bits, layout,
+                                             static_cast<hipStream_t>(hip_stream));
+    return kmq::hip_status(e);
+}
+
+const char* kmq_last_hip_error(void) { return kmq::g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,165 @@
+// Shape-agnostic kernels: any K >= 1, any bit-width, both layouts, batch 1..16.
+// They are the fallback behind the shape-specialised kernels and the
+// bit-exact dequantiser.  Operation: paper App. E, "Kernel implementations"
+// (lookup, then multiply-accumulate), per-row codebooks, fp32 accumulation.
+#include "kmq_device.h"
+#include "kmq_launch.h"
+
+namespace kmq {
+
+// b-bit field `e` (0..31) of a 32-element group held in BITS consecutive words.
+template <int BITS>
+__device__ __forceinline__ uint32_t group_field(const uint32_t (&w)[BITS], int e) {
+    constexpr uint32_t mask = (1u << BITS) - 1u;
+    const int p = e * BITS;               // bit position inside the group
+    const int wi = p >> 5, sh = p & 31;
+    uint32_t v = w[wi] >> sh;
+    if constexpr (BITS == 3) {
+        if (sh > 29) v |= w[wi + 1] << (32 - sh);   // field straddles two words
+    }
+    return v & mask;
+}
+
+// One wave per output row, four rows per workgroup.  Each lane walks over
+// 32-element groups (BITS words each, so groups start on a word boundary for
+// every bit-width), looks weights up in the row's codebook (fp32 copy in LDS)
+// and accumulates MT batch columns.
+template <int BITS, int MT>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(
+    const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
+    const uint16_t* __restrict__ X, uint16_t* __restrict__ Y,
+    int64_t N, int64_t K, int M, int layout) {
+    constexpr int C = 1 << BITS;
+    __shared__ float lut[4][C];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t n = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+    const bool live = n < N;
+    if (live && lane < C) lut[wave][lane] = bf16_to_f32(codebook[n * C + lane]);
+    __syncthreads();
+    if (!live) return;
+
+    const int64_t wpr = words_per_row(BITS, K);
+    const int64_t ngroups = (K + 31) >> 5;
+    const bool vec_x = (K & 7) == 0;      // rows of X start 16-byte aligned
+    float acc[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) acc[m] = 0.f;
+
+    for (int64_t g = lane; g < ngroups; g += kWave) {
+        uint32_t w[BITS];
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) {
+            const int64_t wi = g * BITS + j;
+            w[j] = wi < wpr ? W[word_index(layout, n, wi, wpr)] : 0u;
+        }
+        const int64_t k0 = g << 5;
+        const bool full = k0 + 32 <= K;
+        float wt[32];
+#pragma unroll
+        for (int e = 0; e < 32; ++e) wt[e] = lut[wave][group_field<BITS>(w, e)];
+        if (full && vec_x) {
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                if (m < M) {
+                    const u32x4_t* xp = reinterpret_cast<const u32x4_t*>(X + m * K + k0);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const u32x4_t xv = xp[q];
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            acc[m] = fmaf(wt[q * 8 + t * 2], __uint_as_float(xv[t] << 16), acc[m]);
+                            acc[m] = fmaf(wt[q * 8 + t * 2 + 1], __uint_as_float(xv[t] & 0xFFFF0000u), acc[m]);
+                        }
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 32; ++e) {
+                if (k0 + e < K) {
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+                        if (m < M) acc[m] = fmaf(wt[e], bf16_to_f32(X[m * K + k0 + e]), acc[m]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const float s = group_sum<64>(acc[m]);
+        if (lane == 63 && m < M) Y[static_cast<int64_t>(m) * N + n] = f32_to_bf16(s);
+    }
+}
+
+// One thread per (row, 32-element group): Wdense[n][k] = codebook[n][idx[n][k]].
+template <int BITS>
+__global__ __launch_bounds__(256) void dequant_kernel(
+    const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
+    uint16_t* __restrict__ Wd, int64_t N, int64_t K, int layout) {
+    constexpr int C = 1 << BITS;
+    const int64_t wpr = words_per_row(BITS, K);
+    const int64_t ngroups = (K + 31) >> 5;
+    const int64_t total = N * ngroups;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < total;
+         i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+        const int64_t n = i / ngroups, g = i % ngroups;
+        uint32_t w[BITS];
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) {
+            const int64_t wi = g * BITS + j;
+            w[j] = wi < wpr ? W[word_index(layout, n, wi, wpr)] : 0u;
+        }
+        uint16_t c[C];
+#pragma unroll
+        for (int j = 0; j < C; ++j) c[j] = codebook[n * C + j];
+        const int64_t k0 = g << 5;
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {
+            const uint32_t f = group_field<BITS>(w, e);
+            uint16_t v = c[0];
+#pragma unroll
+            for (int j = 1; j < C; ++j) v = f == static_cast<uint32_t>(j) ? c[j] : v;
+            if (k0 + e < K) Wd[n * K + k0 + e] = v;
+        }
+    }
+}
+
+template <int BITS>
+static hipError_t launch_generic_bits(const GemmArgs& a, hipStream_t s) {
+    const dim3 grid(static_cast<unsigned>((a.N + 3) / 4)), block(256);
+    if (a.M == 1)
+        hipLaunchKernelGGL((gemm_generic_kernel<BITS, 1>), grid, block, 0, s, a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.layout);
+    else if (a.M <= 4)
+        hipLaunchKernelGGL((gemm_generic_kernel<BITS, 4>), grid, block, 0, s, a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.layout);
+    else if (a.M <= 8)
+        hipLaunchKernelGGL((gemm_generic_kernel<BITS, 8>), grid, block, 0, s, a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.layout);
+    else
+        hipLaunchKernelGGL((gemm_generic_kernel<BITS, 16>), grid, block, 0, s, a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.layout);
+    return hipGetLastError();
+}
+
+hipError_t launch_generic(const GemmArgs& a, hipStream_t s) {
+    switch (a.bits) {
+        case 1: return launch_generic_bits<1>(a, s);
+        case 2: return launch_generic_bits<2>(a, s);
+        case 3: return launch_generic_bits<3>(a, s);
+        default: return launch_generic_bits<4>(a, s);
+    }
+}
+
+hipError_t launch_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd, int64_t N,
+                          int64_t K, int bits, int layout, hipStream_t s) {
+    const int64_t total = N * ((K + 31) >> 5);
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    const dim3 grid(static_cast<unsigned>(blocks)), block(256);
+    switch (bits) {
+        case 1: hipLaunchKernelGGL(dequant_kernel<1>, grid, block, 0, s, W, codebook, Wd, N, K, layout); break;
+        case 2: hipLaunchKernelGGL(dequant_kernel<2>, grid, block, 0, s, W, codebook, Wd, N, K, layout); break;
+        case 3: hipLaunchKernelGGL(dequant_kernel<3>, grid, block, 0, s, W, codebook, Wd, N, K, layout); break;
+        default: hipLaunchKernelGGL(dequant_kernel<4>, grid, block, 0, s, W, codebook, Wd, N, K, layout); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace kmq

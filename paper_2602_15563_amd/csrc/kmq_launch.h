@@ -1,0 +1,50 @@
+// Internal launch interface between the C-ABI layer and the kernel files.
+#ifndef KMQ_LAUNCH_H
+#define KMQ_LAUNCH_H
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+
+namespace kmq {
+
+struct GemmArgs {
+    const uint32_t* W;
+    const uint16_t* codebook;
+    const uint16_t* X;
+    uint16_t* Y;
+    int64_t N, K;
+    int M, bits, layout;
+    void* workspace;
+    size_t workspace_bytes;
+};
+
+// Kernel variants the heuristic can pick (kmq_kernel_name reports them).
+enum Variant {
+    kVariantInvalid = 0,
+    kVariantGeneric,     // any shape: wave per row, fp32 codebook in LDS
+    kVariantRowsplit,    // batch 1, K from a table: x in registers, LUT in LDS, dot2
+};
+
+struct Plan {
+    Variant variant;
+    int table_index;         // which specialisation (variant-specific), -1 if none
+    size_t workspace_bytes;  // device workspace this plan needs
+    const char* name;
+};
+
+Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout);
+
+hipError_t launch_generic(const GemmArgs& a, hipStream_t s);
+hipError_t launch_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd, int64_t N,
+                          int64_t K, int bits, int layout, hipStream_t s);
+
+// Rowsplit specialisations: -1 if (bits, K, layout) has none.
+int rowsplit_find(int64_t K, int bits, int layout);
+const char* rowsplit_name(int table_index);
+hipError_t launch_rowsplit(int table_index, const GemmArgs& a, hipStream_t s);
+
+}  // namespace kmq
+
+#endif

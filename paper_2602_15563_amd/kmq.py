@@ -1,0 +1,177 @@
+"""Thin binding over the C-ABI library (include/kmq.h): argument marshalling
+only.  Host functions take numpy arrays; device functions take torch tensors
+that already live on the GPU and enqueue on torch's current stream.  There is
+no fallback: if libkmq.so is missing, importing this module fails."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkmq.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2602_15563_amd.build`")
+
+
+def _preload_torch_hip_runtime():
+    """PyTorch's ROCm wheel bundles its own HIP runtime (same soname as the
+    system one).  Streams and device pointers handed to libkmq.so come from
+    that runtime, so it must be the one libkmq.so binds to: load it first, and
+    the dynamic loader resolves libkmq.so's dependency to it by soname."""
+    import importlib.util
+    spec = importlib.util.find_spec("torch")
+    if spec is None or not spec.submodule_search_locations:
+        return
+    cand = os.path.join(list(spec.submodule_search_locations)[0], "lib", "libamdhip64.so")
+    if os.path.exists(cand):
+        ctypes.CDLL(cand, mode=ctypes.RTLD_GLOBAL)
+
+
+_preload_torch_hip_runtime()
+_lib = ctypes.CDLL(LIB_PATH)
+
+OK = 0
+LAYOUT_CANONICAL, LAYOUT_TILED = 0, 1
+MAX_BATCH = 16
+
+_i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+_lib.kmq_words_per_row.restype = _i64
+_lib.kmq_words_per_row.argtypes = [_int, _i64]
+_lib.kmq_pack.restype = ctypes.c_int32
+_lib.kmq_pack.argtypes = [_vp, _i64, _i64, _int, _vp]
+_lib.kmq_unpack.restype = ctypes.c_int32
+_lib.kmq_unpack.argtypes = [_vp, _i64, _i64, _int, _vp]
+_lib.kmq_repack.restype = ctypes.c_int32
+_lib.kmq_repack.argtypes = [_vp, _i64, _i64, _int, _int, _vp]
+_lib.kmq_unrepack.restype = ctypes.c_int32
+_lib.kmq_unrepack.argtypes = [_vp, _i64, _i64, _int, _int, _vp]
+_lib.kmq_tiled_words.restype = _i64
+_lib.kmq_tiled_words.argtypes = [_i64, _i64, _int, _int]
+_lib.kmq_workspace_bytes.restype = _sz
+_lib.kmq_workspace_bytes.argtypes = [_i64, _i64, _int, _int, _int]
+_lib.kmq_gemv.restype = ctypes.c_int32
+_lib.kmq_gemv.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _vp, _sz, _vp]
+_lib.kmq_gemm_smallbatch.restype = ctypes.c_int32
+_lib.kmq_gemm_smallbatch.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp, _sz, _vp]
+_lib.kmq_dequant.restype = ctypes.c_int32
+_lib.kmq_dequant.argtypes = [_vp, _vp, _vp, _i64, _i64, _int, _int, _vp]
+_lib.kmq_kernel_name.restype = ctypes.c_char_p
+_lib.kmq_kernel_name.argtypes = [_i64, _i64, _int, _int, _int]
+_lib.kmq_last_hip_error.restype = ctypes.c_char_p
+_lib.kmq_last_hip_error.argtypes = []
+_lib.kmq_status_string.restype = ctypes.c_char_p
+_lib.kmq_status_string.argtypes = [ctypes.c_int32]
+
+
+class KmqError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = int(status)
+        detail = f" ({_lib.kmq_last_hip_error().decode()})" if self.status == 8 else ""
+        super().__init__(f"kmq status {status}: {status_string(status)}{detail}")
+
+
+def raw():
+    """The ctypes library object (for tests that call the C ABI directly)."""
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return _lib.kmq_status_string(int(status)).decode()
+
+
+def _check(status: int):
+    if status != OK:
+        raise KmqError(status)
+
+
+def _np(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _npp(a):
+    return a.ctypes.data_as(_vp)
+
+
+def words_per_row(bits: int, K: int) -> int:
+    return int(_lib.kmq_words_per_row(bits, K))
+
+
+def tiled_words(N: int, K: int, bits: int, layout: int) -> int:
+    return int(_lib.kmq_tiled_words(N, K, bits, layout))
+
+
+def pack(idx: np.ndarray, bits: int) -> np.ndarray:
+    idx = _np(idx, np.uint8)
+    N, K = idx.shape
+    wpr = words_per_row(bits, K)
+    if wpr < 0:
+        raise KmqError(2 if not 1 <= bits <= 4 else 3)
+    out = np.empty((N, wpr), dtype=np.uint32)
+    _check(_lib.kmq_pack(_npp(idx), N, K, bits, _npp(out)))
+    return out
+
+
+def unpack(packed: np.ndarray, K: int, bits: int) -> np.ndarray:
+    packed = _np(packed, np.uint32)
+    N = packed.shape[0]
+    out = np.empty((N, K), dtype=np.uint8)
+    _check(_lib.kmq_unpack(_npp(packed), N, K, bits, _npp(out)))
+    return out
+
+
+def repack(canonical: np.ndarray, K: int, bits: int, layout: int) -> np.ndarray:
+    canonical = _np(canonical, np.uint32)
+    N = canonical.shape[0]
+    n = tiled_words(N, K, bits, layout)
+    if n < 0:
+        raise KmqError(7)
+    out = np.empty(n, dtype=np.uint32)
+    _check(_lib.kmq_repack(_npp(canonical), N, K, bits, layout, _npp(out)))
+    return out
+
+
+def unrepack(tiled: np.ndarray, N: int, K: int, bits: int, layout: int) -> np.ndarray:
+    tiled = _np(tiled, np.uint32)
+    out = np.empty((N, words_per_row(bits, K)), dtype=np.uint32)
+    _check(_lib.kmq_unrepack(_npp(tiled), N, K, bits, layout, _npp(out)))
+    return out
+
+
+def workspace_bytes(N: int, K: int, bits: int, M: int, layout: int = 0) -> int:
+    return int(_lib.kmq_workspace_bytes(N, K, bits, M, layout))
+
+
+def kernel_name(N: int, K: int, bits: int, M: int, layout: int = 0) -> str:
+    return _lib.kmq_kernel_name(N, K, bits, M, layout).decode()
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def gemv(W, codebook, x, y, N: int, K: int, bits: int, layout: int = 0, workspace=None):
+    """y[N] = W x on torch's current stream.  All tensors are device tensors
+    (W int32/uint32 words, codebook/x/y int16 or bfloat16 storage)."""
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(_lib.kmq_gemv(_ptr(W), _ptr(codebook), _ptr(x), _ptr(y), N, K, bits, layout,
+                         _ptr(workspace), ws_bytes, _stream()))
+
+
+def gemm_smallbatch(W, codebook, X, Y, N: int, K: int, M: int, bits: int, layout: int = 0, workspace=None):
+    """Y[M][N] = X[M][K] W^T on torch's current stream."""
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(_lib.kmq_gemm_smallbatch(_ptr(W), _ptr(codebook), _ptr(X), _ptr(Y), N, K, M, bits, layout,
+                                    _ptr(workspace), ws_bytes, _stream()))
+
+
+def dequant(W, codebook, Wdense, N: int, K: int, bits: int, layout: int = 0):
+    """Wdense[N][K] (bf16 storage) = codebook[n][idx[n][k]] on torch's current stream."""
+    _check(_lib.kmq_dequant(_ptr(W), _ptr(codebook), _ptr(Wdense), N, K, bits, layout, _stream()))
