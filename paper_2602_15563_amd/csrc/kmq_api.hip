@@ -16,6 +16,8 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout) {
     if (layout != KMQ_LAYOUT_CANONICAL && layout != KMQ_LAYOUT_TILED) return p;
     if (layout == KMQ_LAYOUT_TILED && words_per_row(bits, K) % kTileColWords) return p;
     if (M == 1) {
+        const int l = lut_find(K, bits, layout);
+        if (l >= 0) return Plan{kVariantLut, l, 0, lut_name(l)};
         const int i = rowsplit_find(K, bits, layout);
         if (i >= 0) return Plan{kVariantRowsplit, i, 0, rowsplit_name(i)};
     }
@@ -46,6 +48,7 @@ static kmq_status check_and_run(const GemmArgs& a, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
     switch (plan.variant) {
+        case kVariantLut: e = launch_lut_entry(plan.table_index, a, s); break;
         case kVariantRowsplit: e = launch_rowsplit(plan.table_index, a, s); break;
         default: e = launch_generic(a, s); break;
     }

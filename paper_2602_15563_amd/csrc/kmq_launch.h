@@ -24,7 +24,8 @@ struct GemmArgs {
 enum Variant {
     kVariantInvalid = 0,
     kVariantGeneric,     // any shape: wave per row, fp32 codebook in LDS
-    kVariantRowsplit,    // batch 1, K from a table: x in registers, LUT in LDS, dot2
+    kVariantRowsplit,    // batch 1, K from a table: x in registers, LUT in LDS (compiler-scheduled; 3-bit)
+    kVariantLut,         // batch 1, 1/2/4-bit, K from a table: hand-scheduled LDS-table kernel
 };
 
 struct Plan {
@@ -44,6 +45,11 @@ hipError_t launch_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t*
 int rowsplit_find(int64_t K, int bits, int layout);
 const char* rowsplit_name(int table_index);
 hipError_t launch_rowsplit(int table_index, const GemmArgs& a, hipStream_t s);
+
+// Hand-scheduled table kernels (1/2/4-bit): -1 if (bits, K, layout) has none.
+int lut_find(int64_t K, int bits, int layout);
+const char* lut_name(int table_index);
+hipError_t launch_lut_entry(int table_index, const GemmArgs& a, hipStream_t s);
 
 }  // namespace kmq
 

@@ -1,0 +1,498 @@
+// Batch-1 kernels specialised on (bits, K), canonical layout: y = W x with
+// w = codebook lookup (paper App. E, "Kernel implementations"; batch 1 is the
+// memory-bound regime of App. D).
+//
+// Work split.  A row is cut into NWK slices along K, one per wave; inside a
+// slice LPR lanes each own G consecutive words (EL = G*32/bits elements), so the
+// index stream is read once with one contiguous vector load per lane and
+// (row, slice).  With LPR < 64 a wave covers RPL = 64/LPR rows per load.  A
+// workgroup is NWK x NWR waves and owns NWR*RPL*RS consecutive rows.  Every
+// wave issues all of its index loads before it uses any of them.
+//
+// Operands on chip.  The activations a lane needs stay in VGPRs for all of its
+// rows; the workgroup stages x through LDS once so that global reads of x are
+// coalesced.  Weights come from 16-entry tables in LDS, which are conflict-free
+// because the lanes of a row read one 64- or 128-byte table:
+//   2-bit  per-row table: nibble (two indices) -> two bf16 weights, one
+//          v_dot2c_f32_bf16 against a packed pair of activations per lookup;
+//   4-bit  per-row table: index -> centroid as fp32, one FMA per lookup;
+//   1-bit  one row-independent table: nibble -> four bf16 {0,1} masks (8 bytes);
+//          the kernel accumulates S1 = sum_{idx=1} x and finishes with the
+//          two-centroid closed form y = c0*sum(x) + (c1 - c0)*S1.
+//
+// Inner loop.  The table address of a lookup is 4*nibble (8*nibble for 1-bit)
+// plus the table base.  Rotating the word by +-2 (+3/-1) bits puts the even/odd
+// nibbles at bits 2..5 (3..6) of every byte, and one SDWA byte-select AND then
+// produces the address byte; it writes only byte 0 of a register whose upper
+// bytes hold the 256-byte-aligned table base, so there is no add.  Eight
+// addresses and eight LDS reads are issued per word, about one word ahead of the
+// multiply-accumulates that consume them (in two groups of four, so that no more
+// than 12 LDS reads are ever outstanding).  These blocks are inline assembly
+// with explicit s_waitcnt lgkmcnt(), because the compiler cannot see LDS reads
+// issued from assembly and its own schedule exposed the LDS latency.
+//
+// K-reduction: DPP adds inside the LPR-lane group, then across the NWK slices
+// through LDS; fp32 -> bf16 round-to-nearest-even; one coalesced store per
+// workgroup.
+#include <type_traits>
+
+#include "kmq_device.h"
+#include "kmq_launch.h"
+
+namespace kmq {
+
+typedef __attribute__((address_space(3))) const uint32_t lds_cu32_t;
+
+// ---- hand-scheduled blocks -----------------------------------------------------
+// `a` holds eight address registers whose bytes 1..3 are the table base.
+
+// The LGKM counter of a wave has 4 bits: at most 15 LDS/scalar-memory operations
+// may be outstanding, or s_waitcnt lgkmcnt(n) stops meaning what it says.  The
+// pipeline below therefore issues lookups in groups of four and never has more
+// than 12 in flight.
+
+// 2-bit / 4-bit: four 4-byte lookups, nibbles 4H..4H+3 of `word` (H = 0, 1), into
+// v[4H..4H+3]; v[2i] belongs to nibble 2i (even).  re/ro are the rotated words,
+// produced when H == 0 and reused when H == 1.
+template <int OFF, int H>
+__device__ __forceinline__ void issue4_b32(uint32_t word, uint32_t& re, uint32_t& ro, uint32_t (&a)[8],
+                                           uint32_t (&v)[8], uint32_t mask) {
+    if constexpr (H == 0) {
+        asm volatile(
+            "v_alignbit_b32 %4, %10, %10, 30\n\t"
+            "v_alignbit_b32 %5, %10, %10, 2\n\t"
+            "v_and_b32_sdwa %6, %4, %11 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_0 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %7, %5, %11 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_0 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %8, %4, %11 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_1 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %9, %5, %11 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_1 src1_sel:DWORD\n\t"
+            "ds_read_b32 %0, %6 offset:%c12\n\t"
+            "ds_read_b32 %1, %7 offset:%c12\n\t"
+            "ds_read_b32 %2, %8 offset:%c12\n\t"
+            "ds_read_b32 %3, %9 offset:%c12"
+            : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(re), "=&v"(ro),
+              "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3])
+            : "v"(word), "v"(mask), "n"(OFF));
+    } else {
+        asm volatile(
+            "v_and_b32_sdwa %4, %8, %10 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_2 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %5, %9, %10 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_2 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %6, %8, %10 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_3 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %7, %9, %10 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_3 src1_sel:DWORD\n\t"
+            "ds_read_b32 %0, %4 offset:%c11\n\t"
+            "ds_read_b32 %1, %5 offset:%c11\n\t"
+            "ds_read_b32 %2, %6 offset:%c11\n\t"
+            "ds_read_b32 %3, %7 offset:%c11"
+            : "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7]),
+              "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+            : "v"(re), "v"(ro), "v"(mask), "n"(OFF));
+    }
+}
+
+// 2-bit: eight dot2 (two accumulator chains).  PENDING = LDS reads issued after
+// the eight this block consumes.
+template <int PENDING>
+__device__ __forceinline__ void consume8_dot2(const uint32_t (&v)[8], const uint32_t* xr, float& a0, float& a1) {
+    asm volatile(
+        "s_waitcnt lgkmcnt(%c18)\n\t"
+        "v_dot2c_f32_bf16 %0, %2, %10\n\t"
+        "v_dot2c_f32_bf16 %1, %3, %11\n\t"
+        "v_dot2c_f32_bf16 %0, %4, %12\n\t"
+        "v_dot2c_f32_bf16 %1, %5, %13\n\t"
+        "v_dot2c_f32_bf16 %0, %6, %14\n\t"
+        "v_dot2c_f32_bf16 %1, %7, %15\n\t"
+        "v_dot2c_f32_bf16 %0, %8, %16\n\t"
+        "v_dot2c_f32_bf16 %1, %9, %17"
+        : "+v"(a0), "+v"(a1)
+        : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7]),
+          "v"(xr[0]), "v"(xr[1]), "v"(xr[2]), "v"(xr[3]), "v"(xr[4]), "v"(xr[5]), "v"(xr[6]), "v"(xr[7]),
+          "n"(PENDING));
+}
+
+// 4-bit: eight FMAs, weights and activations as fp32.
+template <int PENDING>
+__device__ __forceinline__ void consume8_fma(const uint32_t (&v)[8], const uint32_t* xr, float& a0, float& a1) {
+    asm volatile(
+        "s_waitcnt lgkmcnt(%c18)\n\t"
+        "v_fmac_f32 %0, %2, %10\n\t"
+        "v_fmac_f32 %1, %3, %11\n\t"
+        "v_fmac_f32 %0, %4, %12\n\t"
+        "v_fmac_f32 %1, %5, %13\n\t"
+        "v_fmac_f32 %0, %6, %14\n\t"
+        "v_fmac_f32 %1, %7, %15\n\t"
+        "v_fmac_f32 %0, %8, %16\n\t"
+        "v_fmac_f32 %1, %9, %17"
+        : "+v"(a0), "+v"(a1)
+        : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7]),
+          "v"(xr[0]), "v"(xr[1]), "v"(xr[2]), "v"(xr[3]), "v"(xr[4]), "v"(xr[5]), "v"(xr[6]), "v"(xr[7]),
+          "n"(PENDING));
+}
+
+// 1-bit: four 8-byte lookups for nibbles 4H..4H+3 of `word` (H = 0, 1); each
+// returns four bf16 {0,1} masks.  re/ro are the rotated words, produced when
+// H == 0 and reused when H == 1.  vv[2i] belongs to the even nibble.
+template <int H>
+__device__ __forceinline__ void issue4_b64(uint32_t word, uint32_t& re, uint32_t& ro, uint32_t (&a)[8],
+                                           u32x2_t (&vv)[4], uint32_t mask) {
+    if constexpr (H == 0) {
+        asm volatile(
+            "v_alignbit_b32 %4, %10, %10, 29\n\t"
+            "v_alignbit_b32 %5, %10, %10, 1\n\t"
+            "v_and_b32_sdwa %6, %4, %11 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_0 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %7, %5, %11 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_0 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %8, %4, %11 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_1 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %9, %5, %11 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_1 src1_sel:DWORD\n\t"
+            "ds_read_b64 %0, %6\n\t"
+            "ds_read_b64 %1, %7\n\t"
+            "ds_read_b64 %2, %8\n\t"
+            "ds_read_b64 %3, %9"
+            : "=&v"(vv[0]), "=&v"(vv[1]), "=&v"(vv[2]), "=&v"(vv[3]), "=&v"(re), "=&v"(ro),
+              "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3])
+            : "v"(word), "v"(mask));
+    } else {
+        asm volatile(
+            "v_and_b32_sdwa %4, %8, %10 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_2 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %5, %9, %10 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_2 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %6, %8, %10 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_3 src1_sel:DWORD\n\t"
+            "v_and_b32_sdwa %7, %9, %10 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_3 src1_sel:DWORD\n\t"
+            "ds_read_b64 %0, %4\n\t"
+            "ds_read_b64 %1, %5\n\t"
+            "ds_read_b64 %2, %6\n\t"
+            "ds_read_b64 %3, %7"
+            : "=&v"(vv[0]), "=&v"(vv[1]), "=&v"(vv[2]), "=&v"(vv[3]),
+              "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+            : "v"(re), "v"(ro), "v"(mask));
+    }
+}
+
+// 1-bit: eight dot2 of mask pairs against activation pairs.
+template <int PENDING>
+__device__ __forceinline__ void consume4_b64(const u32x2_t (&vv)[4], const uint32_t* xr, float& a0, float& a1) {
+    asm volatile(
+        "s_waitcnt lgkmcnt(%c18)\n\t"
+        "v_dot2c_f32_bf16 %0, %2, %10\n\t"
+        "v_dot2c_f32_bf16 %1, %3, %11\n\t"
+        "v_dot2c_f32_bf16 %0, %4, %12\n\t"
+        "v_dot2c_f32_bf16 %1, %5, %13\n\t"
+        "v_dot2c_f32_bf16 %0, %6, %14\n\t"
+        "v_dot2c_f32_bf16 %1, %7, %15\n\t"
+        "v_dot2c_f32_bf16 %0, %8, %16\n\t"
+        "v_dot2c_f32_bf16 %1, %9, %17"
+        : "+v"(a0), "+v"(a1)
+        : "v"(vv[0][0]), "v"(vv[0][1]), "v"(vv[1][0]), "v"(vv[1][1]), "v"(vv[2][0]), "v"(vv[2][1]), "v"(vv[3][0]), "v"(vv[3][1]),
+          "v"(xr[0]), "v"(xr[1]), "v"(xr[2]), "v"(xr[3]), "v"(xr[4]), "v"(xr[5]), "v"(xr[6]), "v"(xr[7]),
+          "n"(PENDING));
+}
+
+template <int I, int END, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < END) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, END>(f);
+    }
+}
+
+template <int G> struct WordVec;
+template <> struct WordVec<1> { using type = uint32_t; };
+template <> struct WordVec<2> { using type = u32x2_t; };
+struct alignas(4) Words3 { uint32_t v[3]; __device__ uint32_t operator[](int j) const { return v[j]; } };
+template <> struct WordVec<3> { using type = Words3; };
+template <> struct WordVec<4> { using type = u32x4_t; };
+
+template <int G>
+__device__ __forceinline__ void load_words(const uint32_t* p, uint32_t (&w)[G]) {
+    using V = typename WordVec<G>::type;
+    if constexpr (G == 1) {
+        w[0] = __builtin_nontemporal_load(p);
+    } else if constexpr (G == 3) {
+        const V v = *reinterpret_cast<const V*>(p);
+#pragma unroll
+        for (int j = 0; j < G; ++j) w[j] = v[j];
+    } else {
+        const V v = __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
+#pragma unroll
+        for (int j = 0; j < G; ++j) w[j] = v[j];
+    }
+}
+
+// ---- the kernel ----------------------------------------------------------------------
+
+template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE>
+__global__ __launch_bounds__(NWK * NWR * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
+void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
+                     const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int64_t N) {
+    static_assert(BITS == 1 || BITS == 2 || BITS == 4, "3-bit fields do not align with nibbles");
+    constexpr int C = 1 << BITS;
+    constexpr int EL = G * 32 / BITS;              // elements per lane and row slice
+    constexpr int K = NWK * LPR * EL;
+    constexpr int WPR = K * BITS / 32;
+    constexpr int RPL = kWave / LPR;               // rows per wave-wide load
+    constexpr int ROWS_WAVE = RPL * RS;
+    constexpr int ROWS_WG = NWR * ROWS_WAVE;
+    constexpr int THREADS = NWK * NWR * 64;
+    constexpr int U = BITS == 1 ? 2 * G : G;       // lookup units (8 activation registers each) per row slice
+    constexpr int XR = 8 * U;                      // activation registers: bf16 pairs (1/2-bit) or fp32 (4-bit)
+    constexpr int C16 = EL * 2 / 16;               // 16-byte chunks of x per lane slice
+    constexpr int XCHUNKS = K / 8;
+    static_assert(RS <= 4 && (ROWS_WG % 2) == 0 && THREADS <= 1024, "launch shape");
+    static_assert(EL % 8 == 0, "x slices are whole 16-byte chunks");
+
+    struct alignas(256) Smem {
+        uint32_t lut[NWR * RPL][64];               // 2/4-bit: RS tables of 16 x 4 B; 1-bit: lut[0] holds the 16 x 8 B mask table
+        u32x4_t xs[XCHUNKS];                       // staged activations, swizzled per lane slice
+        float part[NWK][ROWS_WG];                  // per-slice partial sums
+        float sxp[NWK];                            // 1-bit: per-slice sum of x
+    };
+    __shared__ Smem sm;
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wk = wave % NWK, wr = wave / NWK;
+    const int sub = lane / LPR, pos = lane % LPR;
+    const int64_t wg_row0 = static_cast<int64_t>(blockIdx.x) * ROWS_WG;
+    const int64_t wave_row0 = wg_row0 + wr * ROWS_WAVE;
+
+    // ---- 1. small operands first: codebook rows for the tables, x chunks ----------------
+    constexpr int LUT_PASSES = BITS == 1 ? 0 : (ROWS_WG * 16 + THREADS - 1) / THREADS;
+    uint32_t cbv[LUT_PASSES > 0 ? LUT_PASSES : 1][BITS == 4 ? 1 : 2];
+#pragma unroll
+    for (int p = 0; p < LUT_PASSES; ++p) {
+        int rl = (threadIdx.x + p * THREADS) >> 4;                     // row inside the workgroup
+        rl = rl < ROWS_WG ? rl : ROWS_WG - 1;
+        int64_t row = wg_row0 + rl;
+        row = row < N ? row : N - 1;
+        if constexpr (BITS == 2) {
+            const u32x2_t c = *reinterpret_cast<const u32x2_t*>(codebook + row * C);
+            cbv[p][0] = c[0];
+            cbv[p][1] = c[1];
+        } else {
+            cbv[p][0] = codebook[row * C + (threadIdx.x & 15)];
+        }
+    }
+    constexpr int XPASSES = (XCHUNKS + THREADS - 1) / THREADS;
+    u32x4_t xt[XPASSES];
+#pragma unroll
+    for (int h = 0; h < XPASSES; ++h) {
+        int c = threadIdx.x + h * THREADS;
+        c = c < XCHUNKS ? c : XCHUNKS - 1;
+        xt[h] = reinterpret_cast<const u32x4_t*>(x)[c];
+    }
+
+    // ---- 2. every index load of this wave -------------------------------------------------
+    uint32_t w[RS][G];
+#pragma unroll
+    for (int t = 0; t < RS; ++t) {
+        int64_t row = wave_row0 + t * RPL + sub;
+        row = row < N ? row : N - 1;                                   // clamped: loads stay unconditional
+        load_words<G>(W + row * WPR + (wk * LPR + pos) * G, w[t]);
+    }
+
+    // ---- 3. tables and staged activations into LDS ------------------------------------------
+#pragma unroll
+    for (int h = 0; h < XPASSES; ++h) {
+        const int c = threadIdx.x + h * THREADS;
+        if (c < XCHUNKS) {
+            const int sl = c / C16, q = c % C16;
+            sm.xs[sl * C16 + (q + sl) % C16] = xt[h];
+        }
+    }
+    if constexpr (BITS == 1) {
+        if (threadIdx.x < 16) {
+            const uint32_t e = threadIdx.x;
+            u32x2_t m;
+            m[0] = ((e & 1u) ? 0x3F80u : 0u) | ((e & 2u) ? 0x3F800000u : 0u);
+            m[1] = ((e & 4u) ? 0x3F80u : 0u) | ((e & 8u) ? 0x3F800000u : 0u);
+            reinterpret_cast<u32x2_t*>(&sm.lut[0][0])[e] = m;
+        }
+    } else {
+#pragma unroll
+        for (int p = 0; p < LUT_PASSES; ++p) {
+            const int rl = (threadIdx.x + p * THREADS) >> 4, e = threadIdx.x & 15;
+            if (rl < ROWS_WG) {
+                // row rl = (wr', t', sub') with rl = wr'*ROWS_WAVE + t'*RPL + sub'
+                const int wr2 = rl / ROWS_WAVE, t2 = (rl % ROWS_WAVE) / RPL, sub2 = rl % RPL;
+                uint32_t entry;
+                if constexpr (BITS == 2) {
+                    const uint64_t c64 = static_cast<uint64_t>(cbv[p][0]) | (static_cast<uint64_t>(cbv[p][1]) << 32);
+                    entry = (static_cast<uint32_t>(c64 >> (16 * (e & 3))) & 0xFFFFu) |
+                            ((static_cast<uint32_t>(c64 >> (16 * (e >> 2))) & 0xFFFFu) << 16);
+                } else {
+                    entry = cbv[p][0] << 16;
+                }
+                sm.lut[wr2 * RPL + sub2][t2 * 16 + e] = entry;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- 4. this lane's activations into registers ---------------------------------------------
+    uint32_t xr[XR];
+    {
+        const int sl = wk * LPR + pos;
+#pragma unroll
+        for (int q = 0; q < C16; ++q) {
+            const u32x4_t v = sm.xs[sl * C16 + (q + sl) % C16];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (BITS == 4) {
+                    xr[q * 8 + 2 * j] = v[j] << 16;
+                    xr[q * 8 + 2 * j + 1] = v[j] & 0xFFFF0000u;
+                } else {
+                    xr[q * 4 + j] = v[j];
+                }
+            }
+        }
+    }
+
+    // ---- 5. lookups and multiply-accumulate, one unit ahead -------------------------------------
+    const uint32_t lut_base = static_cast<uint32_t>(reinterpret_cast<size_t>(
+        (lds_cu32_t*)(&sm.lut[BITS == 1 ? 0 : wr * RPL + sub][0])));
+    uint32_t ar[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ar[i] = lut_base;
+    // Everything the compiler itself has in flight on the LGKM counter (the reads of
+    // x above) must have landed before the hand-counted pipeline starts.
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    const uint32_t mask = BITS == 1 ? 0x78u : 0x3Cu;
+    float acc[RS];
+    float a0 = 0.f, a1 = 0.f;
+    constexpr int NU = RS * U;
+    if constexpr (BITS == 1) {
+        u32x2_t vv[2][4];
+        uint32_t re = 0, ro = 0;
+        issue4_b64<0>(w[0][0], re, ro, ar, vv[0], mask);
+        static_for<0, NU>([&](auto ic) {
+            constexpr int n = decltype(ic)::value;
+            constexpr int t = n / U, u = n % U;
+            if constexpr (n + 1 < NU) {
+                constexpr int t1 = (n + 1) / U, u1 = (n + 1) % U;
+                issue4_b64<u1 % 2>(w[t1][u1 / 2], re, ro, ar, vv[(n + 1) & 1], mask);
+                consume4_b64<4>(vv[n & 1], &xr[u * 8], a0, a1);
+            } else {
+                consume4_b64<0>(vv[n & 1], &xr[u * 8], a0, a1);
+            }
+            if constexpr (u == U - 1) { acc[t] = a0 + a1; a0 = 0.f; a1 = 0.f; }
+        });
+    } else {
+        uint32_t v[2][8];
+        uint32_t re = 0, ro = 0;
+        issue4_b32<0, 0>(w[0][0], re, ro, ar, v[0], mask);
+        issue4_b32<0, 1>(w[0][0], re, ro, ar, v[0], mask);
+        static_for<0, NU>([&](auto ic) {
+            constexpr int n = decltype(ic)::value;
+            constexpr int t = n / U, u = n % U;
+            if constexpr (n + 1 < NU) {
+                constexpr int t1 = (n + 1) / U, u1 = (n + 1) % U;
+                issue4_b32<t1 * 64, 0>(w[t1][u1], re, ro, ar, v[(n + 1) & 1], mask);
+                if constexpr (BITS == 2) consume8_dot2<4>(v[n & 1], &xr[u * 8], a0, a1);
+                else consume8_fma<4>(v[n & 1], &xr[u * 8], a0, a1);
+                issue4_b32<t1 * 64, 1>(w[t1][u1], re, ro, ar, v[(n + 1) & 1], mask);
+            } else {
+                if constexpr (BITS == 2) consume8_dot2<0>(v[n & 1], &xr[u * 8], a0, a1);
+                else consume8_fma<0>(v[n & 1], &xr[u * 8], a0, a1);
+            }
+            if constexpr (u == U - 1) { acc[t] = a0 + a1; a0 = 0.f; a1 = 0.f; }
+        });
+    }
+
+    // ---- 6. K-reduction: lanes of the group, then slices through LDS ------------------------------
+    if constexpr (BITS == 1) {
+        float sx = 0.f;
+#pragma unroll
+        for (int i = 0; i < XR; ++i) sx = dot2_bf16(0x3F803F80u, xr[i], sx);
+        sx = group_sum<LPR>(sx);
+        if (wr == 0 && lane == 63) sm.sxp[wk] = sx;
+    }
+#pragma unroll
+    for (int t = 0; t < RS; ++t) {
+        const float s = group_sum<LPR>(acc[t]);
+        if (pos == LPR - 1) sm.part[wk][wr * ROWS_WAVE + t * RPL + sub] = s;
+    }
+    __syncthreads();
+
+    // ---- 7. epilogue: two rows per thread, one coalesced store per workgroup ----------------------
+    if (threadIdx.x < ROWS_WG / 2) {
+        float out[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int rl = threadIdx.x * 2 + h;
+            float s = 0.f;
+#pragma unroll
+            for (int k = 0; k < NWK; ++k) s += sm.part[k][rl];
+            if constexpr (BITS == 1) {
+                float sx = 0.f;
+#pragma unroll
+                for (int k = 0; k < NWK; ++k) sx += sm.sxp[k];
+                int64_t row = wg_row0 + rl;
+                row = row < N ? row : N - 1;
+                const uint32_t cc = *reinterpret_cast<const uint32_t*>(codebook + row * 2);
+                const float c0 = bf16_to_f32(cc & 0xFFFFu), c1 = bf16_to_f32(cc >> 16);
+                s = fmaf(c1 - c0, s, c0 * sx);
+            }
+            out[h] = s;
+        }
+        const int64_t r2 = wg_row0 + threadIdx.x * 2;
+        const uint32_t packed = static_cast<uint32_t>(f32_to_bf16(out[0])) | (static_cast<uint32_t>(f32_to_bf16(out[1])) << 16);
+        if (r2 + 1 < N && (reinterpret_cast<uintptr_t>(y) & 3u) == 0) {
+            *reinterpret_cast<uint32_t*>(y + r2) = packed;
+        } else {
+            if (r2 < N) y[r2] = static_cast<uint16_t>(packed);
+            if (r2 + 1 < N) y[r2 + 1] = static_cast<uint16_t>(packed >> 16);
+        }
+    }
+}
+
+// ---- specialisation table ------------------------------------------------------------------
+
+struct LutEntry {
+    int bits;
+    int64_t K;
+    const char* name;
+    void (*launch)(const GemmArgs&, hipStream_t);
+};
+
+template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE>
+static void launch_lut(const GemmArgs& a, hipStream_t s) {
+    constexpr int rows_wg = NWR * (kWave / LPR) * RS;
+    const dim3 grid(static_cast<unsigned>((a.N + rows_wg - 1) / rows_wg)), block(NWK * NWR * 64);
+    hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE>), grid, block, 0, s,
+                       a.W, a.codebook, a.X, a.Y, a.N);
+}
+
+#define KMQ_LUT(BITS, G, LPR, NWK, NWR, RS, WPE) \
+    { BITS, int64_t(NWK) * LPR * (G * 32 / BITS), \
+      "lut_b" #BITS "_g" #G "_l" #LPR "_k" #NWK "_r" #NWR "x" #RS, &launch_lut<BITS, G, LPR, NWK, NWR, RS, WPE> }
+
+static const LutEntry kLut[] = {
+    // 1-bit
+    KMQ_LUT(1, 4, 16, 1, 4, 1, 4),   // K = 2048
+    KMQ_LUT(1, 3, 32, 1, 4, 2, 4),   // K = 3072
+    KMQ_LUT(1, 4, 32, 1, 4, 2, 4),   // K = 4096
+    KMQ_LUT(1, 4, 64, 1, 4, 2, 4),   // K = 8192
+    // 2-bit
+    KMQ_LUT(2, 4, 32, 1, 4, 2, 6),   // K = 2048
+    KMQ_LUT(2, 3, 64, 1, 4, 2, 6),   // K = 3072
+    KMQ_LUT(2, 4, 64, 1, 4, 2, 7),   // K = 4096
+    KMQ_LUT(2, 4, 64, 2, 2, 2, 7),   // K = 8192
+    KMQ_LUT(2, 2, 64, 7, 1, 4, 7),   // K = 14336
+    // 4-bit
+    KMQ_LUT(4, 4, 64, 1, 4, 2, 6),   // K = 2048
+    KMQ_LUT(4, 4, 64, 2, 2, 2, 6),   // K = 4096
+    KMQ_LUT(4, 4, 64, 4, 1, 2, 6),   // K = 8192
+    KMQ_LUT(4, 4, 64, 7, 1, 2, 6),   // K = 14336
+};
+constexpr int kLutCount = sizeof(kLut) / sizeof(kLut[0]);
+
+int lut_find(int64_t K, int bits, int layout) {
+    if (layout != KMQ_LAYOUT_CANONICAL) return -1;
+    for (int i = 0; i < kLutCount; ++i)
+        if (kLut[i].bits == bits && kLut[i].K == K) return i;
+    return -1;
+}
+
+const char* lut_name(int i) { return kLut[i].name; }
+
+hipError_t launch_lut_entry(int i, const GemmArgs& a, hipStream_t s) {
+    kLut[i].launch(a, s);
+    return hipGetLastError();
+}
+
+}  // namespace kmq
