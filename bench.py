@@ -61,7 +61,7 @@ class Instances:
     oracle; the others are drawn on the device with the same distributions
     (uniform index bits, sorted N(0, 0.02) centroids, N(0, 1) activations)."""
 
-    def __init__(self, name, rotate=True):
+    def __init__(self, name, rotate=True, layout=None):
         import numpy as np
         import torch
 
@@ -69,6 +69,9 @@ class Instances:
         self.name = name
         self.bits, self.N, self.K, self.M, seed, matrix, sym = WORKLOADS[name]
         bits, N, K, M = self.bits, self.N, self.K, self.M
+        # batch > 1 runs on the tiled (matrix-core) layout by default: the offline,
+        # reversible repack is outside the timed region
+        self.layout = (1 if M > 1 else 0) if layout is None else layout
         self.bytes = synth.algorithmic_bytes(N, K, bits, M)
         self.R = max(2, -(-2 * LLC_BYTES // self.bytes)) if rotate else 1
         self.R = min(self.R, 2048)
@@ -77,11 +80,18 @@ class Instances:
         self.X = synth.make_x(seed, matrix, M, K)
         self.packed = kmq.pack(self.idx, bits)
         wpr = self.packed.shape[1]
+        stored = self.packed
+        if self.layout == 1:
+            t0 = time.perf_counter()
+            stored = kmq.repack(self.packed, K, bits, 1).reshape(-1, wpr)
+            self.repack_ms = (time.perf_counter() - t0) * 1e3
+            assert np.array_equal(kmq.unrepack(stored, N, K, bits, 1), self.packed)
+        nrows_stored = stored.shape[0]
         g = torch.Generator(device="cuda")
         g.manual_seed(1234 + seed)
-        self.W, self.C, self.Xd, self.Y = [_dev(self.packed)], [_dev(self.cb)], [_dev(self.X)], []
+        self.W, self.C, self.Xd, self.Y = [_dev(stored)], [_dev(self.cb)], [_dev(self.X)], []
         for _ in range(1, self.R):
-            self.W.append(torch.randint(-2**31, 2**31, (N, wpr), dtype=torch.int32, device="cuda", generator=g))
+            self.W.append(torch.randint(-2**31, 2**31, (nrows_stored, wpr), dtype=torch.int32, device="cuda", generator=g))
             if sym:
                 t = (torch.randn(N, device="cuda", generator=g) * 0.02).abs().to(torch.bfloat16)
                 c = torch.stack([-t, t], dim=1)
@@ -92,18 +102,18 @@ class Instances:
             self.Xd.append(torch.randn((M, K), device="cuda", generator=g).to(torch.bfloat16).view(torch.int16))
         for _ in range(self.R):
             self.Y.append(torch.zeros((M, N), dtype=torch.int16, device="cuda"))
-        ws = kmq.workspace_bytes(N, K, bits, M, 0)
+        ws = kmq.workspace_bytes(N, K, bits, M, self.layout)
         self.ws = torch.empty(ws, dtype=torch.uint8, device="cuda") if ws else None
-        self.kernel = kmq.kernel_name(N, K, bits, M, 0)
+        self.kernel = kmq.kernel_name(N, K, bits, M, self.layout)
 
     def call(self, i):
         from paper_2602_15563_amd import kmq
         r = i % self.R
         if self.M == 1:
-            kmq.gemv(self.W[r], self.C[r], self.Xd[r], self.Y[r], self.N, self.K, self.bits, 0, self.ws)
+            kmq.gemv(self.W[r], self.C[r], self.Xd[r], self.Y[r], self.N, self.K, self.bits, self.layout, self.ws)
         else:
             kmq.gemm_smallbatch(self.W[r], self.C[r], self.Xd[r], self.Y[r], self.N, self.K, self.M,
-                                self.bits, 0, self.ws)
+                                self.bits, self.layout, self.ws)
 
     def check(self):
         """Instance 0 against the oracle on sampled row blocks; returns max err/A."""
@@ -190,6 +200,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch directly instead of replaying a HIP graph")
     ap.add_argument("--no-rotate", action="store_true", help="reuse one instance (cache-resident, NOT the headline)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--layout", type=int, default=None, choices=(0, 1),
+                    help="0 canonical, 1 tiled (default: canonical for batch 1, tiled for batch > 1)")
     ap.add_argument("--table", action="store_true", help="also time every contract shape -> gpurun_out/bench_table.json")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -202,7 +214,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    inst = Instances(args.workload, rotate=not args.no_rotate)
+    inst = Instances(args.workload, rotate=not args.no_rotate, layout=args.layout)
     worst = inst.check()
     secs, steps = time_workload(inst, args.steps, args.warmup, use_graph=not args.no_graph)
     us = secs / steps * 1e6
@@ -216,7 +228,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 in/out, fp32 accumulate", "data": "synthetic",
         "config": {"workload": args.workload, "bits": inst.bits, "N": inst.N, "K": inst.K, "batch": inst.M,
-                   "kernel": inst.kernel, "rotating_instances": inst.R, "hip_graph": not args.no_graph,
+                   "kernel": inst.kernel, "layout": "tiled" if inst.layout else "canonical",
+                   "rotating_instances": inst.R, "hip_graph": not args.no_graph,
                    "algorithmic_bytes_per_call": inst.bytes, "max_err_over_A_vs_oracle": float(f"{worst:.3e}")},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
@@ -232,7 +245,8 @@ def main():
             it = Instances(name)
             w = it.check()
             s, n = time_workload(it, 5000, 100)
-            rows.append({"workload": name, "kernel": it.kernel, "us_per_call": round(s / n * 1e6, 3),
+            rows.append({"workload": name, "kernel": it.kernel, "layout": "tiled" if it.layout else "canonical",
+                         "us_per_call": round(s / n * 1e6, 3),
                          "GBps": round(it.bytes / (s / n) / 1e9, 1),
                          "pct_peak": round(100 * it.bytes / (s / n) / 1e9 / HBM_PEAK_GBS, 2),
                          "bytes": it.bytes, "R": it.R, "max_err_over_A": float(f"{w:.3e}")})

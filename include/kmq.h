@@ -74,13 +74,19 @@ kmq_status kmq_unpack(const uint32_t* packed, int64_t N, int64_t K, int bits, ui
  * the paper's remark (App. E, "Micro-benchmarks: Results") that custom code with
  * an optimised data layout is the route to faster low-bit kernels.
  *
- * KMQ_LAYOUT_TILED: rows are grouped in blocks of 16 (the last block may be
- * short); inside a block the words are stored column-block by column-block, a
- * column block being 4 consecutive words (16 bytes) of one row:
- *     tiled[ (rb*wpr4 + cb) * 16*4 + r*4 + j ] = canonical[ (rb*16 + r)*wpr + cb*4 + j ]
- * with wpr4 = wpr/4; requires wpr % 4 == 0 (else KMQ_ERR_LAYOUT).  A short
- * last block keeps the stride 16 (unused slots are zero), so `tiled` holds
- * ceil(N/16)*16*wpr words: size it with kmq_tiled_words(). */
+ * KMQ_LAYOUT_TILED is the operand order of the matrix-core kernels.  The unit
+ * that moves is a GROUP: 8 consecutive elements of a row, i.e. `bits` whole
+ * bytes of the canonical stream (bit order inside a group is unchanged).  Let
+ * gpg = 16, 8, 4, 4 groups for bits = 1, 2, 3, 4.  K is cut into super-blocks of
+ * 4*gpg groups (512, 256, 128, 128 elements) and rows into blocks of 16 (the
+ * last block may be short; its missing rows are zero).  The GRANULE (rb, sb, q, n)
+ * holds, in order j = 0..gpg-1, the groups q + 4j of super-block sb of row
+ * 16*rb + n; it is gpg*bits bytes (16, 16, 12, 16) and lives at byte offset
+ *     ((rb * nsb + sb) * 64 + q*16 + n) * gpg*bits,      nsb = K / (32*gpg),
+ * so one 64-lane load of consecutive granules is 16 rows x one super-block, and
+ * lane (n, q) of a 16x16x32 matrix-core step j reads columns 8*(q+4j)..+7 of both
+ * operands.  Requires K % (32*gpg) == 0 (else KMQ_ERR_LAYOUT).  `tiled` holds
+ * ceil(N/16)*16 * wpr words: size it with kmq_tiled_words(). */
 kmq_status kmq_repack(const uint32_t* canonical, int64_t N, int64_t K, int bits, int layout,
                       uint32_t* tiled);
 kmq_status kmq_unrepack(const uint32_t* tiled, int64_t N, int64_t K, int bits, int layout,

@@ -14,7 +14,11 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout) {
     Plan p{kVariantInvalid, -1, 0, "invalid"};
     if (!bits_valid(bits) || !dims_valid(N, K) || M < 1 || M > KMQ_MAX_BATCH) return p;
     if (layout != KMQ_LAYOUT_CANONICAL && layout != KMQ_LAYOUT_TILED) return p;
-    if (layout == KMQ_LAYOUT_TILED && words_per_row(bits, K) % kTileColWords) return p;
+    if (layout == KMQ_LAYOUT_TILED && !tiled_valid(bits, K)) return p;
+    if (layout == KMQ_LAYOUT_TILED) {
+        static const char* const names[4] = {"mfma_b1", "mfma_b2", "mfma_b3", "mfma_b4"};
+        return Plan{kVariantMfma, -1, 0, names[bits - 1]};
+    }
     if (M == 1) {
         const int l = lut_find(K, bits, layout);
         if (l >= 0) return Plan{kVariantLut, l, 0, lut_name(l)};
@@ -40,7 +44,7 @@ static kmq_status check_and_run(const GemmArgs& a, void* stream) {
     if (!bits_valid(a.bits)) return KMQ_ERR_BITS;
     if (!dims_valid(a.N, a.K) || a.M < 1 || a.M > KMQ_MAX_BATCH) return KMQ_ERR_SHAPE;
     if (a.layout != KMQ_LAYOUT_CANONICAL && a.layout != KMQ_LAYOUT_TILED) return KMQ_ERR_LAYOUT;
-    if (a.layout == KMQ_LAYOUT_TILED && words_per_row(a.bits, a.K) % kTileColWords) return KMQ_ERR_LAYOUT;
+    if (a.layout == KMQ_LAYOUT_TILED && !tiled_valid(a.bits, a.K)) return KMQ_ERR_LAYOUT;
     if (!aligned(a.W, 16) || !aligned(a.X, 16) || !aligned(a.codebook, 4) || !aligned(a.Y, 2)) return KMQ_ERR_ALIGN;
     const Plan plan = make_plan(a.N, a.K, a.bits, a.M, a.layout);
     if (plan.variant == kVariantInvalid) return KMQ_ERR_SHAPE;
@@ -48,6 +52,7 @@ static kmq_status check_and_run(const GemmArgs& a, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
     switch (plan.variant) {
+        case kVariantMfma: e = launch_mfma(a, s); break;
         case kVariantLut: e = launch_lut_entry(plan.table_index, a, s); break;
         case kVariantRowsplit: e = launch_rowsplit(plan.table_index, a, s); break;
         default: e = launch_generic(a, s); break;
@@ -87,7 +92,7 @@ kmq_status kmq_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd
     if (!kmq::bits_valid(bits)) return KMQ_ERR_BITS;
     if (!kmq::dims_valid(N, K)) return KMQ_ERR_SHAPE;
     if (layout != KMQ_LAYOUT_CANONICAL && layout != KMQ_LAYOUT_TILED) return KMQ_ERR_LAYOUT;
-    if (layout == KMQ_LAYOUT_TILED && kmq::words_per_row(bits, K) % kmq::kTileColWords) return KMQ_ERR_LAYOUT;
+    if (layout == KMQ_LAYOUT_TILED && !kmq::tiled_valid(bits, K)) return KMQ_ERR_LAYOUT;
     if ((reinterpret_cast<uintptr_t>(W) & 15) || (reinterpret_cast<uintptr_t>(codebook) & 3) ||
         (reinterpret_cast<uintptr_t>(Wdense) & 1)) return KMQ_ERR_ALIGN;
     const hipError_t e = kmq::launch_dequant(W, codebook, Wdense, N, K, bits, layout,

@@ -54,12 +54,17 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
-// Index of 32-bit word `w` of row `n` in the stored stream.
-__device__ __forceinline__ int64_t word_index(int layout, int64_t n, int64_t w, int64_t wpr) {
-    if (layout == KMQ_LAYOUT_CANONICAL) return n * wpr + w;
-    const int64_t rb = n / kTileRows, r = n % kTileRows;
-    const int64_t cb = w / kTileColWords, j = w % kTileColWords;
-    return ((rb * (wpr / kTileColWords) + cb) * kTileRows + r) * kTileColWords + j;
+// 32-bit word `w` of row `n` of the canonical stream, read from either layout.
+// In the tiled layout the four bytes of a canonical word need not be adjacent.
+__device__ __forceinline__ uint32_t fetch_word(const uint32_t* W, int layout, int bits, int64_t K,
+                                               int64_t n, int64_t w, int64_t wpr) {
+    if (layout == KMQ_LAYOUT_CANONICAL) return W[n * wpr + w];
+    const uint8_t* b = reinterpret_cast<const uint8_t*>(W);
+    uint32_t v = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        v |= static_cast<uint32_t>(b[tiled_byte_index(bits, K, n, w * 4 + i)]) << (8 * i);
+    return v;
 }
 
 }  // namespace kmq

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 #pragma unroll
         for (int j = 0; j < BITS; ++j) {
             const int64_t wi = g * BITS + j;
-            w[j] = wi < wpr ? W[word_index(layout, n, wi, wpr)] : 0u;
+            w[j] = wi < wpr ? fetch_word(W, layout, BITS, K, n, wi, wpr) : 0u;
         }
         const int64_t k0 = g << 5;
         const bool full = k0 + 32 <= K;
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(
 #pragma unroll
         for (int j = 0; j < BITS; ++j) {
             const int64_t wi = g * BITS + j;
-            w[j] = wi < wpr ? W[word_index(layout, n, wi, wpr)] : 0u;
+            w[j] = wi < wpr ? fetch_word(W, layout, BITS, K, n, wi, wpr) : 0u;
         }
         uint16_t c[C];
 #pragma unroll

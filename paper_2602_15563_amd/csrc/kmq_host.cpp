@@ -74,7 +74,7 @@ int64_t kmq_tiled_words(int64_t N, int64_t K, int bits, int layout) {
     const int64_t wpr = kmq::words_per_row(bits, K);
     if (layout == KMQ_LAYOUT_CANONICAL) return N * wpr;
     if (layout == KMQ_LAYOUT_TILED) {
-        if (wpr % kmq::kTileColWords) return -1;
+        if (!kmq::tiled_valid(bits, K)) return -1;
         return kmq::round_up(N, kmq::kTileRows) * wpr;
     }
     return -1;
@@ -90,18 +90,20 @@ static kmq_status repack_impl(const uint32_t* src, int64_t N, int64_t K, int bit
         std::memcpy(dst, src, static_cast<size_t>(N * wpr) * sizeof(uint32_t));
         return KMQ_OK;
     }
-    if (layout != KMQ_LAYOUT_TILED || wpr % kmq::kTileColWords) return KMQ_ERR_LAYOUT;
-    const int64_t R = kmq::kTileRows, C = kmq::kTileColWords, ncb = wpr / C;
-    const int64_t nrb = (N + R - 1) / R;
-    if (forward) std::memset(dst, 0, static_cast<size_t>(nrb * R * wpr) * sizeof(uint32_t));
-    for (int64_t rb = 0; rb < nrb; ++rb)
-        for (int64_t cb = 0; cb < ncb; ++cb)
-            for (int64_t r = 0; r < R && rb * R + r < N; ++r) {
-                const int64_t t = ((rb * ncb + cb) * R + r) * C;
-                const int64_t c = (rb * R + r) * wpr + cb * C;
-                if (forward) std::memcpy(dst + t, src + c, C * sizeof(uint32_t));
-                else         std::memcpy(dst + c, src + t, C * sizeof(uint32_t));
-            }
+    if (layout != KMQ_LAYOUT_TILED || !kmq::tiled_valid(bits, K)) return KMQ_ERR_LAYOUT;
+    const int64_t row_bytes = wpr * 4;              // K*bits/8 exactly: K is a multiple of 128
+    const int64_t nrows_padded = kmq::round_up(N, kmq::kTileRows);
+    const uint8_t* s8 = reinterpret_cast<const uint8_t*>(src);
+    uint8_t* d8 = reinterpret_cast<uint8_t*>(dst);
+    if (forward) std::memset(dst, 0, static_cast<size_t>(nrows_padded * row_bytes));
+    // groups of `bits` bytes move as a unit
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t g0 = 0; g0 < row_bytes; g0 += bits) {
+            const int64_t t = kmq::tiled_byte_index(bits, K, n, g0);
+            const int64_t c = n * row_bytes + g0;
+            if (forward) std::memcpy(d8 + t, s8 + c, static_cast<size_t>(bits));
+            else         std::memcpy(d8 + c, s8 + t, static_cast<size_t>(bits));
+        }
     return KMQ_OK;
 }
 

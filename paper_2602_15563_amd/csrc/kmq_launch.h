@@ -26,6 +26,7 @@ enum Variant {
     kVariantGeneric,     // any shape: wave per row, fp32 codebook in LDS
     kVariantRowsplit,    // batch 1, K from a table: x in registers, LUT in LDS (compiler-scheduled; 3-bit)
     kVariantLut,         // batch 1, 1/2/4-bit, K from a table: hand-scheduled LDS-table kernel
+    kVariantMfma,        // tiled layout, batch 1..16: matrix-core kernel
 };
 
 struct Plan {
@@ -45,6 +46,11 @@ hipError_t launch_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t*
 int rowsplit_find(int64_t K, int bits, int layout);
 const char* rowsplit_name(int table_index);
 hipError_t launch_rowsplit(int table_index, const GemmArgs& a, hipStream_t s);
+
+// Matrix-core kernel (tiled layout only).
+hipError_t launch_mfma(const GemmArgs& a, hipStream_t s);
+int mfma_waves_along_k(int64_t K, int bits);
+int mfma_row_blocks(int64_t N);
 
 // Hand-scheduled table kernels (1/2/4-bit): -1 if (bits, K, layout) has none.
 int lut_find(int64_t K, int bits, int layout);

@@ -1,0 +1,264 @@
+// Small-batch product Y = X W^T on the matrix cores, tiled layout, any batch
+// 1..16 (paper App. D/E: up to a batch of a few tens the product is still bound
+// by the transfer of W, provided each weight is dequantised once and reused for
+// every batch column).
+//
+// One v_mfma_f32_16x16x32_bf16 step multiplies a 16-row x 32-column tile of
+// dequantised W (A operand) by the matching 32 x 16 slice of X^T (B operand;
+// batch columns beyond M are computed and dropped).  Lane (n, q) = (lane & 15,
+// lane >> 4) supplies 8 weights of row n and 8 activations of batch column n,
+// both for columns 8*(q + 4j)..+7 of the current super-block at step j: the
+// tiled layout stores exactly those groups contiguously per lane (a granule),
+// so the index stream is read with one 12- or 16-byte load per lane and
+// super-block, and the activation loads of a step cover 64 contiguous bytes of
+// each batch row.
+//
+// Dequantisation per step and lane: 8 lookups in the lane's row codebook (bf16
+// entries in LDS, 16 B per row so that the 16 rows of a block tile the 64 banks),
+// combined pairwise into 4 VGPRs.  1-bit needs no per-row table: the A operand
+// is the {0,1} mask of the bits (row-independent nibble table), a second MFMA
+// with an all-ones A operand accumulates sum_k x, and the epilogue applies the
+// two-centroid closed form y = c0*sum(x) + (c1 - c0)*sum_{idx=1} x.
+//
+// A workgroup is NWK waves that split K (whole super-blocks each) for RBW blocks
+// of 16 rows; partial 16x16 tiles are summed through LDS in a fixed order.
+#include "kmq_device.h"
+#include "kmq_launch.h"
+
+namespace kmq {
+
+constexpr int kPrefetch = 4;   // super-blocks of index granules in flight per wave
+
+template <int BITS> struct Tiled {
+    static constexpr int GPG = BITS == 1 ? 16 : BITS == 2 ? 8 : 4;   // groups (MFMA steps) per granule
+    static constexpr int GW = GPG * BITS / 4;                        // dwords per granule
+    static constexpr int SBE = 32 * GPG;                             // elements per super-block
+};
+
+template <int GW>
+__device__ __forceinline__ void load_granule(const uint32_t* p, uint32_t (&g)[GW]) {
+    if constexpr (GW == 3) {
+        struct alignas(4) W3 { uint32_t v[3]; };
+        const W3 t = *reinterpret_cast<const W3*>(p);
+        g[0] = t.v[0]; g[1] = t.v[1]; g[2] = t.v[2];
+    } else {
+        const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+        g[0] = t[0]; g[1] = t[1]; g[2] = t[2]; g[3] = t[3];
+    }
+}
+
+// The `bits`*8 index bits of group j of a granule, in the low bits of the result.
+template <int BITS, int GW>
+__device__ __forceinline__ uint32_t group_bits(const uint32_t (&g)[GW], int j) {
+    if constexpr (BITS == 4) return g[j];
+    if constexpr (BITS == 2) return (g[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
+    if constexpr (BITS == 1) return (g[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+    if constexpr (BITS == 3) {
+        switch (j) {
+            case 0: return g[0];
+            case 1: return __builtin_amdgcn_alignbit(g[1], g[0], 24);
+            case 2: return __builtin_amdgcn_alignbit(g[2], g[1], 16);
+            default: return g[2] >> 8;
+        }
+    }
+    return 0;
+}
+
+template <int BITS, int NWK, int RBW>
+__global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
+    const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
+    const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int64_t N, int64_t K, int M) {
+    using T = Tiled<BITS>;
+    constexpr int GPG = T::GPG, GW = T::GW, SBE = T::SBE, C = 1 << BITS;
+    constexpr int THREADS = NWK * 64;
+
+    struct alignas(256) Smem {
+        uint16_t tbl[BITS == 1 ? 1 : RBW * 16][BITS == 1 ? 8 : (C < 8 ? 8 : C)];   // 16 B (32 B for 4-bit) per row
+        u32x2_t masks[16];                                  // 1-bit: nibble -> four bf16 {0,1}
+        float red[NWK][RBW][256];                           // partial tiles, [n][m]
+        float redx[BITS == 1 ? NWK : 1][16];                // 1-bit: partial sum_k x per batch column
+    };
+    __shared__ Smem sm;
+
+    const int wk = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int n = lane & 15, q = lane >> 4;
+    const int64_t rb0 = static_cast<int64_t>(blockIdx.x) * RBW;
+    const int64_t nrb = (N + 15) >> 4;
+    const int nsb = static_cast<int>(K / SBE);
+    const int spw = nsb / NWK;                              // super-blocks per wave (host guarantees divisibility)
+    const int sb0 = wk * spw;
+
+    // ---- tables ---------------------------------------------------------------------------
+    if constexpr (BITS == 1) {
+        if (threadIdx.x < 16) {
+            const uint32_t e = threadIdx.x;
+            u32x2_t m;
+            m[0] = ((e & 1u) ? 0x3F80u : 0u) | ((e & 2u) ? 0x3F800000u : 0u);
+            m[1] = ((e & 4u) ? 0x3F80u : 0u) | ((e & 8u) ? 0x3F800000u : 0u);
+            sm.masks[e] = m;
+        }
+    } else {
+        for (int i = threadIdx.x; i < RBW * 16 * C; i += THREADS) {
+            const int r = i / C, e = i % C;
+            int64_t row = (rb0 + r / 16) * 16 + (r % 16);
+            row = row < N ? row : N - 1;
+            sm.tbl[r][e] = codebook[row * C + e];
+        }
+    }
+
+    // ---- index granules: kPrefetch super-blocks in flight per row block ----------------------
+    const int64_t gstride = 64 * GW;                        // dwords per (row block, super-block) tile
+    const uint32_t* wbase[RBW];
+#pragma unroll
+    for (int r = 0; r < RBW; ++r) {
+        int64_t rb = rb0 + r;
+        rb = rb < nrb ? rb : nrb - 1;
+        wbase[r] = W + (rb * nsb + sb0) * gstride + lane * GW;
+    }
+    uint32_t gran[kPrefetch][RBW][GW];
+#pragma unroll
+    for (int p = 0; p < kPrefetch; ++p) {
+        const int s = p < spw ? p : spw - 1;
+#pragma unroll
+        for (int r = 0; r < RBW; ++r) load_granule<GW>(wbase[r] + s * gstride, gran[p][r]);
+    }
+    __syncthreads();
+
+    // activations: lane (m = n, q) reads 16 bytes at X[m][sb*SBE + 8*(q + 4j)]
+    const int mrow = n < M ? n : M - 1;                     // columns >= M are computed and dropped
+    const uint16_t* xlane = X + static_cast<int64_t>(mrow) * K + static_cast<int64_t>(sb0) * SBE + 8 * q;
+
+    f32x4_t acc[RBW];
+#pragma unroll
+    for (int r = 0; r < RBW; ++r) acc[r] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    [[maybe_unused]] f32x4_t accx = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    [[maybe_unused]] const uint16_t* trow[RBW];
+    if constexpr (BITS != 1) {
+#pragma unroll
+        for (int r = 0; r < RBW; ++r) trow[r] = &sm.tbl[r * 16 + n][0];
+    }
+
+    for (int s0 = 0; s0 < spw; s0 += kPrefetch) {
+#pragma unroll
+        for (int p = 0; p < kPrefetch; ++p) {
+            const int s = s0 + p;
+            if (s < spw) {
+                const uint16_t* xs = xlane + static_cast<int64_t>(s) * SBE;
+                u32x4_t xf[GPG];
+#pragma unroll
+                for (int j = 0; j < GPG; ++j) xf[j] = *reinterpret_cast<const u32x4_t*>(xs + 32 * j);
+#pragma unroll
+                for (int j = 0; j < GPG; ++j) {
+                    const bf16x8_t b = __builtin_bit_cast(bf16x8_t, xf[j]);
+#pragma unroll
+                    for (int r = 0; r < RBW; ++r) {
+                        const uint32_t gb = group_bits<BITS, GW>(gran[p][r], j);
+                        u32x4_t a;
+                        if constexpr (BITS == 1) {
+                            const u32x2_t lo = sm.masks[gb & 15u], hi = sm.masks[gb >> 4];
+                            a = u32x4_t{lo[0], lo[1], hi[0], hi[1]};
+                        } else {
+                            uint32_t wv[8];
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) wv[e] = trow[r][(gb >> (BITS * e)) & (C - 1)];
+                            a = u32x4_t{wv[0] | (wv[1] << 16), wv[2] | (wv[3] << 16),
+                                        wv[4] | (wv[5] << 16), wv[6] | (wv[7] << 16)};
+                        }
+                        acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), b, acc[r], 0, 0, 0);
+                    }
+                    if constexpr (BITS == 1) {
+                        const u32x4_t ones = u32x4_t{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+                        accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ones), b, accx, 0, 0, 0);
+                    }
+                }
+                // refill this slot with the granule kPrefetch super-blocks ahead
+                const int sn = s + kPrefetch < spw ? s + kPrefetch : spw - 1;
+#pragma unroll
+                for (int r = 0; r < RBW; ++r) load_granule<GW>(wbase[r] + sn * gstride, gran[p][r]);
+            }
+        }
+    }
+
+    // ---- K-reduction across the waves, fixed order ---------------------------------------------
+    // lane holds D[row 4*q + i][batch column n], i = 0..3
+#pragma unroll
+    for (int r = 0; r < RBW; ++r)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sm.red[wk][r][(4 * q + i) * 16 + n] = acc[r][i];
+    if constexpr (BITS == 1) {
+        if (q == 0) sm.redx[wk][n] = accx[0];               // every row of the all-ones tile is sum_k x[m][k]
+    }
+    __syncthreads();
+
+    for (int o = threadIdx.x; o < RBW * 256; o += THREADS) {
+        const int m = o / (RBW * 16), nl = o % (RBW * 16);  // consecutive threads -> consecutive rows
+        const int r = nl >> 4, nn = nl & 15;
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < NWK; ++k) s += sm.red[k][r][nn * 16 + m];
+        const int64_t row = (rb0 + r) * 16 + nn;
+        if (m < M && row < N) {
+            if constexpr (BITS == 1) {
+                float sx = 0.f;
+#pragma unroll
+                for (int k = 0; k < NWK; ++k) sx += sm.redx[k][m];
+                const float c0 = bf16_to_f32(codebook[row * 2]), c1 = bf16_to_f32(codebook[row * 2 + 1]);
+                s = fmaf(c1 - c0, s, c0 * sx);
+            }
+            Y[static_cast<int64_t>(m) * N + row] = f32_to_bf16(s);
+        }
+    }
+}
+
+// ---- launch ------------------------------------------------------------------------------------
+
+template <int BITS, int NWK, int RBW>
+static void launch_mfma_one(const GemmArgs& a, hipStream_t s) {
+    const int64_t nrb = (a.N + 15) / 16;
+    const dim3 grid(static_cast<unsigned>((nrb + RBW - 1) / RBW)), block(NWK * 64);
+    hipLaunchKernelGGL((gemm_mfma_kernel<BITS, NWK, RBW>), grid, block, 0, s,
+                       a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M);
+}
+
+template <int BITS>
+static void launch_mfma_bits(const GemmArgs& a, int nwk, int rbw, hipStream_t s) {
+    if (rbw == 2) {
+        switch (nwk) {
+            case 8: launch_mfma_one<BITS, 8, 2>(a, s); break;
+            case 4: launch_mfma_one<BITS, 4, 2>(a, s); break;
+            case 2: launch_mfma_one<BITS, 2, 2>(a, s); break;
+            default: launch_mfma_one<BITS, 1, 2>(a, s); break;
+        }
+    } else {
+        switch (nwk) {
+            case 8: launch_mfma_one<BITS, 8, 1>(a, s); break;
+            case 4: launch_mfma_one<BITS, 4, 1>(a, s); break;
+            case 2: launch_mfma_one<BITS, 2, 1>(a, s); break;
+            default: launch_mfma_one<BITS, 1, 1>(a, s); break;
+        }
+    }
+}
+
+// Waves along K: the largest of 8, 4, 2, 1 that divides the number of super-blocks.
+int mfma_waves_along_k(int64_t K, int bits) {
+    const int64_t nsb = K / tiled_superblock_elems(bits);
+    for (int w = 8; w > 1; w >>= 1)
+        if (nsb % w == 0) return w;
+    return 1;
+}
+
+// Row blocks per workgroup: two when that still leaves at least two workgroups per CU.
+int mfma_row_blocks(int64_t N) { return (N + 15) / 16 >= 4 * 256 ? 2 : 1; }
+
+hipError_t launch_mfma(const GemmArgs& a, hipStream_t s) {
+    const int nwk = mfma_waves_along_k(a.K, a.bits), rbw = mfma_row_blocks(a.N);
+    switch (a.bits) {
+        case 1: launch_mfma_bits<1>(a, nwk, rbw, s); break;
+        case 2: launch_mfma_bits<2>(a, nwk, rbw, s); break;
+        case 3: launch_mfma_bits<3>(a, nwk, rbw, s); break;
+        default: launch_mfma_bits<4>(a, nwk, rbw, s); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace kmq

@@ -65,20 +65,34 @@ def test_repack_is_a_reversible_permutation(bits, N):
     wpr = kmq.words_per_row(bits, K)
     assert t.size == -(-N // 16) * 16 * wpr == kmq.tiled_words(N, K, bits, 1)
     assert np.array_equal(kmq.unrepack(t, N, K, bits, kmq.LAYOUT_TILED), p)
-    # the documented index formula
-    for (n, w) in [(0, 0), (N - 1, wpr - 1), (N // 2, 5), (N - 1, 4)]:
-        rb, r, cb, j = n // 16, n % 16, w // 4, w % 4
-        assert t[((rb * (wpr // 4) + cb) * 16 + r) * 4 + j] == p[n, w]
-    # same multiset of words (plus zero padding of the short last block)
-    assert np.array_equal(np.sort(t)[t.size - p.size:], np.sort(p.ravel())) or N % 16
+    # the documented byte formula: groups of 8 elements (= `bits` bytes) move as units
+    gpg = {1: 16, 2: 8, 3: 4, 4: 4}[bits]
+    gb, nsb = gpg * bits, K // (32 * gpg)
+    tb = t.view(np.uint8)
+    cb = np.ascontiguousarray(p).view(np.uint8).reshape(N, -1)
+    for _ in range(200):
+        n = int(g.integers(0, N))
+        grp = int(g.integers(0, K // 8))                 # group index along the row
+        sb, gi = divmod(grp, 4 * gpg)
+        q, j = gi % 4, gi // 4
+        rb, nn = divmod(n, 16)
+        off = ((rb * nsb + sb) * 64 + q * 16 + nn) * gb + j * bits
+        assert np.array_equal(tb[off:off + bits], cb[n, grp * bits:(grp + 1) * bits])
+    # rows of a short last block are zero
+    if N % 16:
+        rb, nn = divmod(N, 16)                            # first missing row
+        off = ((rb * nsb) * 64 + nn) * gb
+        assert not tb[off:off + gb].any()
     assert np.array_equal(kmq.repack(p, K, bits, kmq.LAYOUT_CANONICAL).reshape(N, wpr), p)
 
 
-def test_repack_rejects_rows_that_are_not_whole_column_blocks():
-    idx = np.zeros((4, 33), dtype=np.uint8)          # 2-bit: 3 words per row
-    p = kmq.pack(idx, 2)
+@pytest.mark.parametrize("bits,K", [(1, 256), (2, 128), (3, 64), (4, 96), (2, 33)])
+def test_repack_rejects_k_that_is_not_whole_superblocks(bits, K):
+    idx = np.zeros((4, K), dtype=np.uint8)
+    p = kmq.pack(idx, bits)
+    assert kmq.tiled_words(4, K, bits, kmq.LAYOUT_TILED) == -1
     with pytest.raises(kmq.KmqError) as e:
-        kmq.repack(p, 33, 2, kmq.LAYOUT_TILED)
+        kmq.repack(p, K, bits, kmq.LAYOUT_TILED)
     assert e.value.status == 7
 
 
@@ -103,7 +117,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert gemv(N=0) == 3 and gemv(K=0) == 3 and gemv(N=-1) == 3 and gemv(K=1 << 30) == 3
     assert gemm(0) == 3 and gemm(17) == 3
     assert gemv(layout=2) == 7 and gemv(layout=-1) == 7
-    assert gemv(K=40, layout=1) == 7                  # 2-bit K=40: 3 words per row, not tileable
+    assert gemv(K=40, layout=1) == 7                  # 2-bit K=40 is not a whole number of 256-element super-blocks
     assert gemv(W=W + 4) == 4 and gemv(x=x + 2) == 4 and gemv(cb=cb + 2) == 4 and gemv(y=y + 1) == 4
     assert lib.kmq_dequant(None, cb, y, 4, 64, 2, 0, None) == 1
     assert lib.kmq_dequant(W, cb, y, 4, 64, 7, 0, None) == 2
@@ -122,3 +136,5 @@ def test_heuristic_names():
     assert kmq.kernel_name(2048, 2048, 1, 1).startswith("lut_b1")
     assert kmq.kernel_name(4096, 4096, 3, 1).startswith("rowsplit_b3")
     assert kmq.kernel_name(77, 515, 2, 1) == "generic"
+    assert kmq.kernel_name(4096, 4096, 3, 16, kmq.LAYOUT_TILED) == "mfma_b3"
+    assert kmq.kernel_name(4096, 4000, 3, 16, kmq.LAYOUT_TILED) == "invalid"

@@ -36,8 +36,8 @@ def test_dequant_bit_exact(gpu, bits, layout, N, K):
     idx, cb, _ = _small_case(bits * 100 + N + K, N, K, bits, 1)
     p = kmq.pack(idx, bits)
     if layout == 1:
-        if kmq.words_per_row(bits, K) % 4:
-            pytest.skip("tiled layout needs words-per-row % 4 == 0")
+        if kmq.tiled_words(N, K, bits, 1) < 0:
+            pytest.skip("tiled layout needs K to be whole super-blocks")
         stored = kmq.repack(p, K, bits, 1)
     else:
         stored = p
@@ -60,14 +60,49 @@ def test_generic_shapes_vs_oracle(gpu, bits, M, N, K):
 
 
 @pytest.mark.parametrize("bits", BITS)
-@pytest.mark.parametrize("N,K", [(130, 1024), (48, 4096)])
-def test_tiled_layout_vs_oracle(gpu, bits, N, K):
+@pytest.mark.parametrize("N,K", [(1, 512), (15, 1024), (17, 1024), (33, 1536), (130, 1024), (48, 4096), (300, 3072)])
+@pytest.mark.parametrize("M", (1, 2, 5, 8, 13, 16))
+def test_tiled_layout_mfma_vs_oracle(gpu, bits, N, K, M):
+    """The matrix-core kernel: every batch size, ragged row counts (short last
+    16-row block), K with 1, 2, 3, 4, 6, 8 super-blocks per wave split."""
     from paper_2602_15563_amd import kmq
-    for M in (1, 8):
-        idx, cb, X = _small_case(11 * bits + N + M, N, K, bits, M)
-        p = kmq.pack(idx, bits)
-        Yg = gpu.run_gemm(gpu.dev(kmq.repack(p, K, bits, 1)), gpu.dev(cb), X, N, K, bits, layout=1)
-        gpu.check_against_oracle(Yg, oracle.pack(idx, bits), cb, X, K, bits, label=f"tiled b{bits} M{M}")
+    idx, cb, X = _small_case(11 * bits + N + M + K, N, K, bits, M)
+    p = kmq.pack(idx, bits)
+    assert kmq.kernel_name(N, K, bits, M, 1).startswith("mfma")
+    Yg = gpu.run_gemm(gpu.dev(kmq.repack(p, K, bits, 1)), gpu.dev(cb), X, N, K, bits, layout=1, use_gemv=(M == 1))
+    gpu.check_against_oracle(Yg, oracle.pack(idx, bits), cb, X, K, bits, label=f"tiled b{bits} {N}x{K} M{M}")
+
+
+@pytest.mark.parametrize("bits", (2, 3, 4))
+def test_tiled_one_hot_batch16_probe_is_bit_exact(gpu, bits):
+    from paper_2602_15563_amd import kmq
+    N, K = 40, 1024
+    idx, cb, _ = _small_case(3 * bits, N, K, bits, 1)
+    p = kmq.pack(idx, bits)
+    Wd = oracle.dequant(oracle.pack(idx, bits), cb, K, bits)
+    pd, cd = gpu.dev(kmq.repack(p, K, bits, 1)), gpu.dev(cb)
+    for k0 in (0, 8, 24, 100, 511, K - 16):
+        X = np.zeros((16, K), dtype=np.uint16)
+        for m in range(16):
+            X[m, k0 + m] = 0x3F80
+        Yg = gpu.run_gemm(pd, cd, X, N, K, bits, layout=1)
+        assert np.array_equal(Yg, Wd[:, k0:k0 + 16].T.copy()), f"k0={k0}"
+
+
+@pytest.mark.parametrize("cfg", (3, 4))
+def test_contract_configs_tiled(gpu, cfg):
+    """The small-batch configurations at full size on the tiled layout (the
+    launch configuration bench.py times for batch > 1)."""
+    from paper_2602_15563_amd import kmq
+    for case in synth.cases(cfg):
+        idx, cb, X = case.tensors()
+        p = kmq.pack(idx, case.bits)
+        t = kmq.repack(p, case.K, case.bits, 1)
+        assert np.array_equal(kmq.unrepack(t, case.N, case.K, case.bits, 1), p)
+        Yg = gpu.run_gemm(gpu.dev(t), gpu.dev(cb), X, case.N, case.K, case.bits, layout=1, use_gemv=False)
+        ranges = gpu.sample_ranges(case.N, case.seed + case.matrix)
+        worst = gpu.check_against_oracle(Yg, p, cb, X, case.K, case.bits, ranges, label=case.name)
+        print(f"{case.name}: kernel={kmq.kernel_name(case.N, case.K, case.bits, case.M, 1)} max err/A={worst:.2e}")
 
 
 FAST_SHAPES = [(1, 2048), (1, 3072), (1, 4096), (1, 8192), (2, 2048), (2, 3072), (2, 4096), (2, 8192),
