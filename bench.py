@@ -46,6 +46,7 @@ WORKLOADS = {
     "cfg4_down_b1_3072x8192_m16": (1, 3072, 8192, 16, 4, 4, True),
 }
 HEADLINE = "cfg2_gateup_b2_14336x4096_m1"
+TRAFFIC_SUMMARIES = {HEADLINE: "gemv_b2_14336x4096_m1_pmc_traffic.txt"}
 
 
 def _dev(a):
@@ -171,6 +172,47 @@ def time_workload(inst: Instances, steps: int, warmup: int, use_graph: bool = Tr
     return e0.elapsed_time(e1) * 1e-3, steps
 
 
+def time_read_ceiling(inst: Instances, steps: int):
+    """Pure read of the same packed index streams (same rotation, same graph replay)."""
+    import torch
+
+    from paper_2602_15563_amd import kmq
+    stream = torch.cuda.Stream()
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    with torch.cuda.stream(stream):
+        for i in range(20):
+            kmq.stream_read(inst.W[i % inst.R], sink)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(CALLS_PER_GRAPH):
+                kmq.stream_read(inst.W[i % inst.R], sink)
+        graph.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = max(1, steps // CALLS_PER_GRAPH)
+        e0.record(stream)
+        for _ in range(n):
+            graph.replay()
+        e1.record(stream)
+        stream.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (n * CALLS_PER_GRAPH)
+    nbytes = inst.W[0].numel() * 4
+    return {"us_per_call": round(us, 3), "GB/s": round(nbytes / us * 1e-3, 1), "bytes": nbytes,
+            "what": "kmq_stream_read over the same rotating index streams (reads only, no decode)"}
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", TRAFFIC_SUMMARIES.get(workload, "_none_"))
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch"):
+            return int(line.split("=")[1])
+    return None
+
+
 def cpu_baseline(inst: Instances):
     """The oracle, as it stands, single-threaded, on the same matrix."""
     import oracle
@@ -202,6 +244,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--layout", type=int, default=None, choices=(0, 1),
                     help="0 canonical, 1 tiled (default: canonical for batch 1, tiled for batch > 1)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="before the timed region, launch a plain 64 MiB device copy 10 times: a kernel of known "
+                         "traffic against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
     ap.add_argument("--table", action="store_true", help="also time every contract shape -> gpurun_out/bench_table.json")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -216,6 +261,12 @@ def main():
 
     inst = Instances(args.workload, rotate=not args.no_rotate, layout=args.layout)
     worst = inst.check()
+    if args.calibrate_copy:
+        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").random_()
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     secs, steps = time_workload(inst, args.steps, args.warmup, use_graph=not args.no_graph)
     us = secs / steps * 1e6
     gbs = inst.bytes / (secs / steps) / 1e9
@@ -232,10 +283,11 @@ def main():
                    "rotating_instances": inst.R, "hip_graph": not args.no_graph,
                    "algorithmic_bytes_per_call": inst.bytes, "max_err_over_A_vs_oracle": float(f"{worst:.3e}")},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.workload),
                      "note": "achieved = algorithmic bytes per launch / average launch-to-launch time "
                              "(HIP events on the launch stream around the timed region)"},
     }
+    out["roofline"]["read_ceiling"] = time_read_ceiling(inst, min(steps, 5000))
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(inst)
 

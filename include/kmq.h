@@ -128,6 +128,14 @@ kmq_status kmq_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd
  * (static string, never NULL; "invalid" on bad arguments).  For reports. */
 const char* kmq_kernel_name(int64_t N, int64_t K, int bits, int M, int layout);
 
+/* Measurement aid (paper App. E: effective bandwidth is judged against what the
+ * memory system can deliver): reads `bytes` (>= 16, rounded down to 16) of DEVICE
+ * memory at `data` (16-byte aligned) once, with the access shape of the GEMV
+ * kernels, and discards them.  Gives the time a pure read of the same size
+ * takes on this machine.  `sink` (device, 4 bytes, may be NULL) is never written
+ * in practice; it only keeps the loads alive. */
+kmq_status kmq_stream_read(const void* data, size_t bytes, void* sink, void* hip_stream);
+
 const char* kmq_status_string(kmq_status s);
 
 /* Text the HIP runtime gave for the last KMQ_ERR_HIP on the calling thread

@@ -100,6 +100,13 @@ kmq_status kmq_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd
     return kmq::hip_status(e);
 }
 
+kmq_status kmq_stream_read(const void* data, size_t bytes, void* sink, void* hip_stream) {
+    if (!data) return KMQ_ERR_NULL;
+    if (bytes < 16 || bytes > (size_t(1) << 40)) return KMQ_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(data) & 15) return KMQ_ERR_ALIGN;
+    return kmq::hip_status(kmq::launch_stream_read(data, bytes, sink, static_cast<hipStream_t>(hip_stream)));
+}
+
 const char* kmq_last_hip_error(void) { return kmq::g_last_hip_error; }
 
 }  // extern "C"

@@ -47,6 +47,8 @@ int rowsplit_find(int64_t K, int bits, int layout);
 const char* rowsplit_name(int table_index);
 hipError_t launch_rowsplit(int table_index, const GemmArgs& a, hipStream_t s);
 
+hipError_t launch_stream_read(const void* p, size_t bytes, void* sink, hipStream_t s);
+
 // Matrix-core kernel (tiled layout only).
 hipError_t launch_mfma(const GemmArgs& a, hipStream_t s);
 int mfma_waves_along_k(int64_t K, int bits);

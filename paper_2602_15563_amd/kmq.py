@@ -60,6 +60,8 @@ _lib.kmq_dequant.restype = ctypes.c_int32
 _lib.kmq_dequant.argtypes = [_vp, _vp, _vp, _i64, _i64, _int, _int, _vp]
 _lib.kmq_kernel_name.restype = ctypes.c_char_p
 _lib.kmq_kernel_name.argtypes = [_i64, _i64, _int, _int, _int]
+_lib.kmq_stream_read.restype = ctypes.c_int32
+_lib.kmq_stream_read.argtypes = [_vp, _sz, _vp, _vp]
 _lib.kmq_last_hip_error.restype = ctypes.c_char_p
 _lib.kmq_last_hip_error.argtypes = []
 _lib.kmq_status_string.restype = ctypes.c_char_p
@@ -175,3 +177,8 @@ def gemm_smallbatch(W, codebook, X, Y, N: int, K: int, M: int, bits: int, layout
 def dequant(W, codebook, Wdense, N: int, K: int, bits: int, layout: int = 0):
     """Wdense[N][K] (bf16 storage) = codebook[n][idx[n][k]] on torch's current stream."""
     _check(_lib.kmq_dequant(_ptr(W), _ptr(codebook), _ptr(Wdense), N, K, bits, layout, _stream()))
+
+
+def stream_read(t, sink=None):
+    """Read a device tensor once and discard it (read-ceiling probe) on torch's current stream."""
+    _check(_lib.kmq_stream_read(_ptr(t), t.numel() * t.element_size(), _ptr(sink), _stream()))
