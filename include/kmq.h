@@ -68,25 +68,33 @@ kmq_status kmq_pack(const uint8_t* idx, int64_t N, int64_t K, int bits, uint32_t
 /* Inverse of kmq_pack (host pointers).  Pad bits of `packed` are ignored. */
 kmq_status kmq_unpack(const uint32_t* packed, int64_t N, int64_t K, int bits, uint8_t* idx);
 
-/* Host, offline, integer only, reversible: permutes the words of the canonical
- * stream into the tile order named by `layout` (same number of words in and
- * out; kmq_unrepack(kmq_repack(P)) == P with pad bits as given).  Motivated by
+/* Host, offline, integer only, reversible: permutes the index bits of the
+ * canonical stream into the order named by `layout` (kmq_unrepack(kmq_repack(P))
+ * == P).  Motivated by
  * the paper's remark (App. E, "Micro-benchmarks: Results") that custom code with
  * an optimised data layout is the route to faster low-bit kernels.
  *
- * KMQ_LAYOUT_TILED is the operand order of the matrix-core kernels.  The unit
- * that moves is a GROUP: 8 consecutive elements of a row, i.e. `bits` whole
- * bytes of the canonical stream (bit order inside a group is unchanged).  Let
- * gpg = 16, 8, 4, 4 groups for bits = 1, 2, 3, 4.  K is cut into super-blocks of
- * 4*gpg groups (512, 256, 128, 128 elements) and rows into blocks of 16 (the
- * last block may be short; its missing rows are zero).  The GRANULE (rb, sb, q, n)
- * holds, in order j = 0..gpg-1, the groups q + 4j of super-block sb of row
- * 16*rb + n; it is gpg*bits bytes (16, 16, 12, 16) and lives at byte offset
- *     ((rb * nsb + sb) * 64 + q*16 + n) * gpg*bits,      nsb = K / (32*gpg),
+ * KMQ_LAYOUT_TILED is the operand order of the matrix-core kernels.  A GROUP is
+ * 8 consecutive elements of a row.  Let gpg = 16, 8, 4, 4 groups for bits = 1, 2,
+ * 3, 4.  K is cut into super-blocks of 4*gpg groups (512, 256, 128, 128 elements)
+ * and rows into blocks of 16 (the last block may be short; its missing rows are
+ * zero).  The GRANULE (rb, sb, q, n) holds the groups q + 4j, j = 0..gpg-1, of
+ * super-block sb of row 16*rb + n; it is gw = gpg*bits/4 dwords (4, 4, 3, 4) at
+ * dword offset
+ *     ((rb * nsb + sb) * 64 + q*16 + n) * gw,      nsb = K / (32*gpg),
  * so one 64-lane load of consecutive granules is 16 rows x one super-block, and
- * lane (n, q) of a 16x16x32 matrix-core step j reads columns 8*(q+4j)..+7 of both
- * operands.  Requires K % (32*gpg) == 0 (else KMQ_ERR_LAYOUT).  `tiled` holds
- * ceil(N/16)*16 * wpr words: size it with kmq_tiled_words(). */
+ * lane (n, q) of 16x16x32 matrix-core step j owns columns 8*(q+4j)..+7 of both
+ * operands.  Inside a granule (bit positions count through its dwords, LSB
+ * first), bit t of the index of element e (0..7) of step j sits at
+ *     bits = 1:  8*j + e                               (groups in order, one byte each)
+ *     bits = 4:  32*j + 4*e + t                        (groups in order, one dword each)
+ *     bits = 2:  32*(c/4) + 8*(e%4) + 2*(c%4) + t,     c = 2*j + e/4
+ *     bits = 3:  t < 2:  32*(e/4) + 8*(e%4) + 2*j + t
+ *                t = 2:  64 + 8*(e%4) + 2*j + e/4
+ * The 2- and 3-bit orders spread the fields so that one shift and one AND leave
+ * four indices in the four bytes of a register.  Requires K % (32*gpg) == 0
+ * (else KMQ_ERR_LAYOUT).  Same size as the canonical stream with rows padded
+ * to 16: size `tiled` with kmq_tiled_words(). */
 kmq_status kmq_repack(const uint32_t* canonical, int64_t N, int64_t K, int bits, int layout,
                       uint32_t* tiled);
 kmq_status kmq_unrepack(const uint32_t* tiled, int64_t N, int64_t K, int bits, int layout,

@@ -54,16 +54,18 @@ __device__ __forceinline__ float group_sum(float v) {
     return v;
 }
 
-// 32-bit word `w` of row `n` of the canonical stream, read from either layout.
-// In the tiled layout the four bytes of a canonical word need not be adjacent.
-__device__ __forceinline__ uint32_t fetch_word(const uint32_t* W, int layout, int bits, int64_t K,
-                                               int64_t n, int64_t w, int64_t wpr) {
-    if (layout == KMQ_LAYOUT_CANONICAL) return W[n * wpr + w];
-    const uint8_t* b = reinterpret_cast<const uint8_t*>(W);
+// Index of element k of row n read from the tiled stream (slow path: used by the
+// shape-agnostic kernels only).
+__device__ __forceinline__ uint32_t tiled_fetch_index(const uint32_t* W, int bits, int64_t K, int64_t n, int64_t k) {
+    const int gpg = tiled_groups_per_granule(bits);
+    const int64_t g = (k % (32 * gpg)) / 8;
+    const int j = static_cast<int>(g / 4), e = static_cast<int>(k % 8);
+    const uint32_t* gr = W + tiled_granule_dword(bits, K, n, k);
     uint32_t v = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        v |= static_cast<uint32_t>(b[tiled_byte_index(bits, K, n, w * 4 + i)]) << (8 * i);
+    for (int t = 0; t < bits; ++t) {
+        const int tp = tiled_bit_position(bits, j, e, t);
+        v |= ((gr[tp >> 5] >> (tp & 31)) & 1u) << t;
+    }
     return v;
 }
 

@@ -46,17 +46,21 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
     for (int m = 0; m < MT; ++m) acc[m] = 0.f;
 
     for (int64_t g = lane; g < ngroups; g += kWave) {
-        uint32_t w[BITS];
-#pragma unroll
-        for (int j = 0; j < BITS; ++j) {
-            const int64_t wi = g * BITS + j;
-            w[j] = wi < wpr ? fetch_word(W, layout, BITS, K, n, wi, wpr) : 0u;
-        }
         const int64_t k0 = g << 5;
         const bool full = k0 + 32 <= K;
         float wt[32];
+        if (layout == KMQ_LAYOUT_CANONICAL) {
+            uint32_t w[BITS];
 #pragma unroll
-        for (int e = 0; e < 32; ++e) wt[e] = lut[wave][group_field<BITS>(w, e)];
+            for (int j = 0; j < BITS; ++j) {
+                const int64_t wi = g * BITS + j;
+                w[j] = wi < wpr ? W[n * wpr + wi] : 0u;
+            }
+#pragma unroll
+            for (int e = 0; e < 32; ++e) wt[e] = lut[wave][group_field<BITS>(w, e)];
+        } else {
+            for (int e = 0; e < 32; ++e) wt[e] = lut[wave][tiled_fetch_index(W, BITS, K, n, k0 + e)];   // K % 128 == 0 here
+        }
         if (full && vec_x) {
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
@@ -107,7 +111,7 @@ __global__ __launch_bounds__(256) void dequant_kernel(
 #pragma unroll
         for (int j = 0; j < BITS; ++j) {
             const int64_t wi = g * BITS + j;
-            w[j] = wi < wpr ? fetch_word(W, layout, BITS, K, n, wi, wpr) : 0u;
+            w[j] = (layout == KMQ_LAYOUT_CANONICAL && wi < wpr) ? W[n * wpr + wi] : 0u;
         }
         uint16_t c[C];
 #pragma unroll
@@ -115,7 +119,8 @@ __global__ __launch_bounds__(256) void dequant_kernel(
         const int64_t k0 = g << 5;
 #pragma unroll
         for (int e = 0; e < 32; ++e) {
-            const uint32_t f = group_field<BITS>(w, e);
+            const uint32_t f = layout == KMQ_LAYOUT_CANONICAL ? group_field<BITS>(w, e)
+                                                              : tiled_fetch_index(W, BITS, K, n, k0 + e);
             uint16_t v = c[0];
 #pragma unroll
             for (int j = 1; j < C; ++j) v = f == static_cast<uint32_t>(j) ? c[j] : v;

@@ -91,19 +91,32 @@ static kmq_status repack_impl(const uint32_t* src, int64_t N, int64_t K, int bit
         return KMQ_OK;
     }
     if (layout != KMQ_LAYOUT_TILED || !kmq::tiled_valid(bits, K)) return KMQ_ERR_LAYOUT;
-    const int64_t row_bytes = wpr * 4;              // K*bits/8 exactly: K is a multiple of 128
     const int64_t nrows_padded = kmq::round_up(N, kmq::kTileRows);
-    const uint8_t* s8 = reinterpret_cast<const uint8_t*>(src);
-    uint8_t* d8 = reinterpret_cast<uint8_t*>(dst);
-    if (forward) std::memset(dst, 0, static_cast<size_t>(nrows_padded * row_bytes));
-    // groups of `bits` bytes move as a unit
-    for (int64_t n = 0; n < N; ++n)
-        for (int64_t g0 = 0; g0 < row_bytes; g0 += bits) {
-            const int64_t t = kmq::tiled_byte_index(bits, K, n, g0);
-            const int64_t c = n * row_bytes + g0;
-            if (forward) std::memcpy(d8 + t, s8 + c, static_cast<size_t>(bits));
-            else         std::memcpy(d8 + c, s8 + t, static_cast<size_t>(bits));
+    if (forward) std::memset(dst, 0, static_cast<size_t>(nrows_padded * wpr) * sizeof(uint32_t));
+    else         std::memset(dst, 0, static_cast<size_t>(N * wpr) * sizeof(uint32_t));
+    const uint32_t* canon = forward ? src : dst;
+    uint32_t* canon_out = forward ? nullptr : dst;
+    const uint32_t* tiled_in = forward ? nullptr : src;
+    uint32_t* tiled_out = forward ? dst : nullptr;
+    const int gpg = kmq::tiled_groups_per_granule(bits);
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t k = 0; k < K; ++k) {
+            const int64_t g = (k % (32 * gpg)) / 8;
+            const int j = static_cast<int>(g / 4), e = static_cast<int>(k % 8);
+            const int64_t gd = kmq::tiled_granule_dword(bits, K, n, k);
+            for (int t = 0; t < bits; ++t) {
+                const int64_t cp = k * bits + t;                       // canonical stream bit of this row
+                const int tp = kmq::tiled_bit_position(bits, j, e, t);
+                if (forward) {
+                    const uint32_t bit = (canon[n * wpr + (cp >> 5)] >> (cp & 31)) & 1u;
+                    tiled_out[gd + (tp >> 5)] |= bit << (tp & 31);
+                } else {
+                    const uint32_t bit = (tiled_in[gd + (tp >> 5)] >> (tp & 31)) & 1u;
+                    canon_out[n * wpr + (cp >> 5)] |= bit << (cp & 31);
+                }
+            }
         }
+    }
     return KMQ_OK;
 }
 

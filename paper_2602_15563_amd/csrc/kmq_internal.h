@@ -19,26 +19,44 @@ constexpr int64_t kTileRows = 16;               // KMQ_LAYOUT_TILED: rows per bl
 inline bool bits_valid(int bits) { return bits >= 1 && bits <= 4; }
 inline bool dims_valid(int64_t N, int64_t K) { return N >= 1 && K >= 1 && N <= kMaxDim && K <= kMaxDim; }
 KMQ_HD inline int64_t words_per_row(int bits, int64_t K) { return (K * bits + 31) >> 5; }
+inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
 // KMQ_LAYOUT_TILED (see include/kmq.h).  A group is 8 consecutive elements of a
-// row = `bits` bytes of the canonical stream; a granule is the `gpg` groups
-// {q, q+4, q+8, ...} of one super-block (4*gpg groups) of one row.
+// row; a granule is the `gpg` groups {q, q+4, q+8, ...} of one super-block
+// (4*gpg groups) of one row, stored as gpg*bits/4 dwords.
 KMQ_HD inline int tiled_groups_per_granule(int bits) { return bits == 1 ? 16 : bits == 2 ? 8 : 4; }
 KMQ_HD inline int64_t tiled_superblock_elems(int bits) { return 32 * tiled_groups_per_granule(bits); }
 KMQ_HD inline bool tiled_valid(int bits, int64_t K) { return K % tiled_superblock_elems(bits) == 0; }
-// Byte offset in the tiled stream of canonical byte `byte_in_row` of row n.
-KMQ_HD inline int64_t tiled_byte_index(int bits, int64_t K, int64_t n, int64_t byte_in_row) {
+
+// Dword offset in the tiled stream of the granule that holds element k of row n.
+KMQ_HD inline int64_t tiled_granule_dword(int bits, int64_t K, int64_t n, int64_t k) {
     const int64_t gpg = tiled_groups_per_granule(bits);
-    const int64_t gb = gpg * bits;                 // bytes per granule
-    const int64_t sbb = 4 * gb;                    // bytes per super-block and row
-    const int64_t nsb = (K * bits / 8) / sbb;
-    const int64_t sb = byte_in_row / sbb, r = byte_in_row % sbb;
-    const int64_t g = r / bits, o = r % bits;
-    const int64_t q = g % 4, j = g / 4;
+    const int64_t gw = gpg * bits / 4;             // dwords per granule
+    const int64_t sbe = 32 * gpg;
+    const int64_t nsb = K / sbe;
+    const int64_t sb = k / sbe, g = (k % sbe) / 8, q = g % 4;
     const int64_t rb = n / kTileRows, nn = n % kTileRows;
-    return ((rb * nsb + sb) * 64 + q * 16 + nn) * gb + j * bits + o;
+    return ((rb * nsb + sb) * 64 + q * 16 + nn) * gw;
 }
-inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+
+// Inside a granule: bit position (0 .. 32*gw-1, dword-major) of bit t of the index
+// of element e (0..7) of step j (0..gpg-1).  1- and 4-bit granules keep the
+// canonical order of their groups; 2- and 3-bit granules spread the fields so
+// that one shift and one AND put four indices into the four bytes of a register
+// (a v_perm_b32 selector).
+KMQ_HD inline int tiled_bit_position(int bits, int j, int e, int t) {
+    switch (bits) {
+        case 1: return 8 * j + e;
+        case 4: return 32 * j + 4 * e + t;
+        case 2: {
+            const int c = 2 * j + e / 4, k = e % 4;
+            return 32 * (c / 4) + 8 * k + 2 * (c % 4) + t;
+        }
+        default:  // 3: two low bits in dwords 0/1, high bit in dword 2
+            if (t < 2) return 32 * (e / 4) + 8 * (e % 4) + 2 * j + t;
+            return 64 + 8 * (e % 4) + 2 * j + e / 4;
+    }
+}
 
 }  // namespace kmq
 

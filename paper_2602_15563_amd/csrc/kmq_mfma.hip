@@ -13,15 +13,22 @@
 // super-block, and the activation loads of a step cover 64 contiguous bytes of
 // each batch row.
 //
-// Dequantisation per step and lane: 8 lookups in the lane's row codebook (bf16
-// entries in LDS, 16 B per row so that the 16 rows of a block tile the 64 banks),
-// combined pairwise into 4 VGPRs.  1-bit needs no per-row table: the A operand
-// is the {0,1} mask of the bits (row-independent nibble table), a second MFMA
-// with an all-ones A operand accumulates sum_k x, and the epilogue applies the
-// two-centroid closed form y = c0*sum(x) + (c1 - c0)*sum_{idx=1} x.
+// Dequantisation per step and lane (8 weights -> 4 VGPRs of bf16 pairs):
+//   2/3-bit  the lane's row codebook (8 or 16 bytes) lives in VGPRs, split into a
+//            low-byte and a high-byte pool; the tiled granule stores the index
+//            fields spread so that one shift + AND yields four indices in the
+//            four bytes of a register, which is a v_perm_b32 selector: two byte
+//            gathers (low, high) and two interleaves per four weights, no LDS;
+//   4-bit    16 centroids do not fit a perm pool: bf16 table per row in LDS;
+//   1-bit    no per-row table: the A operand is the {0,1} mask of the bits
+//            (row-independent nibble table in LDS), a second MFMA with an all-ones
+//            A operand accumulates sum_k x, and the epilogue applies the closed
+//            form y = c0*sum(x) + (c1 - c0)*sum_{idx=1} x.
 //
 // A workgroup is NWK waves that split K (whole super-blocks each) for RBW blocks
 // of 16 rows; partial 16x16 tiles are summed through LDS in a fixed order.
+#include <cstdlib>
+
 #include "kmq_device.h"
 #include "kmq_launch.h"
 
@@ -47,20 +54,11 @@ __device__ __forceinline__ void load_granule(const uint32_t* p, uint32_t (&g)[GW
     }
 }
 
-// The `bits`*8 index bits of group j of a granule, in the low bits of the result.
+// 1- and 4-bit granules: the bits*8 index bits of group j, in the low bits of the result.
 template <int BITS, int GW>
 __device__ __forceinline__ uint32_t group_bits(const uint32_t (&g)[GW], int j) {
     if constexpr (BITS == 4) return g[j];
-    if constexpr (BITS == 2) return (g[j >> 1] >> (16 * (j & 1))) & 0xFFFFu;
     if constexpr (BITS == 1) return (g[j >> 2] >> (8 * (j & 3))) & 0xFFu;
-    if constexpr (BITS == 3) {
-        switch (j) {
-            case 0: return g[0];
-            case 1: return __builtin_amdgcn_alignbit(g[1], g[0], 24);
-            case 2: return __builtin_amdgcn_alignbit(g[2], g[1], 16);
-            default: return g[2] >> 8;
-        }
-    }
     return 0;
 }
 
@@ -73,8 +71,9 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     constexpr int THREADS = NWK * 64;
 
     struct alignas(256) Smem {
-        uint16_t tbl[BITS == 1 ? 1 : RBW * 16][BITS == 1 ? 8 : (C < 8 ? 8 : C)];   // 16 B (32 B for 4-bit) per row
+        uint16_t tbl[BITS == 4 ? RBW * 16 : 1][16];         // 4-bit: bf16 codebook rows
         u32x2_t masks[16];                                  // 1-bit: nibble -> four bf16 {0,1}
+        u32x4_t xstage[NWK][16 * 17];                       // per wave: 16 batch rows x (16 + 1 pad) 16-byte pieces
         float red[NWK][RBW][256];                           // partial tiles, [n][m]
         float redx[BITS == 1 ? NWK : 1][16];                // 1-bit: partial sum_k x per batch column
     };
@@ -97,7 +96,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
             m[1] = ((e & 4u) ? 0x3F80u : 0u) | ((e & 8u) ? 0x3F800000u : 0u);
             sm.masks[e] = m;
         }
-    } else {
+    } else if constexpr (BITS == 4) {
         for (int i = threadIdx.x; i < RBW * 16 * C; i += THREADS) {
             const int r = i / C, e = i % C;
             int64_t row = (rb0 + r / 16) * 16 + (r % 16);
@@ -124,51 +123,117 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     }
     __syncthreads();
 
-    // activations: lane (m = n, q) reads 16 bytes at X[m][sb*SBE + 8*(q + 4j)]
-    const int mrow = n < M ? n : M - 1;                     // columns >= M are computed and dropped
-    const uint16_t* xlane = X + static_cast<int64_t>(mrow) * K + static_cast<int64_t>(sb0) * SBE + 8 * q;
+    // Activations of a chunk (16 batch rows x 128 columns) go through a wave-private LDS
+    // tile: global loads take 256 contiguous bytes per row (rows of X are K*2 bytes apart,
+    // so gathering 16 rows x 64 bytes per instruction thrashes one memory channel), and
+    // lane (m = n, q) then reads the 16 bytes of columns 8*(q + 4i)..+7 for step i.
+    // Batch columns >= M are fed row M-1 and dropped at the end.
+    const uint16_t* xsrc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int m = 4 * i + q;
+        m = m < M ? m : M - 1;
+        xsrc[i] = X + static_cast<int64_t>(m) * K + static_cast<int64_t>(sb0) * SBE + 8 * n;
+    }
+    u32x4_t* xtile = &sm.xstage[wk][0];
 
     f32x4_t acc[RBW];
 #pragma unroll
     for (int r = 0; r < RBW; ++r) acc[r] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     [[maybe_unused]] f32x4_t accx = f32x4_t{0.f, 0.f, 0.f, 0.f};
     [[maybe_unused]] const uint16_t* trow[RBW];
-    if constexpr (BITS != 1) {
+    [[maybe_unused]] uint32_t lo0[RBW], lo1[RBW], hi0[RBW], hi1[RBW];   // perm pools: low / high bytes of the lane's centroids
+    if constexpr (BITS == 4) {
 #pragma unroll
         for (int r = 0; r < RBW; ++r) trow[r] = &sm.tbl[r * 16 + n][0];
+    } else if constexpr (BITS == 2 || BITS == 3) {
+#pragma unroll
+        for (int r = 0; r < RBW; ++r) {
+            int64_t row = (rb0 + r) * 16 + n;
+            row = row < N ? row : N - 1;
+            const uint32_t* cw = reinterpret_cast<const uint32_t*>(codebook + row * C);
+            // v_perm_b32(S0, S1, sel): selector values 0..3 pick bytes of S1, 4..7 bytes of S0
+            lo0[r] = __builtin_amdgcn_perm(cw[1], cw[0], 0x06040200u);
+            hi0[r] = __builtin_amdgcn_perm(cw[1], cw[0], 0x07050301u);
+            if constexpr (BITS == 3) {
+                lo1[r] = __builtin_amdgcn_perm(cw[3], cw[2], 0x06040200u);
+                hi1[r] = __builtin_amdgcn_perm(cw[3], cw[2], 0x07050301u);
+            } else {
+                lo1[r] = lo0[r];
+                hi1[r] = hi0[r];
+            }
+        }
     }
+
+    // Activations are fetched one chunk (4 steps) ahead of the chunk being multiplied.
+    constexpr int CPG = GPG / 4;                            // chunks per super-block
+    const int nchunks = spw * CPG;
+    u32x4_t xg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xg[i] = *reinterpret_cast<const u32x4_t*>(xsrc[i]);
 
     for (int s0 = 0; s0 < spw; s0 += kPrefetch) {
 #pragma unroll
         for (int p = 0; p < kPrefetch; ++p) {
             const int s = s0 + p;
             if (s < spw) {
-                const uint16_t* xs = xlane + static_cast<int64_t>(s) * SBE;
-                u32x4_t xf[GPG];
 #pragma unroll
-                for (int j = 0; j < GPG; ++j) xf[j] = *reinterpret_cast<const u32x4_t*>(xs + 32 * j);
+                for (int cc = 0; cc < CPG; ++cc) {
+                    // this chunk: registers -> LDS tile -> B fragments; next chunk: global -> registers
 #pragma unroll
-                for (int j = 0; j < GPG; ++j) {
-                    const bf16x8_t b = __builtin_bit_cast(bf16x8_t, xf[j]);
+                    for (int i = 0; i < 4; ++i) xtile[(4 * i + q) * 17 + n] = xg[i];
+                    {
+                        int cn = s * CPG + cc + 1;          // clamped: the last chunk is fetched twice
+                        cn = cn < nchunks ? cn : nchunks - 1;
+                        const int64_t off = static_cast<int64_t>(cn) * 128;
 #pragma unroll
-                    for (int r = 0; r < RBW; ++r) {
-                        const uint32_t gb = group_bits<BITS, GW>(gran[p][r], j);
-                        u32x4_t a;
-                        if constexpr (BITS == 1) {
-                            const u32x2_t lo = sm.masks[gb & 15u], hi = sm.masks[gb >> 4];
-                            a = u32x4_t{lo[0], lo[1], hi[0], hi[1]};
-                        } else {
-                            uint32_t wv[8];
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) wv[e] = trow[r][(gb >> (BITS * e)) & (C - 1)];
-                            a = u32x4_t{wv[0] | (wv[1] << 16), wv[2] | (wv[3] << 16),
-                                        wv[4] | (wv[5] << 16), wv[6] | (wv[7] << 16)};
-                        }
-                        acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), b, acc[r], 0, 0, 0);
+                        for (int i = 0; i < 4; ++i) xg[i] = *reinterpret_cast<const u32x4_t*>(xsrc[i] + off);
                     }
-                    if constexpr (BITS == 1) {
-                        const u32x4_t ones = u32x4_t{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
-                        accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ones), b, accx, 0, 0, 0);
+                    u32x4_t xf[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) xf[i] = xtile[n * 17 + q + 4 * i];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int j = cc * 4 + i;
+                        const bf16x8_t b = __builtin_bit_cast(bf16x8_t, xf[i]);
+#pragma unroll
+                        for (int r = 0; r < RBW; ++r) {
+                            u32x4_t a;
+                            if constexpr (BITS == 1) {
+                                const uint32_t gb = group_bits<BITS, GW>(gran[p][r], j);
+                                const u32x2_t lo = sm.masks[gb & 15u], hi = sm.masks[gb >> 4];
+                                a = u32x4_t{lo[0], lo[1], hi[0], hi[1]};
+                            } else if constexpr (BITS == 4) {
+                                const uint32_t gb = group_bits<BITS, GW>(gran[p][r], j);
+                                uint32_t wv[8];
+#pragma unroll
+                                for (int e = 0; e < 8; ++e) wv[e] = trow[r][(gb >> (4 * e)) & 15u];
+                                a = u32x4_t{wv[0] | (wv[1] << 16), wv[2] | (wv[3] << 16),
+                                            wv[4] | (wv[5] << 16), wv[6] | (wv[7] << 16)};
+                            } else {
+#pragma unroll
+                                for (int h = 0; h < 2; ++h) {      // elements 4h..4h+3 of this step
+                                    uint32_t sel;
+                                    if constexpr (BITS == 2) {
+                                        const int c = 2 * j + h;
+                                        sel = (gran[p][r][c >> 2] >> (2 * (c & 3))) & 0x03030303u;
+                                    } else {
+                                        const int pos = 2 * j + h;   // bit-in-byte of the high bits in dword 2
+                                        const uint32_t hb = pos >= 2 ? gran[p][r][2] >> (pos - 2) : gran[p][r][2] << (2 - pos);
+                                        sel = ((gran[p][r][h] >> (2 * j)) & 0x03030303u) | (hb & 0x04040404u);
+                                    }
+                                    const uint32_t lo = __builtin_amdgcn_perm(lo1[r], lo0[r], sel);
+                                    const uint32_t hi = __builtin_amdgcn_perm(hi1[r], hi0[r], sel);
+                                    a[2 * h] = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+                                    a[2 * h + 1] = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+                                }
+                            }
+                            acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), b, acc[r], 0, 0, 0);
+                        }
+                        if constexpr (BITS == 1) {
+                            const u32x4_t ones = u32x4_t{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+                            accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ones), b, accx, 0, 0, 0);
+                        }
                     }
                 }
                 // refill this slot with the granule kPrefetch super-blocks ahead
@@ -222,7 +287,14 @@ static void launch_mfma_one(const GemmArgs& a, hipStream_t s) {
 
 template <int BITS>
 static void launch_mfma_bits(const GemmArgs& a, int nwk, int rbw, hipStream_t s) {
-    if (rbw == 2) {
+    if (rbw == 4) {
+        switch (nwk) {
+            case 8: launch_mfma_one<BITS, 8, 4>(a, s); break;
+            case 4: launch_mfma_one<BITS, 4, 4>(a, s); break;
+            case 2: launch_mfma_one<BITS, 2, 4>(a, s); break;
+            default: launch_mfma_one<BITS, 1, 4>(a, s); break;
+        }
+    } else if (rbw == 2) {
         switch (nwk) {
             case 8: launch_mfma_one<BITS, 8, 2>(a, s); break;
             case 4: launch_mfma_one<BITS, 4, 2>(a, s); break;
@@ -239,16 +311,27 @@ static void launch_mfma_bits(const GemmArgs& a, int nwk, int rbw, hipStream_t s)
     }
 }
 
+// Tuning override for sweeps: KMQ_MFMA_NWK / KMQ_MFMA_RBW in the environment (read once).
+static int env_int(const char* name) {
+    const char* v = std::getenv(name);
+    return v ? std::atoi(v) : 0;
+}
+
 // Waves along K: the largest of 8, 4, 2, 1 that divides the number of super-blocks.
 int mfma_waves_along_k(int64_t K, int bits) {
+    static const int forced = env_int("KMQ_MFMA_NWK");
     const int64_t nsb = K / tiled_superblock_elems(bits);
     for (int w = 8; w > 1; w >>= 1)
-        if (nsb % w == 0) return w;
+        if (nsb % w == 0 && (forced == 0 || w <= forced)) return w;
     return 1;
 }
 
 // Row blocks per workgroup: two when that still leaves at least two workgroups per CU.
-int mfma_row_blocks(int64_t N) { return (N + 15) / 16 >= 4 * 256 ? 2 : 1; }
+int mfma_row_blocks(int64_t N) {
+    static const int forced = env_int("KMQ_MFMA_RBW");
+    if (forced == 1 || forced == 2 || forced == 4) return forced;
+    return (N + 15) / 16 >= 4 * 256 ? 2 : 1;
+}
 
 hipError_t launch_mfma(const GemmArgs& a, hipStream_t s) {
     const int nwk = mfma_waves_along_k(a.K, a.bits), rbw = mfma_row_blocks(a.N);

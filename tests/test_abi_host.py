@@ -65,24 +65,36 @@ def test_repack_is_a_reversible_permutation(bits, N):
     wpr = kmq.words_per_row(bits, K)
     assert t.size == -(-N // 16) * 16 * wpr == kmq.tiled_words(N, K, bits, 1)
     assert np.array_equal(kmq.unrepack(t, N, K, bits, kmq.LAYOUT_TILED), p)
-    # the documented byte formula: groups of 8 elements (= `bits` bytes) move as units
+    # the documented position formula, element by element
     gpg = {1: 16, 2: 8, 3: 4, 4: 4}[bits]
-    gb, nsb = gpg * bits, K // (32 * gpg)
-    tb = t.view(np.uint8)
-    cb = np.ascontiguousarray(p).view(np.uint8).reshape(N, -1)
-    for _ in range(200):
-        n = int(g.integers(0, N))
-        grp = int(g.integers(0, K // 8))                 # group index along the row
-        sb, gi = divmod(grp, 4 * gpg)
-        q, j = gi % 4, gi // 4
+    gw, nsb = gpg * bits // 4, K // (32 * gpg)
+
+    def position(j, e, tbit):
+        if bits == 1:
+            return 8 * j + e
+        if bits == 4:
+            return 32 * j + 4 * e + tbit
+        if bits == 2:
+            c = 2 * j + e // 4
+            return 32 * (c // 4) + 8 * (e % 4) + 2 * (c % 4) + tbit
+        return 32 * (e // 4) + 8 * (e % 4) + 2 * j + tbit if tbit < 2 else 64 + 8 * (e % 4) + 2 * j + e // 4
+
+    for _ in range(300):
+        n, k = int(g.integers(0, N)), int(g.integers(0, K))
+        sb, grp, e = k // (32 * gpg), (k % (32 * gpg)) // 8, k % 8
+        q, j = grp % 4, grp // 4
         rb, nn = divmod(n, 16)
-        off = ((rb * nsb + sb) * 64 + q * 16 + nn) * gb + j * bits
-        assert np.array_equal(tb[off:off + bits], cb[n, grp * bits:(grp + 1) * bits])
+        base = ((rb * nsb + sb) * 64 + q * 16 + nn) * gw
+        v = 0
+        for tbit in range(bits):
+            pos = position(j, e, tbit)
+            v |= ((int(t[base + pos // 32]) >> (pos % 32)) & 1) << tbit
+        assert v == idx[n, k]
     # rows of a short last block are zero
     if N % 16:
         rb, nn = divmod(N, 16)                            # first missing row
-        off = ((rb * nsb) * 64 + nn) * gb
-        assert not tb[off:off + gb].any()
+        off = ((rb * nsb) * 64 + nn) * gw
+        assert not t[off:off + gw].any()
     assert np.array_equal(kmq.repack(p, K, bits, kmq.LAYOUT_CANONICAL).reshape(N, wpr), p)
 
 
