@@ -73,8 +73,9 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     struct alignas(256) Smem {
         uint16_t tbl[BITS == 4 ? RBW * 16 : 1][16];         // 4-bit: bf16 codebook rows
         u32x2_t masks[16];                                  // 1-bit: nibble -> four bf16 {0,1}
-        u32x4_t xstage[NWK][16 * 17];                       // per wave: 16 batch rows x (16 + 1 pad) 16-byte pieces
-        float red[NWK][RBW][256];                           // partial tiles, [n][m]
+        // per wave: 16 batch rows x (16 + 1 pad) 16-byte pieces of activations; when the wave is
+        // done with them the same memory holds its RBW partial 16x16 tiles ([n][m], 1 KB each)
+        u32x4_t xstage[NWK][16 * 17];
         float redx[BITS == 1 ? NWK : 1][16];                // 1-bit: partial sum_k x per batch column
     };
     __shared__ Smem sm;
@@ -105,24 +106,6 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
         }
     }
 
-    // ---- index granules: kPrefetch super-blocks in flight per row block ----------------------
-    const int64_t gstride = 64 * GW;                        // dwords per (row block, super-block) tile
-    const uint32_t* wbase[RBW];
-#pragma unroll
-    for (int r = 0; r < RBW; ++r) {
-        int64_t rb = rb0 + r;
-        rb = rb < nrb ? rb : nrb - 1;
-        wbase[r] = W + (rb * nsb + sb0) * gstride + lane * GW;
-    }
-    uint32_t gran[kPrefetch][RBW][GW];
-#pragma unroll
-    for (int p = 0; p < kPrefetch; ++p) {
-        const int s = p < spw ? p : spw - 1;
-#pragma unroll
-        for (int r = 0; r < RBW; ++r) load_granule<GW>(wbase[r] + s * gstride, gran[p][r]);
-    }
-    __syncthreads();
-
     // Activations of a chunk (16 batch rows x 128 columns) go through a wave-private LDS
     // tile: global loads take 256 contiguous bytes per row (rows of X are K*2 bytes apart,
     // so gathering 16 rows x 64 bytes per instruction thrashes one memory channel), and
@@ -136,6 +119,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
         xsrc[i] = X + static_cast<int64_t>(m) * K + static_cast<int64_t>(sb0) * SBE + 8 * n;
     }
     u32x4_t* xtile = &sm.xstage[wk][0];
+    static_assert(RBW * 256 * sizeof(float) <= 16 * 17 * sizeof(u32x4_t), "partial tiles reuse the activation tile");
 
     f32x4_t acc[RBW];
 #pragma unroll
@@ -165,12 +149,42 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
         }
     }
 
-    // Activations are fetched one chunk (4 steps) ahead of the chunk being multiplied.
+    // Activations are fetched kXAhead chunks (of 4 steps) ahead of the chunk being multiplied.
     constexpr int CPG = GPG / 4;                            // chunks per super-block
+#ifndef KMQ_XAHEAD
+#define KMQ_XAHEAD 2
+#endif
+    constexpr int kXAhead = KMQ_XAHEAD;                      // divides kPrefetch * CPG, so ring slots are static
     const int nchunks = spw * CPG;
-    u32x4_t xg[4];
+    u32x4_t xg[kXAhead][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) xg[i] = *reinterpret_cast<const u32x4_t*>(xsrc[i]);
+    for (int c = 0; c < kXAhead; ++c) {
+        const int cn = c < nchunks ? c : nchunks - 1;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xg[c][i] = *reinterpret_cast<const u32x4_t*>(xsrc[i] + cn * 128);
+    }
+
+    // Issue order matters: vmcnt retires loads in order, and the memory system serves the
+    // whole grid's requests roughly first come first served.  Small operands (codebook rows,
+    // first activation chunks) were requested above; granules follow in the order they are
+    // consumed, so a wave can start on super-block 0 when a quarter of its data is there.
+    const int64_t gstride = 64 * GW;                        // dwords per (row block, super-block) tile
+    const uint32_t* wbase[RBW];
+#pragma unroll
+    for (int r = 0; r < RBW; ++r) {
+        int64_t rb = rb0 + r;
+        rb = rb < nrb ? rb : nrb - 1;
+        wbase[r] = W + (rb * nsb + sb0) * gstride + lane * GW;
+    }
+    uint32_t gran[kPrefetch][RBW][GW];
+#pragma unroll
+    for (int p = 0; p < kPrefetch; ++p) {
+        const int s = p < spw ? p : spw - 1;
+#pragma unroll
+        for (int r = 0; r < RBW; ++r) load_granule<GW>(wbase[r] + s * gstride, gran[p][r]);
+    }
+
+    __syncthreads();                                        // tables visible; every load above is in flight
 
     for (int s0 = 0; s0 < spw; s0 += kPrefetch) {
 #pragma unroll
@@ -179,15 +193,15 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
             if (s < spw) {
 #pragma unroll
                 for (int cc = 0; cc < CPG; ++cc) {
-                    // this chunk: registers -> LDS tile -> B fragments; next chunk: global -> registers
+                    // this chunk: registers -> LDS tile -> B fragments; chunk + kXAhead: global -> registers
+                    constexpr int slot_dummy = 0; (void)slot_dummy;
+                    const int slot = (p * CPG + cc) % kXAhead;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) xtile[(4 * i + q) * 17 + n] = xg[i];
-                    {
-                        int cn = s * CPG + cc + 1;          // clamped: the last chunk is fetched twice
-                        cn = cn < nchunks ? cn : nchunks - 1;
+                    for (int i = 0; i < 4; ++i) xtile[(4 * i + q) * 17 + n] = xg[slot][i];
+                    if (const int cn = s * CPG + cc + kXAhead; cn < nchunks) {   // wave-uniform
                         const int64_t off = static_cast<int64_t>(cn) * 128;
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) xg[i] = *reinterpret_cast<const u32x4_t*>(xsrc[i] + off);
+                        for (int i = 0; i < 4; ++i) xg[slot][i] = *reinterpret_cast<const u32x4_t*>(xsrc[i] + off);
                     }
                     u32x4_t xf[4];
 #pragma unroll
@@ -237,9 +251,10 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
                     }
                 }
                 // refill this slot with the granule kPrefetch super-blocks ahead
-                const int sn = s + kPrefetch < spw ? s + kPrefetch : spw - 1;
+                if (const int sn = s + kPrefetch; sn < spw) {
 #pragma unroll
-                for (int r = 0; r < RBW; ++r) load_granule<GW>(wbase[r] + sn * gstride, gran[p][r]);
+                    for (int r = 0; r < RBW; ++r) load_granule<GW>(wbase[r] + sn * gstride, gran[p][r]);
+                }
             }
         }
     }
@@ -249,7 +264,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
 #pragma unroll
     for (int r = 0; r < RBW; ++r)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sm.red[wk][r][(4 * q + i) * 16 + n] = acc[r][i];
+        for (int i = 0; i < 4; ++i) reinterpret_cast<float*>(xtile)[r * 256 + (4 * q + i) * 16 + n] = acc[r][i];
     if constexpr (BITS == 1) {
         if (q == 0) sm.redx[wk][n] = accx[0];               // every row of the all-ones tile is sum_k x[m][k]
     }
@@ -260,7 +275,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
         const int r = nl >> 4, nn = nl & 15;
         float s = 0.f;
 #pragma unroll
-        for (int k = 0; k < NWK; ++k) s += sm.red[k][r][nn * 16 + m];
+        for (int k = 0; k < NWK; ++k) s += reinterpret_cast<const float*>(&sm.xstage[k][0])[r * 256 + nn * 16 + m];
         const int64_t row = (rb0 + r) * 16 + nn;
         if (m < M && row < N) {
             if constexpr (BITS == 1) {
