@@ -244,7 +244,8 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     };
     __shared__ Smem sm;
 
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // the wave index is uniform: telling the compiler so moves address arithmetic to the scalar unit
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int wk = wave % NWK, wr = wave / NWK;
     const int sub = lane / LPR, pos = lane % LPR;
     const int64_t wg_row0 = static_cast<int64_t>(blockIdx.x) * ROWS_WG;

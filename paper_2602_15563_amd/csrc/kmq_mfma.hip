@@ -62,7 +62,12 @@ __device__ __forceinline__ uint32_t group_bits(const uint32_t (&g)[GW], int j) {
     return 0;
 }
 
-template <int BITS, int NWK, int RBW>
+// SPW > 0 fixes the number of super-blocks per wave at compile time: the K loop is then
+// fully unrolled and has no back edge.  That matters beyond loop overhead: with loads in
+// flight across a back edge the compiler's s_waitcnt vmcnt() placement becomes
+// conservative and drains the whole prefetch queue at every iteration.  SPW = 0 is the
+// general (runtime trip count) version.
+template <int BITS, int NWK, int RBW, int SPW>
 __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
     const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int64_t N, int64_t K, int M) {
@@ -80,12 +85,14 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     };
     __shared__ Smem sm;
 
-    const int wk = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // the wave index is uniform: telling the compiler so moves the address arithmetic to the scalar unit
+    const int wk = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int n = lane & 15, q = lane >> 4;
     const int64_t rb0 = static_cast<int64_t>(blockIdx.x) * RBW;
     const int64_t nrb = (N + 15) >> 4;
     const int nsb = static_cast<int>(K / SBE);
-    const int spw = nsb / NWK;                              // super-blocks per wave (host guarantees divisibility)
+    constexpr int kOuterUnroll = SPW > 0 ? (SPW + kPrefetch - 1) / kPrefetch : 1;
+    const int spw = SPW > 0 ? SPW : nsb / NWK;              // super-blocks per wave (host guarantees divisibility)
     const int sb0 = wk * spw;
 
     // ---- tables ---------------------------------------------------------------------------
@@ -111,12 +118,13 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     // so gathering 16 rows x 64 bytes per instruction thrashes one memory channel), and
     // lane (m = n, q) then reads the 16 bytes of columns 8*(q + 4i)..+7 for step i.
     // Batch columns >= M are fed row M-1 and dropped at the end.
-    const uint16_t* xsrc[4];
+    const char* xbase = reinterpret_cast<const char*>(X + static_cast<int64_t>(sb0) * SBE);   // uniform
+    uint32_t xoff[4];                                       // per-lane byte offsets (M*K*2 < 2^30)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int m = 4 * i + q;
         m = m < M ? m : M - 1;
-        xsrc[i] = X + static_cast<int64_t>(m) * K + static_cast<int64_t>(sb0) * SBE + 8 * n;
+        xoff[i] = (static_cast<uint32_t>(m) * static_cast<uint32_t>(K) + 8u * n) * 2u;
     }
     u32x4_t* xtile = &sm.xstage[wk][0];
     static_assert(RBW * 256 * sizeof(float) <= 16 * 17 * sizeof(u32x4_t), "partial tiles reuse the activation tile");
@@ -161,7 +169,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     for (int c = 0; c < kXAhead; ++c) {
         const int cn = c < nchunks ? c : nchunks - 1;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) xg[c][i] = *reinterpret_cast<const u32x4_t*>(xsrc[i] + cn * 128);
+        for (int i = 0; i < 4; ++i) xg[c][i] = *reinterpret_cast<const u32x4_t*>(xbase + (xoff[i] + static_cast<uint32_t>(cn) * 256u));
     }
 
     // Issue order matters: vmcnt retires loads in order, and the memory system serves the
@@ -174,18 +182,19 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     for (int r = 0; r < RBW; ++r) {
         int64_t rb = rb0 + r;
         rb = rb < nrb ? rb : nrb - 1;
-        wbase[r] = W + (rb * nsb + sb0) * gstride + lane * GW;
+        wbase[r] = W + (rb * nsb + sb0) * gstride;           // uniform; the lane adds lane * GW dwords
     }
     uint32_t gran[kPrefetch][RBW][GW];
 #pragma unroll
     for (int p = 0; p < kPrefetch; ++p) {
         const int s = p < spw ? p : spw - 1;
 #pragma unroll
-        for (int r = 0; r < RBW; ++r) load_granule<GW>(wbase[r] + s * gstride, gran[p][r]);
+        for (int r = 0; r < RBW; ++r) load_granule<GW>(wbase[r] + s * gstride + lane * GW, gran[p][r]);
     }
 
     __syncthreads();                                        // tables visible; every load above is in flight
 
+#pragma unroll kOuterUnroll
     for (int s0 = 0; s0 < spw; s0 += kPrefetch) {
 #pragma unroll
         for (int p = 0; p < kPrefetch; ++p) {
@@ -199,9 +208,8 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
 #pragma unroll
                     for (int i = 0; i < 4; ++i) xtile[(4 * i + q) * 17 + n] = xg[slot][i];
                     if (const int cn = s * CPG + cc + kXAhead; cn < nchunks) {   // wave-uniform
-                        const int64_t off = static_cast<int64_t>(cn) * 128;
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) xg[slot][i] = *reinterpret_cast<const u32x4_t*>(xsrc[i] + off);
+                        for (int i = 0; i < 4; ++i) xg[slot][i] = *reinterpret_cast<const u32x4_t*>(xbase + (xoff[i] + static_cast<uint32_t>(cn) * 256u));
                     }
                     u32x4_t xf[4];
 #pragma unroll
@@ -253,7 +261,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
                 // refill this slot with the granule kPrefetch super-blocks ahead
                 if (const int sn = s + kPrefetch; sn < spw) {
 #pragma unroll
-                    for (int r = 0; r < RBW; ++r) load_granule<GW>(wbase[r] + sn * gstride, gran[p][r]);
+                    for (int r = 0; r < RBW; ++r) load_granule<GW>(wbase[r] + sn * gstride + lane * GW, gran[p][r]);
                 }
             }
         }
@@ -292,38 +300,30 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
 
 // ---- launch ------------------------------------------------------------------------------------
 
-template <int BITS, int NWK, int RBW>
+template <int BITS, int NWK, int RBW, int SPW>
 static void launch_mfma_one(const GemmArgs& a, hipStream_t s) {
     const int64_t nrb = (a.N + 15) / 16;
     const dim3 grid(static_cast<unsigned>((nrb + RBW - 1) / RBW)), block(NWK * 64);
-    hipLaunchKernelGGL((gemm_mfma_kernel<BITS, NWK, RBW>), grid, block, 0, s,
+    hipLaunchKernelGGL((gemm_mfma_kernel<BITS, NWK, RBW, SPW>), grid, block, 0, s,
                        a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M);
 }
 
+// Launch shapes with a compile-time K loop (the ones the heuristic picks for common K),
+// otherwise the runtime-loop kernel for that (NWK, RBW).
 template <int BITS>
-static void launch_mfma_bits(const GemmArgs& a, int nwk, int rbw, hipStream_t s) {
-    if (rbw == 4) {
-        switch (nwk) {
-            case 8: launch_mfma_one<BITS, 8, 4>(a, s); break;
-            case 4: launch_mfma_one<BITS, 4, 4>(a, s); break;
-            case 2: launch_mfma_one<BITS, 2, 4>(a, s); break;
-            default: launch_mfma_one<BITS, 1, 4>(a, s); break;
-        }
-    } else if (rbw == 2) {
-        switch (nwk) {
-            case 8: launch_mfma_one<BITS, 8, 2>(a, s); break;
-            case 4: launch_mfma_one<BITS, 4, 2>(a, s); break;
-            case 2: launch_mfma_one<BITS, 2, 2>(a, s); break;
-            default: launch_mfma_one<BITS, 1, 2>(a, s); break;
-        }
-    } else {
-        switch (nwk) {
-            case 8: launch_mfma_one<BITS, 8, 1>(a, s); break;
-            case 4: launch_mfma_one<BITS, 4, 1>(a, s); break;
-            case 2: launch_mfma_one<BITS, 2, 1>(a, s); break;
-            default: launch_mfma_one<BITS, 1, 1>(a, s); break;
-        }
-    }
+static void launch_mfma_bits(const GemmArgs& a, int nwk, int rbw, int spw, hipStream_t s) {
+#define KMQ_MFMA_TRY(NWK_, RBW_, SPW_) \
+    if (nwk == NWK_ && rbw == RBW_ && spw == SPW_) { launch_mfma_one<BITS, NWK_, RBW_, SPW_>(a, s); return; }
+    KMQ_MFMA_TRY(8, 1, 1) KMQ_MFMA_TRY(8, 1, 2) KMQ_MFMA_TRY(8, 1, 4)
+    KMQ_MFMA_TRY(4, 2, 2) KMQ_MFMA_TRY(4, 2, 4) KMQ_MFMA_TRY(4, 2, 8)
+    KMQ_MFMA_TRY(2, 1, 3) KMQ_MFMA_TRY(4, 1, 3) KMQ_MFMA_TRY(4, 1, 4)
+#undef KMQ_MFMA_TRY
+#define KMQ_MFMA_RT(NWK_, RBW_) \
+    if (nwk == NWK_ && rbw == RBW_) { launch_mfma_one<BITS, NWK_, RBW_, 0>(a, s); return; }
+    KMQ_MFMA_RT(8, 1) KMQ_MFMA_RT(4, 1) KMQ_MFMA_RT(2, 1) KMQ_MFMA_RT(1, 1)
+    KMQ_MFMA_RT(8, 2) KMQ_MFMA_RT(4, 2) KMQ_MFMA_RT(2, 2) KMQ_MFMA_RT(1, 2)
+#undef KMQ_MFMA_RT
+    launch_mfma_one<BITS, 1, 1, 0>(a, s);
 }
 
 // Tuning override for sweeps: KMQ_MFMA_NWK / KMQ_MFMA_RBW in the environment (read once).
@@ -338,7 +338,7 @@ static int env_int(const char* name) {
 // 1-bit granules already carry 16 steps each and measured faster with one row block.
 int mfma_row_blocks(int64_t N, int bits) {
     static const int forced = env_int("KMQ_MFMA_RBW");
-    if (forced == 1 || forced == 2 || forced == 4) return forced;
+    if (forced == 1 || forced == 2) return forced;
     return (bits >= 2 && (N + 15) / 16 >= 2 * 256) ? 2 : 1;
 }
 
@@ -355,11 +355,12 @@ int mfma_waves_along_k(int64_t N, int64_t K, int bits) {
 
 hipError_t launch_mfma(const GemmArgs& a, hipStream_t s) {
     const int nwk = mfma_waves_along_k(a.N, a.K, a.bits), rbw = mfma_row_blocks(a.N, a.bits);
+    const int spw = static_cast<int>(a.K / tiled_superblock_elems(a.bits) / nwk);
     switch (a.bits) {
-        case 1: launch_mfma_bits<1>(a, nwk, rbw, s); break;
-        case 2: launch_mfma_bits<2>(a, nwk, rbw, s); break;
-        case 3: launch_mfma_bits<3>(a, nwk, rbw, s); break;
-        default: launch_mfma_bits<4>(a, nwk, rbw, s); break;
+        case 1: launch_mfma_bits<1>(a, nwk, rbw, spw, s); break;
+        case 2: launch_mfma_bits<2>(a, nwk, rbw, spw, s); break;
+        case 3: launch_mfma_bits<3>(a, nwk, rbw, spw, s); break;
+        default: launch_mfma_bits<4>(a, nwk, rbw, spw, s); break;
     }
     return hipGetLastError();
 }
