@@ -232,13 +232,25 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     constexpr int U = BITS == 1 ? 2 * G : G;       // lookup units (8 activation registers each) per row slice
     constexpr int XR = 8 * U;                      // activation registers: bf16 pairs (1/2-bit) or fp32 (4-bit)
     constexpr int C16 = EL * 2 / 16;               // 16-byte chunks of x per lane slice
+    // Every wave builds the tables of its own rows (16 lanes per row, LUT_PASSES passes of 64
+    // lanes) in its own row groups; lanes past the last row write into padding: no branch.
+    constexpr int LUT_PASSES = BITS == 1 ? 0 : (ROWS_WAVE * 16 + 63) / 64;
+    constexpr int LUT_TABLES = BITS == 1 ? 1 : (LUT_PASSES * 4 + RPL - 1) / RPL;   // tables per row group incl. padding
+    constexpr int LUT_GROUPS = BITS == 1 ? 1 : NWK * NWR * RPL;
+    constexpr int TBL = ((LUT_TABLES > RS ? LUT_TABLES : RS) * 16 + 63) / 64 * 64;   // dwords per row group: bases stay 256-byte aligned
     constexpr int XCHUNKS = K / 8;
-    static_assert(RS <= 4 && (ROWS_WG % 2) == 0 && THREADS <= 1024, "launch shape");
+    constexpr int XPT = (XCHUNKS + NWK * NWR * 64 - 1) / (NWK * NWR * 64);   // 16-byte chunks of x staged per thread
+    constexpr int XSLOTS = XPT * NWK * NWR * 64;
+    static_assert(RS <= 8 && (ROWS_WG % 2) == 0 && THREADS <= 1024, "launch shape");
     static_assert(EL % 8 == 0, "x slices are whole 16-byte chunks");
 
     struct alignas(256) Smem {
-        uint32_t lut[NWR * RPL][64];               // 2/4-bit: RS tables of 16 x 4 B; 1-bit: lut[0] holds the 16 x 8 B mask table
-        u32x4_t xs[XCHUNKS];                       // staged activations, swizzled per lane slice
+        // 2/4-bit: per wave and row group, RS tables of 16 x 4 B; 1-bit: lut[0] holds the 16 x 8 B mask table
+        uint32_t lut[LUT_GROUPS][TBL];
+        // staged activations, swizzled per lane slice; threads past the end of x (the
+        // thread count need not divide the chunk count) write clamped data into the tail,
+        // so that staging has no branch for the loads to be sunk into
+        u32x4_t xs[(XSLOTS + C16 - 1) / C16 * C16];
         float part[NWK][ROWS_WG];                  // per-slice partial sums
         float sxp[NWK];                            // 1-bit: per-slice sum of x
     };
@@ -251,31 +263,44 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     const int64_t wg_row0 = static_cast<int64_t>(blockIdx.x) * ROWS_WG;
     const int64_t wave_row0 = wg_row0 + wr * ROWS_WAVE;
 
-    // ---- 1. small operands first: codebook rows for the tables, x chunks ----------------
-    constexpr int LUT_PASSES = BITS == 1 ? 0 : (ROWS_WG * 16 + THREADS - 1) / THREADS;
+    // ---- 1. small operands first: x chunks, then the codebook rows of this wave's own rows ----
+    // Loads return in issue order.  x comes from the L2 and is there early; the codebook
+    // rows are DRAM reads that queue behind other waves' index loads like the index loads
+    // themselves, so they go second and nothing before the lookups waits for them.
+    // Each thread stages XPT consecutive 16-byte chunks of x, fetched as ONE wide load: separate
+    // loads get reordered behind the index loads by instruction selection.
+    static_assert(XPT == 1 || XPT == 2 || XPT == 4, "x chunks per thread");
+    typedef __attribute__((ext_vector_type(4 * XPT))) uint32_t xwide_t;
+    xwide_t xt;
+    {
+        int c = threadIdx.x * XPT;
+        c = c < XCHUNKS ? c : XCHUNKS - XPT;
+        xt = *reinterpret_cast<const xwide_t*>(x + c * 8);
+    }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     uint32_t cbv[LUT_PASSES > 0 ? LUT_PASSES : 1][BITS == 4 ? 1 : 2];
 #pragma unroll
     for (int p = 0; p < LUT_PASSES; ++p) {
-        int rl = (threadIdx.x + p * THREADS) >> 4;                     // row inside the workgroup
-        rl = rl < ROWS_WG ? rl : ROWS_WG - 1;
-        int64_t row = wg_row0 + rl;
+        int rw = (lane + p * 64) >> 4;                                 // row inside the wave: t * RPL + sub
+        rw = rw < ROWS_WAVE ? rw : ROWS_WAVE - 1;
+        int64_t row = wave_row0 + rw;
         row = row < N ? row : N - 1;
         if constexpr (BITS == 2) {
             const u32x2_t c = *reinterpret_cast<const u32x2_t*>(codebook + row * C);
             cbv[p][0] = c[0];
             cbv[p][1] = c[1];
         } else {
-            cbv[p][0] = codebook[row * C + (threadIdx.x & 15)];
+            cbv[p][0] = codebook[row * C + (lane & 15)];
         }
     }
-    constexpr int XPASSES = (XCHUNKS + THREADS - 1) / THREADS;
-    u32x4_t xt[XPASSES];
-#pragma unroll
-    for (int h = 0; h < XPASSES; ++h) {
-        int c = threadIdx.x + h * THREADS;
-        c = c < XCHUNKS ? c : XCHUNKS - 1;
-        xt[h] = reinterpret_cast<const u32x4_t*>(x)[c];
-    }
+
+    // The small loads must be ahead of the index loads in the wave's (in-order) load queue:
+    // staging x then waits for x only, with everything else still in flight.  Left to
+    // itself the compiler sinks small loads below the index loads (or into a branch) and the
+    // barrier ends up waiting for the whole index stream.
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- 2. every index load of this wave -------------------------------------------------
     uint32_t w[RS][G];
@@ -285,15 +310,15 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         row = row < N ? row : N - 1;                                   // clamped: loads stay unconditional
         load_words<G>(W + row * WPR + (wk * LPR + pos) * G, w[t]);
     }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
 
-    // ---- 3. tables and staged activations into LDS ------------------------------------------
+    // ---- 3. staged activations into LDS ----------------------------------------------------------
 #pragma unroll
-    for (int h = 0; h < XPASSES; ++h) {
-        const int c = threadIdx.x + h * THREADS;
-        if (c < XCHUNKS) {
-            const int sl = c / C16, q = c % C16;
-            sm.xs[sl * C16 + (q + sl) % C16] = xt[h];
-        }
+    for (int h = 0; h < XPT; ++h) {
+        const int c = threadIdx.x * XPT + h;
+        const int sl = c / C16, q = c % C16;
+        sm.xs[sl * C16 + (q + sl) % C16] = u32x4_t{xt[4 * h], xt[4 * h + 1], xt[4 * h + 2], xt[4 * h + 3]};
     }
     if constexpr (BITS == 1) {
         if (threadIdx.x < 16) {
@@ -302,24 +327,6 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
             m[0] = ((e & 1u) ? 0x3F80u : 0u) | ((e & 2u) ? 0x3F800000u : 0u);
             m[1] = ((e & 4u) ? 0x3F80u : 0u) | ((e & 8u) ? 0x3F800000u : 0u);
             reinterpret_cast<u32x2_t*>(&sm.lut[0][0])[e] = m;
-        }
-    } else {
-#pragma unroll
-        for (int p = 0; p < LUT_PASSES; ++p) {
-            const int rl = (threadIdx.x + p * THREADS) >> 4, e = threadIdx.x & 15;
-            if (rl < ROWS_WG) {
-                // row rl = (wr', t', sub') with rl = wr'*ROWS_WAVE + t'*RPL + sub'
-                const int wr2 = rl / ROWS_WAVE, t2 = (rl % ROWS_WAVE) / RPL, sub2 = rl % RPL;
-                uint32_t entry;
-                if constexpr (BITS == 2) {
-                    const uint64_t c64 = static_cast<uint64_t>(cbv[p][0]) | (static_cast<uint64_t>(cbv[p][1]) << 32);
-                    entry = (static_cast<uint32_t>(c64 >> (16 * (e & 3))) & 0xFFFFu) |
-                            ((static_cast<uint32_t>(c64 >> (16 * (e >> 2))) & 0xFFFFu) << 16);
-                } else {
-                    entry = cbv[p][0] << 16;
-                }
-                sm.lut[wr2 * RPL + sub2][t2 * 16 + e] = entry;
-            }
         }
     }
     __syncthreads();
@@ -343,9 +350,29 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         }
     }
 
+    // ---- 4b. this wave's tables, once its codebook rows have arrived --------------------------------
+    // (the wave reads back only what it wrote itself: LDS serves a wave's instructions in order)
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (BITS != 1) {
+#pragma unroll
+        for (int p = 0; p < LUT_PASSES; ++p) {
+            const int rw = (lane + p * 64) >> 4, e = lane & 15;
+            const int t2 = rw / RPL, sub2 = rw % RPL;
+            uint32_t entry;
+            if constexpr (BITS == 2) {
+                const uint64_t c64 = static_cast<uint64_t>(cbv[p][0]) | (static_cast<uint64_t>(cbv[p][1]) << 32);
+                entry = (static_cast<uint32_t>(c64 >> (16 * (e & 3))) & 0xFFFFu) |
+                        ((static_cast<uint32_t>(c64 >> (16 * (e >> 2))) & 0xFFFFu) << 16);
+            } else {
+                entry = cbv[p][0] << 16;
+            }
+            sm.lut[wave * RPL + sub2][t2 * 16 + e] = entry;
+        }
+    }
+
     // ---- 5. lookups and multiply-accumulate, one unit ahead -------------------------------------
     const uint32_t lut_base = static_cast<uint32_t>(reinterpret_cast<size_t>(
-        (lds_cu32_t*)(&sm.lut[BITS == 1 ? 0 : wr * RPL + sub][0])));
+        (lds_cu32_t*)(&sm.lut[BITS == 1 ? 0 : wave * RPL + sub][0])));
     uint32_t ar[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) ar[i] = lut_base;

@@ -317,6 +317,7 @@ static void launch_mfma_bits(const GemmArgs& a, int nwk, int rbw, int spw, hipSt
     KMQ_MFMA_TRY(8, 1, 1) KMQ_MFMA_TRY(8, 1, 2) KMQ_MFMA_TRY(8, 1, 4)
     KMQ_MFMA_TRY(4, 2, 2) KMQ_MFMA_TRY(4, 2, 4) KMQ_MFMA_TRY(4, 2, 8)
     KMQ_MFMA_TRY(2, 1, 3) KMQ_MFMA_TRY(4, 1, 3) KMQ_MFMA_TRY(4, 1, 4)
+    KMQ_MFMA_TRY(8, 4, 4) KMQ_MFMA_TRY(16, 4, 2) KMQ_MFMA_TRY(8, 4, 2) KMQ_MFMA_TRY(16, 4, 1) KMQ_MFMA_TRY(16, 2, 2) KMQ_MFMA_TRY(16, 2, 1)
 #undef KMQ_MFMA_TRY
 #define KMQ_MFMA_RT(NWK_, RBW_) \
     if (nwk == NWK_ && rbw == RBW_) { launch_mfma_one<BITS, NWK_, RBW_, 0>(a, s); return; }
@@ -338,7 +339,7 @@ static int env_int(const char* name) {
 // 1-bit granules already carry 16 steps each and measured faster with one row block.
 int mfma_row_blocks(int64_t N, int bits) {
     static const int forced = env_int("KMQ_MFMA_RBW");
-    if (forced == 1 || forced == 2) return forced;
+    if (forced == 1 || forced == 2 || forced == 4) return forced;
     return (bits >= 2 && (N + 15) / 16 >= 2 * 256) ? 2 : 1;
 }
 
@@ -348,7 +349,7 @@ int mfma_waves_along_k(int64_t N, int64_t K, int bits) {
     static const int forced = env_int("KMQ_MFMA_NWK");
     const int64_t nsb = K / tiled_superblock_elems(bits);
     const int cap = forced ? forced : (mfma_row_blocks(N, bits) >= 2 ? 4 : 8);
-    for (int w = 8; w > 1; w >>= 1)
+    for (int w = 16; w > 1; w >>= 1)
         if (nsb % w == 0 && w <= cap) return w;
     return 1;
 }
