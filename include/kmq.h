@@ -89,10 +89,14 @@ kmq_status kmq_unpack(const uint32_t* packed, int64_t N, int64_t K, int bits, ui
  *     bits = 1:  8*j + e                               (groups in order, one byte each)
  *     bits = 4:  32*j + 4*e + t                        (groups in order, one dword each)
  *     bits = 2:  32*(c/4) + 8*(e%4) + 2*(c%4) + t,     c = 2*j + e/4
- *     bits = 3:  t < 2:  32*(e/4) + 8*(e%4) + 2*j + t
- *                t = 2:  64 + 8*(e%4) + 2*j + e/4
- * The 2- and 3-bit orders spread the fields so that one shift and one AND leave
- * four indices in the four bytes of a register.  Requires K % (32*gpg) == 0
+ *     bits = 3:  h = e/4, p = 8*(e%4):
+ *                j < 3:          32*j + p + 3*h + t     (two 3-bit fields in bits 0..5 of each byte)
+ *                j = 3, h = 0:   t < 2: p + 6 + t       (the bytes' two spare top bits, dword 0)
+ *                                t = 2: 32 + p + 6
+ *                j = 3, h = 1:   t = 0: 32 + p + 7
+ *                                t > 0: 64 + p + 5 + t
+ * The 2- and 3-bit orders spread the fields so that at most one shift and one
+ * AND leave four indices in the four bytes of a register (3-bit, step 3: two of each).  Requires K % (32*gpg) == 0
  * (else KMQ_ERR_LAYOUT).  Same size as the canonical stream with rows padded
  * to 16: size `tiled` with kmq_tiled_words(). */
 kmq_status kmq_repack(const uint32_t* canonical, int64_t N, int64_t K, int bits, int layout,

@@ -42,8 +42,8 @@ KMQ_HD inline int64_t tiled_granule_dword(int bits, int64_t K, int64_t n, int64_
 // Inside a granule: bit position (0 .. 32*gw-1, dword-major) of bit t of the index
 // of element e (0..7) of step j (0..gpg-1).  1- and 4-bit granules keep the
 // canonical order of their groups; 2- and 3-bit granules spread the fields so
-// that one shift and one AND put four indices into the four bytes of a register
-// (a v_perm_b32 selector).
+// that at most one shift and one AND put four indices into the four bytes of a
+// register (a v_perm_b32 selector).
 KMQ_HD inline int tiled_bit_position(int bits, int j, int e, int t) {
     switch (bits) {
         case 1: return 8 * j + e;
@@ -52,9 +52,12 @@ KMQ_HD inline int tiled_bit_position(int bits, int j, int e, int t) {
             const int c = 2 * j + e / 4, k = e % 4;
             return 32 * (c / 4) + 8 * k + 2 * (c % 4) + t;
         }
-        default:  // 3: two low bits in dwords 0/1, high bit in dword 2
-            if (t < 2) return 32 * (e / 4) + 8 * (e % 4) + 2 * j + t;
-            return 64 + 8 * (e % 4) + 2 * j + e / 4;
+        default: {  // 3: steps 0..2 fill bits 0..5 of the bytes of dwords 0..2, step 3 the spare top bits
+            const int h = e / 4, p = 8 * (e % 4);
+            if (j < 3) return 32 * j + p + 3 * h + t;
+            if (h == 0) return t < 2 ? p + 6 + t : 32 + p + 6;
+            return t == 0 ? 32 + p + 7 : 64 + p + 5 + t;
+        }
     }
 }
 

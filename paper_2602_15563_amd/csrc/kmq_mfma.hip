@@ -240,9 +240,10 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
                                         const int c = 2 * j + h;
                                         sel = (gran[p][r][c >> 2] >> (2 * (c & 3))) & 0x03030303u;
                                     } else {
-                                        const int pos = 2 * j + h;   // bit-in-byte of the high bits in dword 2
-                                        const uint32_t hb = pos >= 2 ? gran[p][r][2] >> (pos - 2) : gran[p][r][2] << (2 - pos);
-                                        sel = ((gran[p][r][h] >> (2 * j)) & 0x03030303u) | (hb & 0x04040404u);
+                                        const uint32_t* D = gran[p][r];
+                                        if (j < 3) sel = (h == 0 ? D[j] : D[j] >> 3) & 0x07070707u;
+                                        else if (h == 0) sel = ((D[0] >> 6) & 0x03030303u) | ((D[1] >> 4) & 0x04040404u);
+                                        else sel = ((D[1] >> 7) & 0x01010101u) | ((D[2] >> 5) & 0x06060606u);
                                     }
                                     const uint32_t lo = __builtin_amdgcn_perm(lo1[r], lo0[r], sel);
                                     const uint32_t hi = __builtin_amdgcn_perm(hi1[r], hi0[r], sel);
@@ -317,7 +318,7 @@ static void launch_mfma_bits(const GemmArgs& a, int nwk, int rbw, int spw, hipSt
     KMQ_MFMA_TRY(8, 1, 1) KMQ_MFMA_TRY(8, 1, 2) KMQ_MFMA_TRY(8, 1, 4)
     KMQ_MFMA_TRY(4, 2, 2) KMQ_MFMA_TRY(4, 2, 4) KMQ_MFMA_TRY(4, 2, 8)
     KMQ_MFMA_TRY(2, 1, 3) KMQ_MFMA_TRY(4, 1, 3) KMQ_MFMA_TRY(4, 1, 4)
-    KMQ_MFMA_TRY(8, 4, 4) KMQ_MFMA_TRY(16, 4, 2) KMQ_MFMA_TRY(8, 4, 2) KMQ_MFMA_TRY(16, 4, 1) KMQ_MFMA_TRY(16, 2, 2) KMQ_MFMA_TRY(16, 2, 1)
+    KMQ_MFMA_TRY(6, 1, 1) KMQ_MFMA_TRY(6, 1, 2) KMQ_MFMA_TRY(3, 1, 2)
 #undef KMQ_MFMA_TRY
 #define KMQ_MFMA_RT(NWK_, RBW_) \
     if (nwk == NWK_ && rbw == RBW_) { launch_mfma_one<BITS, NWK_, RBW_, 0>(a, s); return; }
@@ -339,18 +340,19 @@ static int env_int(const char* name) {
 // 1-bit granules already carry 16 steps each and measured faster with one row block.
 int mfma_row_blocks(int64_t N, int bits) {
     static const int forced = env_int("KMQ_MFMA_RBW");
-    if (forced == 1 || forced == 2 || forced == 4) return forced;
+    if (forced == 1 || forced == 2) return forced;
     return (bits >= 2 && (N + 15) / 16 >= 2 * 256) ? 2 : 1;
 }
 
-// Waves along K: the largest of 8 (4 with two row blocks per wave), 4, 2, 1 that divides
-// the number of super-blocks.
+// Waves along K: the largest of 8 (4 with two row blocks per wave), 6, 4, 3, 2, 1 that
+// divides the number of super-blocks (6 and 3 serve K = 3072 at 1 bit: six super-blocks).
 int mfma_waves_along_k(int64_t N, int64_t K, int bits) {
     static const int forced = env_int("KMQ_MFMA_NWK");
     const int64_t nsb = K / tiled_superblock_elems(bits);
     const int cap = forced ? forced : (mfma_row_blocks(N, bits) >= 2 ? 4 : 8);
-    for (int w = 16; w > 1; w >>= 1)
-        if (nsb % w == 0 && w <= cap) return w;
+    static const int kChoices[] = {8, 6, 4, 3, 2};
+    for (int w : kChoices)
+        if (nsb % w == 0 && w <= cap && (w != 6 && w != 3 || nsb / w <= 2)) return w;
     return 1;
 }
 

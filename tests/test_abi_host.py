@@ -77,7 +77,12 @@ def test_repack_is_a_reversible_permutation(bits, N):
         if bits == 2:
             c = 2 * j + e // 4
             return 32 * (c // 4) + 8 * (e % 4) + 2 * (c % 4) + tbit
-        return 32 * (e // 4) + 8 * (e % 4) + 2 * j + tbit if tbit < 2 else 64 + 8 * (e % 4) + 2 * j + e // 4
+        h, p = e // 4, 8 * (e % 4)
+        if j < 3:
+            return 32 * j + p + 3 * h + tbit
+        if h == 0:
+            return p + 6 + tbit if tbit < 2 else 32 + p + 6
+        return 32 + p + 7 if tbit == 0 else 64 + p + 5 + tbit
 
     for _ in range(300):
         n, k = int(g.integers(0, N)), int(g.integers(0, K))
