@@ -52,7 +52,7 @@ hipError_t launch_stream_read(const void* p, size_t bytes, void* sink, hipStream
 // Matrix-core kernel (tiled layout only).
 hipError_t launch_mfma(const GemmArgs& a, hipStream_t s);
 int mfma_waves_along_k(int64_t N, int64_t K, int bits);
-int mfma_row_blocks(int64_t N, int bits);
+int mfma_row_blocks(int64_t N, int64_t K, int bits);
 
 // Hand-scheduled table kernels (1/2/4-bit): -1 if (bits, K, layout) has none.
 int lut_find(int64_t K, int bits, int layout);

@@ -309,23 +309,37 @@ static void launch_mfma_one(const GemmArgs& a, hipStream_t s) {
                        a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M);
 }
 
-// Launch shapes with a compile-time K loop (the ones the heuristic picks for common K),
-// otherwise the runtime-loop kernel for that (NWK, RBW).
+// Launch shapes (waves along K, row blocks per wave, super-blocks per wave) with a
+// compile-time K loop, and the (waves, row blocks) pairs that also exist with a runtime loop.
+#define KMQ_MFMA_SHAPES(X) \
+    X(8, 1, 1) X(8, 1, 2) X(8, 1, 4) X(4, 1, 3) X(4, 1, 4) X(2, 1, 3) \
+    X(6, 1, 1) X(6, 1, 2) X(3, 1, 2) \
+    X(4, 2, 2) X(4, 2, 4) X(4, 2, 8) X(6, 2, 1) X(8, 2, 2) \
+    X(6, 3, 1) X(8, 3, 2)
+#define KMQ_MFMA_RT_SHAPES(X) \
+    X(8, 1) X(4, 1) X(2, 1) X(1, 1) X(8, 2) X(4, 2) X(2, 2) X(1, 2)
+
 template <int BITS>
 static void launch_mfma_bits(const GemmArgs& a, int nwk, int rbw, int spw, hipStream_t s) {
-#define KMQ_MFMA_TRY(NWK_, RBW_, SPW_) \
+#define X(NWK_, RBW_, SPW_) \
     if (nwk == NWK_ && rbw == RBW_ && spw == SPW_) { launch_mfma_one<BITS, NWK_, RBW_, SPW_>(a, s); return; }
-    KMQ_MFMA_TRY(8, 1, 1) KMQ_MFMA_TRY(8, 1, 2) KMQ_MFMA_TRY(8, 1, 4)
-    KMQ_MFMA_TRY(4, 2, 2) KMQ_MFMA_TRY(4, 2, 4) KMQ_MFMA_TRY(4, 2, 8)
-    KMQ_MFMA_TRY(2, 1, 3) KMQ_MFMA_TRY(4, 1, 3) KMQ_MFMA_TRY(4, 1, 4)
-    KMQ_MFMA_TRY(6, 1, 1) KMQ_MFMA_TRY(6, 1, 2) KMQ_MFMA_TRY(3, 1, 2)
-#undef KMQ_MFMA_TRY
-#define KMQ_MFMA_RT(NWK_, RBW_) \
+    KMQ_MFMA_SHAPES(X)
+#undef X
+#define X(NWK_, RBW_) \
     if (nwk == NWK_ && rbw == RBW_) { launch_mfma_one<BITS, NWK_, RBW_, 0>(a, s); return; }
-    KMQ_MFMA_RT(8, 1) KMQ_MFMA_RT(4, 1) KMQ_MFMA_RT(2, 1) KMQ_MFMA_RT(1, 1)
-    KMQ_MFMA_RT(8, 2) KMQ_MFMA_RT(4, 2) KMQ_MFMA_RT(2, 2) KMQ_MFMA_RT(1, 2)
-#undef KMQ_MFMA_RT
-    launch_mfma_one<BITS, 1, 1, 0>(a, s);
+    KMQ_MFMA_RT_SHAPES(X)
+#undef X
+    launch_mfma_one<BITS, 1, 1, 0>(a, s);                  // any K the layout allows, one wave per row block
+}
+
+static bool mfma_has_shape(int nwk, int rbw, int spw) {
+#define X(NWK_, RBW_, SPW_) if (nwk == NWK_ && rbw == RBW_ && spw == SPW_) return true;
+    KMQ_MFMA_SHAPES(X)
+#undef X
+#define X(NWK_, RBW_) if (nwk == NWK_ && rbw == RBW_) return true;
+    KMQ_MFMA_RT_SHAPES(X)
+#undef X
+    return false;
 }
 
 // Tuning override for sweeps: KMQ_MFMA_NWK / KMQ_MFMA_RBW in the environment (read once).
@@ -334,30 +348,45 @@ static int env_int(const char* name) {
     return v ? std::atoi(v) : 0;
 }
 
-// Row blocks per wave: two from 512 row blocks (N >= 8192) on, where the grid still has
-// more than one workgroup per CU and sharing the activation tile between two row blocks
-// saves a quarter of the vector instructions (measured on 14336 x 4096: 14.4 -> 11.7 us).
-// 1-bit granules already carry 16 steps each and measured faster with one row block.
-int mfma_row_blocks(int64_t N, int bits) {
-    static const int forced = env_int("KMQ_MFMA_RBW");
-    if (forced == 1 || forced == 2) return forced;
-    return (bits >= 2 && (N + 15) / 16 >= 2 * 256) ? 2 : 1;
-}
-
-// Waves along K: the largest of 8 (4 with two row blocks per wave), 6, 4, 3, 2, 1 that
-// divides the number of super-blocks (6 and 3 serve K = 3072 at 1 bit: six super-blocks).
-int mfma_waves_along_k(int64_t N, int64_t K, int bits) {
+// Waves along K for `rbw` row blocks per wave: the largest of 8, 6, 4, 3, 2, 1 that divides
+// the number of super-blocks and has a kernel.  With two or more row blocks per wave and
+// 2..4-bit decoding, more than 4 waves measured slower (registers).
+static int waves_along_k(int64_t K, int bits, int rbw) {
     static const int forced = env_int("KMQ_MFMA_NWK");
-    const int64_t nsb = K / tiled_superblock_elems(bits);
-    const int cap = forced ? forced : (mfma_row_blocks(N, bits) >= 2 ? 4 : 8);
+    const int nsb = static_cast<int>(K / tiled_superblock_elems(bits));
+    const int cap = forced ? forced : ((bits >= 2 && rbw >= 2) ? 4 : 8);
     static const int kChoices[] = {8, 6, 4, 3, 2};
     for (int w : kChoices)
-        if (nsb % w == 0 && w <= cap && (w != 6 && w != 3 || nsb / w <= 2)) return w;
+        if (nsb % w == 0 && w <= cap && mfma_has_shape(w, rbw, nsb / w)) return w;
     return 1;
 }
 
+// Row blocks per wave.  Every workgroup reads all of X through the L1, so fewer, fatter
+// workgroups cut that traffic (it is 16x the index bytes at 1 bit with one row block), but
+// the grid should still come out even over the 256 CUs: the cost model is (rounds of 256
+// workgroups) x (row blocks per workgroup), ties go to the fatter workgroup.  Measured
+// (us): 9216 x 3072, 1-bit, M = 16: 7.8 / 7.9 / 6.6 / 7.6 for 1 / 2 / 3 / 4 row blocks;
+// 14336 x 4096, 3-bit, M = 16: 13.2 / 11.1 / - / 12.5.
+int mfma_row_blocks(int64_t N, int64_t K, int bits) {
+    static const int forced = env_int("KMQ_MFMA_RBW");
+    const int64_t nrb = (N + 15) / 16;
+    const int max_rbw = bits == 1 ? 3 : 2;
+    int best = 1;
+    int64_t best_cost = 0;
+    for (int r = 1; r <= max_rbw; ++r) {
+        if (forced && r != forced) continue;
+        const int w = waves_along_k(K, bits, r);
+        if (r > 1 && !mfma_has_shape(w, r, static_cast<int>(K / tiled_superblock_elems(bits) / w))) continue;
+        const int64_t wgs = (nrb + r - 1) / r, cost = ((wgs + 255) / 256) * r;
+        if (best_cost == 0 || cost <= best_cost) { best = r; best_cost = cost; }
+    }
+    return best;
+}
+
+int mfma_waves_along_k(int64_t N, int64_t K, int bits) { return waves_along_k(K, bits, mfma_row_blocks(N, K, bits)); }
+
 hipError_t launch_mfma(const GemmArgs& a, hipStream_t s) {
-    const int nwk = mfma_waves_along_k(a.N, a.K, a.bits), rbw = mfma_row_blocks(a.N, a.bits);
+    const int rbw = mfma_row_blocks(a.N, a.K, a.bits), nwk = waves_along_k(a.K, a.bits, rbw);
     const int spw = static_cast<int>(a.K / tiled_superblock_elems(a.bits) / nwk);
     switch (a.bits) {
         case 1: launch_mfma_bits<1>(a, nwk, rbw, spw, s); break;
