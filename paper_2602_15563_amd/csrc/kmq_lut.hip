@@ -44,7 +44,7 @@ namespace kmq {
 typedef __attribute__((address_space(3))) const uint32_t lds_cu32_t;
 
 // ---- hand-scheduled blocks -----------------------------------------------------
-// `a` holds eight address registers whose bytes 1..3 are the table base.
+// `a` holds four address registers whose bytes 1..3 are the table base.
 
 // The LGKM counter of a wave has 4 bits: at most 15 LDS/scalar-memory operations
 // may be outstanding, or s_waitcnt lgkmcnt(n) stops meaning what it says.  The
@@ -55,7 +55,7 @@ typedef __attribute__((address_space(3))) const uint32_t lds_cu32_t;
 // v[4H..4H+3]; v[2i] belongs to nibble 2i (even).  re/ro are the rotated words,
 // produced when H == 0 and reused when H == 1.
 template <int OFF, int H>
-__device__ __forceinline__ void issue4_b32(uint32_t word, uint32_t& re, uint32_t& ro, uint32_t (&a)[8],
+__device__ __forceinline__ void issue4_b32(uint32_t word, uint32_t& re, uint32_t& ro, uint32_t (&a)[4],
                                            uint32_t (&v)[8], uint32_t mask) {
     if constexpr (H == 0) {
         asm volatile(
@@ -83,7 +83,7 @@ __device__ __forceinline__ void issue4_b32(uint32_t word, uint32_t& re, uint32_t
             "ds_read_b32 %2, %6 offset:%c11\n\t"
             "ds_read_b32 %3, %7 offset:%c11"
             : "=&v"(v[4]), "=&v"(v[5]), "=&v"(v[6]), "=&v"(v[7]),
-              "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+              "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3])
             : "v"(re), "v"(ro), "v"(mask), "n"(OFF));
     }
 }
@@ -131,7 +131,7 @@ __device__ __forceinline__ void consume8_fma(const uint32_t (&v)[8], const uint3
 // returns four bf16 {0,1} masks.  re/ro are the rotated words, produced when
 // H == 0 and reused when H == 1.  vv[2i] belongs to the even nibble.
 template <int H>
-__device__ __forceinline__ void issue4_b64(uint32_t word, uint32_t& re, uint32_t& ro, uint32_t (&a)[8],
+__device__ __forceinline__ void issue4_b64(uint32_t word, uint32_t& re, uint32_t& ro, uint32_t (&a)[4],
                                            u32x2_t (&vv)[4], uint32_t mask) {
     if constexpr (H == 0) {
         asm volatile(
@@ -159,7 +159,7 @@ __device__ __forceinline__ void issue4_b64(uint32_t word, uint32_t& re, uint32_t
             "ds_read_b64 %2, %6\n\t"
             "ds_read_b64 %3, %7"
             : "=&v"(vv[0]), "=&v"(vv[1]), "=&v"(vv[2]), "=&v"(vv[3]),
-              "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+              "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3])
             : "v"(re), "v"(ro), "v"(mask));
     }
 }
@@ -373,9 +373,11 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     // ---- 5. lookups and multiply-accumulate, one unit ahead -------------------------------------
     const uint32_t lut_base = static_cast<uint32_t>(reinterpret_cast<size_t>(
         (lds_cu32_t*)(&sm.lut[BITS == 1 ? 0 : wave * RPL + sub][0])));
-    uint32_t ar[8];
+    // Four address registers serve both halves of a unit: a DS instruction has read its
+    // address when it issues, so the next half may overwrite the low byte right behind it.
+    uint32_t ar[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) ar[i] = lut_base;
+    for (int i = 0; i < 4; ++i) ar[i] = lut_base;
     // Everything the compiler itself has in flight on the LGKM counter (the reads of
     // x above) must have landed before the hand-counted pipeline starts.
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
