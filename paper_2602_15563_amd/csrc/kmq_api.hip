@@ -20,7 +20,7 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout) {
         return Plan{kVariantMfma, -1, 0, names[bits - 1]};
     }
     if (M == 1) {
-        const int l = lut_find(K, bits, layout);
+        const int l = lut_find(N, K, bits, layout);
         if (l >= 0) return Plan{kVariantLut, l, 0, lut_name(l)};
         const int i = rowsplit_find(K, bits, layout);
         if (i >= 0) return Plan{kVariantRowsplit, i, 0, rowsplit_name(i)};

@@ -55,7 +55,7 @@ int mfma_waves_along_k(int64_t N, int64_t K, int bits);
 int mfma_row_blocks(int64_t N, int64_t K, int bits);
 
 // Hand-scheduled table kernels (1/2/4-bit): -1 if (bits, K, layout) has none.
-int lut_find(int64_t K, int bits, int layout);
+int lut_find(int64_t N, int64_t K, int bits, int layout);
 const char* lut_name(int table_index);
 hipError_t launch_lut_entry(int table_index, const GemmArgs& a, hipStream_t s);
 

@@ -475,6 +475,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
 struct LutEntry {
     int bits;
     int64_t K;
+    int rows_wg;
     const char* name;
     void (*launch)(const GemmArgs&, hipStream_t);
 };
@@ -488,15 +489,21 @@ static void launch_lut(const GemmArgs& a, hipStream_t s) {
 }
 
 #define KMQ_LUT(BITS, G, LPR, NWK, NWR, RS, WPE) \
-    { BITS, int64_t(NWK) * LPR * (G * 32 / BITS), \
+    { BITS, int64_t(NWK) * LPR * (G * 32 / BITS), NWR * (64 / LPR) * RS, \
       "lut_b" #BITS "_g" #G "_l" #LPR "_k" #NWK "_r" #NWR "x" #RS, &launch_lut<BITS, G, LPR, NWK, NWR, RS, WPE> }
 
 static const LutEntry kLut[] = {
+    // Several shapes may serve one (bits, K): lut_find takes the one whose grid comes out
+    // most even over the CUs for the given N; the first listed wins ties.
     // 1-bit
-    KMQ_LUT(1, 4, 16, 1, 4, 1, 4),   // K = 2048
-    KMQ_LUT(1, 3, 32, 1, 4, 2, 4),   // K = 3072
+    KMQ_LUT(1, 4, 16, 1, 4, 1, 4),   // K = 2048, 16 rows per workgroup
+    KMQ_LUT(1, 4, 16, 1, 2, 1, 4),   //            8
+    KMQ_LUT(1, 3, 32, 1, 4, 2, 4),   // K = 3072, 16
+    KMQ_LUT(1, 3, 32, 1, 3, 3, 4),   //           18
+    KMQ_LUT(1, 3, 32, 1, 3, 2, 4),   //           12
     KMQ_LUT(1, 4, 32, 1, 4, 2, 4),   // K = 4096
-    KMQ_LUT(1, 4, 64, 1, 4, 2, 4),   // K = 8192
+    KMQ_LUT(1, 4, 64, 1, 4, 2, 4),   // K = 8192,  8
+    KMQ_LUT(1, 4, 64, 1, 4, 3, 4),   //           12
     // 2-bit
     KMQ_LUT(2, 4, 32, 1, 4, 2, 6),   // K = 2048
     KMQ_LUT(2, 3, 64, 1, 4, 2, 6),   // K = 3072
@@ -511,11 +518,19 @@ static const LutEntry kLut[] = {
 };
 constexpr int kLutCount = sizeof(kLut) / sizeof(kLut[0]);
 
-int lut_find(int64_t K, int bits, int layout) {
+// Cost of a shape for N rows: the most rows any CU gets when the workgroups are dealt
+// round-robin over 256 CUs.
+int lut_find(int64_t N, int64_t K, int bits, int layout) {
     if (layout != KMQ_LAYOUT_CANONICAL) return -1;
-    for (int i = 0; i < kLutCount; ++i)
-        if (kLut[i].bits == bits && kLut[i].K == K) return i;
-    return -1;
+    int best = -1;
+    int64_t best_cost = 0;
+    for (int i = 0; i < kLutCount; ++i) {
+        if (kLut[i].bits != bits || kLut[i].K != K) continue;
+        const int64_t wgs = (N + kLut[i].rows_wg - 1) / kLut[i].rows_wg;
+        const int64_t cost = ((wgs + 255) / 256) * kLut[i].rows_wg;
+        if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
+    }
+    return best;
 }
 
 const char* lut_name(int i) { return kLut[i].name; }

@@ -122,6 +122,22 @@ def test_specialised_gemv_vs_oracle(gpu, bits, K, N):
     gpu.check_against_oracle(Yg, oracle.pack(idx, bits), cb, X, K, bits, label=f"b{bits} {N}x{K}")
 
 
+@pytest.mark.parametrize("bits,K,N,shape", [
+    (1, 2048, 4090, "_r4x1"), (1, 2048, 2040, "_r2x1"),
+    (1, 3072, 9209, "_r3x3"), (1, 3072, 8190, "_r4x2"), (1, 3072, 3070, "_r3x2"),
+    (1, 8192, 3065, "_r4x3"), (1, 8192, 2047, "_r4x2"),
+])
+def test_gemv_shape_choice_by_rows(gpu, bits, K, N, shape):
+    """Where several launch shapes serve one (bits, K), the row count picks the one whose
+    grid is most even over the CUs; every such shape at an N that selects it, ragged."""
+    from paper_2602_15563_amd import kmq
+    assert kmq.kernel_name(N, K, bits, 1).endswith(shape), kmq.kernel_name(N, K, bits, 1)
+    idx, cb, X = _small_case(7 * bits + N + K, N, K, bits, 1)
+    p = kmq.pack(idx, bits)
+    Yg = gpu.run_gemm(gpu.dev(p), gpu.dev(cb), X[0], N, K, bits)
+    gpu.check_against_oracle(Yg, oracle.pack(idx, bits), cb, X, K, bits, label=f"b{bits} {N}x{K}")
+
+
 @pytest.mark.parametrize("bits,K", [(2, 4096), (2, 14336), (3, 4096), (4, 4096), (2, 100), (3, 515), (4, 33)])
 def test_one_hot_probe_is_bit_exact(gpu, bits, K):
     """x = e_k makes every output a single weight: y[n] must equal the bf16
