@@ -9,7 +9,7 @@ replayed from a HIP graph so that launch overhead from Python is not measured
 (the protocol of the paper's App. E "Micro-benchmarks", adapted to HIP).
 
 Prints ONE JSON line on stdout.  `--table` additionally writes per-shape
-numbers for every contract configuration to gpurun_out/bench_table.json.
+numbers for every contract configuration to bench_table.json in the output folder (--out).
 """
 from __future__ import annotations
 
@@ -247,7 +247,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the timed region, launch a plain 64 MiB device copy 10 times: a kernel of known "
                          "traffic against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
-    ap.add_argument("--table", action="store_true", help="also time every contract shape -> gpurun_out/bench_table.json")
+    ap.add_argument("--table", action="store_true", help="also time every contract shape -> <out>/bench_table.json")
+    ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out"), help="folder for bench_table.json")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); "
@@ -305,8 +306,8 @@ def main():
             print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
             del it
             torch.cuda.empty_cache()
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:
+        os.makedirs(args.out, exist_ok=True)
+        with open(os.path.join(args.out, "bench_table.json"), "w") as f:
             json.dump(rows, f, indent=1)
 
     print(json.dumps(out), flush=True)
