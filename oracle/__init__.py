@@ -6,7 +6,9 @@ single-threaded) with numpy marshalling and nothing else; it never touches the
 GPU library and shares no code with it.
 
 The operation is the fused dequantise-multiply of the paper's App. E
-("Kernel implementations"), with per-output-row codebooks and no block scales.
+("Kernel implementations"), with per-output-row codebooks and no block scales
+(``gemm``), and in the paper's own format, a tensor-wide codebook with one bf16
+scale per block of 64 elements along K (``gemm_blockscaled``).
 """
 from __future__ import annotations
 
@@ -50,6 +52,8 @@ def _load():
         lib.oracle_round_bf16.argtypes = [ctypes.c_double]
         lib.oracle_gemm.restype = ci
         lib.oracle_gemm.argtypes = [vp, vp, vp, i64, i64, ci, i64, i64, i64, vp, vp, vp]
+        lib.oracle_gemm_blockscaled.restype = ci
+        lib.oracle_gemm_blockscaled.argtypes = [vp, vp, vp, vp, i64, i64, ci, i64, i64, i64, i64, ci, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -131,6 +135,38 @@ def gemm(packed: np.ndarray, codebook: np.ndarray, X: np.ndarray, K: int, bits: 
     Yb = np.zeros((M, N), dtype=np.uint16)
     if _load().oracle_gemm(_p(packed), _p(codebook), _p(X2), N, K, bits, M, n0, n1,
                            _p(Y), _p(A), _p(Yb)):
+        raise ValueError("bad argument")
+    if vec:
+        return Y[0], A[0], Yb[0]
+    return Y, A, Yb
+
+
+def gemm_blockscaled(packed: np.ndarray, codebook: np.ndarray, scales: np.ndarray, X: np.ndarray,
+                     K: int, bits: int, block: int = 64, rows: tuple[int, int] | None = None,
+                     deferred: bool = False):
+    """Y = X W^T with w[n][k] = codebook[idx[n][k]] * scales[n][k // block], fp64.
+
+    codebook: uint16 bf16 patterns, shape (2^bits,), shared by all rows; scales:
+    uint16 bf16 patterns, shape (N, K // block).  Returns (Y, A, Ybf16) as ``gemm``.
+    """
+    N = packed.shape[0]
+    packed = _arr(packed, np.uint32, (N, words_per_row(bits, K)))
+    codebook = _arr(codebook, np.uint16, (1 << bits,))
+    if K % block:
+        raise ValueError("K must be a multiple of the block size")
+    scales = _arr(scales, np.uint16, (N, K // block))
+    X = np.ascontiguousarray(X, dtype=np.uint16)
+    vec = X.ndim == 1
+    X2 = X.reshape(1, -1) if vec else X
+    M = X2.shape[0]
+    if X2.shape[1] != K:
+        raise ValueError("X has the wrong K")
+    n0, n1 = (0, N) if rows is None else rows
+    Y = np.full((M, N), np.nan, dtype=np.float64)
+    A = np.full((M, N), np.nan, dtype=np.float64)
+    Yb = np.zeros((M, N), dtype=np.uint16)
+    if _load().oracle_gemm_blockscaled(_p(packed), _p(codebook), _p(scales), _p(X2), N, K, bits, block, M,
+                                       n0, n1, int(deferred), _p(Y), _p(A), _p(Yb)):
         raise ValueError("bad argument")
     if vec:
         return Y[0], A[0], Yb[0]

@@ -29,6 +29,20 @@
 //   * every row starts on a fresh word, rows hold ceil(K*b/32) words, pad bits
 //     are zero.
 //
+// A second entry point, oracle_gemm_blockscaled, states the paper's own weight
+// format (Sec. 2.2 "Nonlinear k-means quantization": centroids shared by the whole
+// tensor, one 16-bit scale per block of B consecutive elements along K; App. E
+// "Kernel implementations", the reference routine and its deferred-scaling
+// variant):
+//
+//     w[n][k] = real( codebook[ idx[n][k] ] ) * real( scale[n][k / B] )
+//     Y[m][n] = sum_k w[n][k] * real( X[m][k] )
+//
+// The product of three bf16 values has at most 24 significant bits: still exact
+// in fp64.  "Immediate" sums c*s*x over k ascending; "deferred" sums c*x inside a
+// block and multiplies the block sum by s, the order the appendix gives as a
+// variant.  Both are the same real number; they differ by fp64 rounding only.
+//
 // Pins (tests/test_oracle_*.py): literal hand-computed words, round trips,
 // brute-force dense products from the unpacked uint8 indices, the 1-bit closed
 // form, one-hot / constant-codebook / scaling / permutation invariants, and the
@@ -156,6 +170,43 @@ int oracle_gemm(const uint32_t* packed, const uint16_t* codebook, const uint16_t
                 double t = w[k] * bf16_to_double(X[m * K + k]);
                 y += t;
                 a += std::fabs(t);
+            }
+            Y[m * N + n] = y;
+            if (A) A[m * N + n] = a;
+            if (Ybf16) Ybf16[m * N + n] = oracle_round_bf16(y);
+        }
+    }
+    return 0;
+}
+
+// Block-scaled product with a tensor-wide codebook of 2^bits bf16 centroids and
+// scales[N][K/B] (bf16).  K must be a multiple of B.  deferred = 0: c*s*x summed
+// over k ascending; deferred = 1: per-block sums of c*x, each multiplied by its
+// scale, blocks ascending.  A = sum_k |c*s*x| either way.  Rows [n0, n1).
+int oracle_gemm_blockscaled(const uint32_t* packed, const uint16_t* codebook, const uint16_t* scales,
+                            const uint16_t* X, int64_t N, int64_t K, int bits, int64_t B, int64_t M,
+                            int64_t n0, int64_t n1, int deferred, double* Y, double* A,
+                            uint16_t* Ybf16) {
+    if (!bits_ok(bits) || N < 0 || K < 0 || M < 0 || B < 1 || K % B != 0 || n0 < 0 || n1 > N || n0 > n1)
+        return 1;
+    const int64_t wpr = words_per_row(bits, K);
+    const int64_t G = K / B;
+    std::vector<double> c(static_cast<size_t>(K));
+    for (int64_t n = n0; n < n1; ++n) {
+        for (int64_t k = 0; k < K; ++k)
+            c[k] = bf16_to_double(codebook[read_field(packed + n * wpr, k, bits)]);
+        for (int64_t m = 0; m < M; ++m) {
+            double y = 0.0, a = 0.0;
+            for (int64_t g = 0; g < G; ++g) {
+                const double s = bf16_to_double(scales[n * G + g]);
+                double z = 0.0;
+                for (int64_t k = g * B; k < (g + 1) * B; ++k) {
+                    const double x = bf16_to_double(X[m * K + k]);
+                    if (deferred) z += c[k] * x;
+                    else y += (c[k] * s) * x;
+                    a += std::fabs((c[k] * s) * x);
+                }
+                if (deferred) y += z * s;
             }
             Y[m * N + n] = y;
             if (A) A[m * N + n] = a;

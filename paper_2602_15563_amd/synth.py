@@ -10,8 +10,16 @@ linear layers of Llama-style models; its checkpoints are not used here.
 Uniform-random indices stand in for k-means indices of trained weights and
 N(0, 0.02) centroids for learned centroids.
 
+For the paper's own weight format (Sec. 2.2 "Nonlinear k-means quantization":
+centroids in [-1, 1] shared by the tensor, one bf16 scale per block of 64
+elements) the stand-ins are: centroids ~ N(0, 0.45) clipped to [-1, 1] and
+sorted (1-bit: (-t, +t), t ~ U(0.5, 0.9)), and scales distributed like the
+absolute maximum of 64 samples of N(0, 0.02), the scale an absmax-normalised
+block of such weights would get.
+
 Generator: numpy's counter-based Philox, keyed by (seed, stream) where
-stream = matrix_number * 16 + kind, kind in {0: indices, 1: codebook, 2: x}.
+stream = matrix_number * 16 + kind, kind in {0: indices, 1: codebook, 2: x,
+3: block scales, 4: tensor-wide codebook}.
 Normal samples are drawn in fp64, narrowed to fp32, then rounded to bf16 with
 round-to-nearest-even; codebooks are sorted after rounding.
 """
@@ -21,7 +29,8 @@ from dataclasses import dataclass
 
 import numpy as np
 
-KIND_IDX, KIND_CODEBOOK, KIND_X = 0, 1, 2
+KIND_IDX, KIND_CODEBOOK, KIND_X, KIND_SCALE, KIND_SHARED_CODEBOOK = 0, 1, 2, 3, 4
+BLOCK = 64      # elements per scale along K
 SIGMA_W = 0.02  # standard deviation of the centroid distribution
 
 
@@ -74,6 +83,30 @@ def make_codebook(seed: int, matrix: int, N: int, bits: int, symmetric: bool = F
 def make_x(seed: int, matrix: int, M: int, K: int) -> np.ndarray:
     """uint16 bf16 X[M][K] ~ N(0, 1)."""
     return f32_to_bf16(rng(seed, matrix, KIND_X).standard_normal(size=(M, K)).astype(np.float32))
+
+
+def make_shared_codebook(seed: int, matrix: int, bits: int) -> np.ndarray:
+    """uint16 bf16 codebook[2^bits] shared by all rows, values in [-1, 1], sorted ascending."""
+    g = rng(seed, matrix, KIND_SHARED_CODEBOOK)
+    if bits == 1:
+        t = f32_to_bf16(np.array([g.uniform(0.5, 0.9)], dtype=np.float32))[0]
+        return np.array([t | np.uint16(0x8000), t], dtype=np.uint16)
+    c = f32_to_bf16(np.clip(g.normal(0.0, 0.45, size=1 << bits), -1.0, 1.0).astype(np.float32))
+    return c[np.argsort(bf16_to_f32(c), kind="stable")]
+
+
+def make_scales(seed: int, matrix: int, N: int, K: int, block: int = BLOCK) -> np.ndarray:
+    """uint16 bf16 scales[N][K // block] > 0, distributed like max |z_j|, j < block, z ~ N(0, SIGMA_W).
+
+    Drawn by inverting the distribution function of that maximum,
+    P(max <= t) = (2 Phi(t / sigma) - 1)^block, so one uniform sample per block suffices.
+    """
+    from scipy.special import ndtri
+    if K % block:
+        raise ValueError("K must be a multiple of the block size")
+    u = rng(seed, matrix, KIND_SCALE).uniform(0.0, 1.0, size=(N, K // block))
+    t = SIGMA_W * ndtri(0.5 * (1.0 + u ** (1.0 / block)))
+    return f32_to_bf16(np.maximum(t, 1e-6).astype(np.float32))
 
 
 # ---- the benchmark contract's five configurations ----------------------------
