@@ -136,6 +136,31 @@ kmq_status kmq_gemm_smallbatch(const uint32_t* W, const uint16_t* codebook, cons
 kmq_status kmq_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wdense,
                        int64_t N, int64_t K, int bits, int layout, void* hip_stream);
 
+/* ---- The paper's own weight format: tensor-wide codebook + block scales -------------
+ * Sec. 2.2 "Nonlinear k-means quantization": the centroids (values in [-1, 1]) are shared
+ * by the whole tensor and every block of KMQ_BLOCK = 64 consecutive elements of a row has
+ * one 16-bit scale; App. E "Kernel implementations" gives the reference routine
+ * (lookup, multiply by the block's scale, matrix product) and the deferred-scaling
+ * variant (scale each block's partial sum), which is what these calls compute:
+ *
+ *     Y[m][n] = sum_g scale[n][g] * sum_{k in block g} codebook[idx[n][k]] * X[m][k]
+ *
+ * with both sums in fp32 and one rounding to bf16 at the end.
+ *   W         packed indices, KMQ_LAYOUT_CANONICAL only (else KMQ_ERR_LAYOUT), 16-byte aligned
+ *   codebook  2^bits bf16 bit patterns (4-byte aligned)
+ *   scales    N x K/64 bf16 bit patterns, row-major (2-byte aligned); K % 64 != 0 -> KMQ_ERR_SHAPE
+ *   x / X, y / Y, M, workspace, hip_stream: as kmq_gemv / kmq_gemm_smallbatch.
+ * All pointers are DEVICE pointers owned by the caller; nothing is allocated or synchronised. */
+#define KMQ_BLOCK 64
+kmq_status kmq_gemv_blockscaled(const uint32_t* W, const uint16_t* codebook, const uint16_t* scales,
+                                const uint16_t* x, uint16_t* y, int64_t N, int64_t K, int bits, int layout,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+kmq_status kmq_gemm_smallbatch_blockscaled(const uint32_t* W, const uint16_t* codebook, const uint16_t* scales,
+                                           const uint16_t* X, uint16_t* Y, int64_t N, int64_t K, int M, int bits,
+                                           int layout, void* workspace, size_t workspace_bytes, void* hip_stream);
+/* As kmq_kernel_name, for the block-scaled calls. */
+const char* kmq_kernel_name_blockscaled(int64_t N, int64_t K, int bits, int M, int layout);
+
 /* Name of the kernel variant the launch heuristic picks for this problem
  * (static string, never NULL; "invalid" on bad arguments).  For reports. */
 const char* kmq_kernel_name(int64_t N, int64_t K, int bits, int M, int layout);

@@ -10,10 +10,18 @@ namespace kmq {
 
 // Launch-shape heuristic (the paper autotunes chunk shapes per problem, App. E
 // "Kernel implementations"; here the choice is a static function of the shape).
-Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout) {
+Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled) {
     Plan p{kVariantInvalid, -1, 0, "invalid"};
     if (!bits_valid(bits) || !dims_valid(N, K) || M < 1 || M > KMQ_MAX_BATCH) return p;
     if (layout != KMQ_LAYOUT_CANONICAL && layout != KMQ_LAYOUT_TILED) return p;
+    if (scaled) {
+        if (layout != KMQ_LAYOUT_CANONICAL || K % KMQ_BLOCK != 0) return p;
+        if (M == 1) {
+            const int l = lut_find(N, K, bits, layout, true);
+            if (l >= 0) return Plan{kVariantLut, l, 0, lut_name(l)};
+        }
+        return Plan{kVariantBlockGeneric, -1, 0, "blockscaled_generic"};
+    }
     if (layout == KMQ_LAYOUT_TILED && !tiled_valid(bits, K)) return p;
     if (layout == KMQ_LAYOUT_TILED) {
         static const char* const names[4] = {"mfma_b1", "mfma_b2", "mfma_b3", "mfma_b4"};
@@ -46,7 +54,13 @@ static kmq_status check_and_run(const GemmArgs& a, void* stream) {
     if (a.layout != KMQ_LAYOUT_CANONICAL && a.layout != KMQ_LAYOUT_TILED) return KMQ_ERR_LAYOUT;
     if (a.layout == KMQ_LAYOUT_TILED && !tiled_valid(a.bits, a.K)) return KMQ_ERR_LAYOUT;
     if (!aligned(a.W, 16) || !aligned(a.X, 16) || !aligned(a.codebook, 4) || !aligned(a.Y, 2)) return KMQ_ERR_ALIGN;
-    const Plan plan = make_plan(a.N, a.K, a.bits, a.M, a.layout);
+    const bool scaled = a.scales != nullptr;
+    if (scaled) {
+        if (a.layout != KMQ_LAYOUT_CANONICAL) return KMQ_ERR_LAYOUT;
+        if (a.K % KMQ_BLOCK != 0) return KMQ_ERR_SHAPE;
+        if (!aligned(a.scales, 2)) return KMQ_ERR_ALIGN;
+    }
+    const Plan plan = make_plan(a.N, a.K, a.bits, a.M, a.layout, scaled);
     if (plan.variant == kVariantInvalid) return KMQ_ERR_SHAPE;
     if (plan.workspace_bytes > 0 && (!a.workspace || a.workspace_bytes < plan.workspace_bytes)) return KMQ_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -55,6 +69,7 @@ static kmq_status check_and_run(const GemmArgs& a, void* stream) {
         case kVariantMfma: e = launch_mfma(a, s); break;
         case kVariantLut: e = launch_lut_entry(plan.table_index, a, s); break;
         case kVariantRowsplit: e = launch_rowsplit(plan.table_index, a, s); break;
+        case kVariantBlockGeneric: e = launch_blockscaled_generic(a, s); break;
         default: e = launch_generic(a, s); break;
     }
     return hip_status(e);
@@ -84,6 +99,25 @@ kmq_status kmq_gemv(const uint32_t* W, const uint16_t* codebook, const uint16_t*
                     void* workspace, size_t workspace_bytes, void* hip_stream) {
     const kmq::GemmArgs a{W, codebook, x, y, N, K, 1, bits, layout, workspace, workspace_bytes};
     return kmq::check_and_run(a, hip_stream);
+}
+
+kmq_status kmq_gemm_smallbatch_blockscaled(const uint32_t* W, const uint16_t* codebook, const uint16_t* scales,
+                                           const uint16_t* X, uint16_t* Y, int64_t N, int64_t K, int M, int bits,
+                                           int layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!scales) return KMQ_ERR_NULL;
+    const kmq::GemmArgs a{W, codebook, X, Y, N, K, M, bits, layout, workspace, workspace_bytes, scales};
+    return kmq::check_and_run(a, hip_stream);
+}
+
+kmq_status kmq_gemv_blockscaled(const uint32_t* W, const uint16_t* codebook, const uint16_t* scales,
+                                const uint16_t* x, uint16_t* y, int64_t N, int64_t K, int bits, int layout,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return kmq_gemm_smallbatch_blockscaled(W, codebook, scales, x, y, N, K, 1, bits, layout, workspace,
+                                           workspace_bytes, hip_stream);
+}
+
+const char* kmq_kernel_name_blockscaled(int64_t N, int64_t K, int bits, int M, int layout) {
+    return kmq::make_plan(N, K, bits, M, layout, true).name;
 }
 
 kmq_status kmq_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wdense,

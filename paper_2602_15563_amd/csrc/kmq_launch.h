@@ -18,6 +18,7 @@ struct GemmArgs {
     int M, bits, layout;
     void* workspace;
     size_t workspace_bytes;
+    const uint16_t* scales = nullptr;   // block-scaled format: N x K/64 bf16, and `codebook` is one tensor-wide table
 };
 
 // Kernel variants the heuristic can pick (kmq_kernel_name reports them).
@@ -27,6 +28,7 @@ enum Variant {
     kVariantRowsplit,    // batch 1, K from a table: x in registers, LUT in LDS (compiler-scheduled; 3-bit)
     kVariantLut,         // batch 1, 1/2/4-bit, K from a table: hand-scheduled LDS-table kernel
     kVariantMfma,        // tiled layout, batch 1..16: matrix-core kernel
+    kVariantBlockGeneric,  // block-scaled format, any shape with K % 64 == 0
 };
 
 struct Plan {
@@ -36,7 +38,7 @@ struct Plan {
     const char* name;
 };
 
-Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout);
+Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled = false);
 
 hipError_t launch_generic(const GemmArgs& a, hipStream_t s);
 hipError_t launch_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd, int64_t N,
@@ -47,6 +49,8 @@ int rowsplit_find(int64_t K, int bits, int layout);
 const char* rowsplit_name(int table_index);
 hipError_t launch_rowsplit(int table_index, const GemmArgs& a, hipStream_t s);
 
+hipError_t launch_blockscaled_generic(const GemmArgs& a, hipStream_t s);
+
 hipError_t launch_stream_read(const void* p, size_t bytes, void* sink, hipStream_t s);
 
 // Matrix-core kernel (tiled layout only).
@@ -55,7 +59,7 @@ int mfma_waves_along_k(int64_t N, int64_t K, int bits);
 int mfma_row_blocks(int64_t N, int64_t K, int bits);
 
 // Hand-scheduled table kernels (1/2/4-bit): -1 if (bits, K, layout) has none.
-int lut_find(int64_t N, int64_t K, int bits, int layout);
+int lut_find(int64_t N, int64_t K, int bits, int layout, bool scaled = false);
 const char* lut_name(int table_index);
 hipError_t launch_lut_entry(int table_index, const GemmArgs& a, hipStream_t s);
 

@@ -88,6 +88,14 @@ __device__ __forceinline__ void issue4_b32(uint32_t word, uint32_t& re, uint32_t
     }
 }
 
+// A dot instruction's result may feed the accumulator of the next dot at once, but any OTHER
+// vector instruction reading it needs three wait states (gfx90a and later).  The compiler
+// inserts those for its own code; it cannot see inside an asm block, so accumulators written
+// by the blocks below pass through this before ordinary code reads them.
+__device__ __forceinline__ void settle_dot(float& a0, float& a1) {
+    asm volatile("s_nop 2" : "+v"(a0), "+v"(a1));
+}
+
 // 2-bit: eight dot2 (two accumulator chains).  PENDING = LDS reads issued after
 // the eight this block consumes.
 template <int PENDING>
@@ -216,10 +224,16 @@ __device__ __forceinline__ void load_words(const uint32_t* p, uint32_t (&w)[G]) 
 
 // ---- the kernel ----------------------------------------------------------------------
 
-template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE>
+// SC selects the paper's own weight format (Sec. 2.2 "Nonlinear k-means quantization"):
+// `codebook` is one table of 2^BITS centroids shared by all rows and `scales` holds one bf16
+// per block of 64 elements of a row; a lane's slice is a whole number of blocks (or half of
+// one), so its fp32 block sums are scaled once, before the reduction over lanes (the
+// deferred-scaling variant of App. E "Kernel implementations").
+template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE, bool SC>
 __global__ __launch_bounds__(NWK * NWR * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
-                     const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int64_t N) {
+                     const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int64_t N,
+                     const uint16_t* __restrict__ scales) {
     static_assert(BITS == 1 || BITS == 2 || BITS == 4, "3-bit fields do not align with nibbles");
     constexpr int C = 1 << BITS;
     constexpr int EL = G * 32 / BITS;              // elements per lane and row slice
@@ -243,6 +257,9 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     constexpr int XSLOTS = XPT * NWK * NWR * 64;
     static_assert(RS <= 8 && (ROWS_WG % 2) == 0 && THREADS <= 1024, "launch shape");
     static_assert(EL % 8 == 0, "x slices are whole 16-byte chunks");
+    constexpr int NSC = EL >= KMQ_BLOCK ? EL / KMQ_BLOCK : 1;      // scales per lane and row slice
+    static_assert(!SC || EL % KMQ_BLOCK == 0 || KMQ_BLOCK % EL == 0, "lane slices must not straddle blocks");
+    static_assert(!SC || NSC == 1 || (BITS == 1 && NSC == 2), "block sums kept by the pipeline");
 
     struct alignas(256) Smem {
         // 2/4-bit: per wave and row group, RS tables of 16 x 4 B; 1-bit: lut[0] holds the 16 x 8 B mask table
@@ -286,6 +303,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         rw = rw < ROWS_WAVE ? rw : ROWS_WAVE - 1;
         int64_t row = wave_row0 + rw;
         row = row < N ? row : N - 1;
+        if constexpr (SC) row = 0;                                     // one table for the whole tensor
         if constexpr (BITS == 2) {
             const u32x2_t c = *reinterpret_cast<const u32x2_t*>(codebook + row * C);
             cbv[p][0] = c[0];
@@ -309,6 +327,18 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         int64_t row = wave_row0 + t * RPL + sub;
         row = row < N ? row : N - 1;                                   // clamped: loads stay unconditional
         load_words<G>(W + row * WPR + (wk * LPR + pos) * G, w[t]);
+    }
+    // block scales of this lane's slices: last in the queue, used after the lookups
+    [[maybe_unused]] uint16_t sv[RS][NSC];
+    if constexpr (SC) {
+        const int blk0 = ((wk * LPR + pos) * EL) / KMQ_BLOCK;
+#pragma unroll
+        for (int t = 0; t < RS; ++t) {
+            int64_t row = wave_row0 + t * RPL + sub;
+            row = row < N ? row : N - 1;
+#pragma unroll
+            for (int i = 0; i < NSC; ++i) sv[t][i] = scales[row * (K / KMQ_BLOCK) + blk0 + i];
+        }
     }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
@@ -380,9 +410,15 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     for (int i = 0; i < 4; ++i) ar[i] = lut_base;
     // Everything the compiler itself has in flight on the LGKM counter (the reads of
     // x above) must have landed before the hand-counted pipeline starts.
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    // That includes scalar loads: the two centroids of the 1-bit block-scaled form are fetched
+    // here, ahead of the pipeline, because a scalar load issued in its middle would count on
+    // the same LGKM counter as the lookups and return out of order with them.
+    [[maybe_unused]] uint32_t cpair = 0;
+    if constexpr (SC && BITS == 1) cpair = *reinterpret_cast<const uint32_t*>(codebook);
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(cpair) : : "memory");
     const uint32_t mask = BITS == 1 ? 0x78u : 0x3Cu;
     float acc[RS];
+    [[maybe_unused]] float accb[RS];               // 1-bit with scales: the first block's sum
     float a0 = 0.f, a1 = 0.f;
     constexpr int NU = RS * U;
     if constexpr (BITS == 1) {
@@ -399,7 +435,8 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
             } else {
                 consume4_b64<0>(vv[n & 1], &xr[u * 8], a0, a1);
             }
-            if constexpr (u == U - 1) { acc[t] = a0 + a1; a0 = 0.f; a1 = 0.f; }
+            if constexpr (SC && u == U / 2 - 1) { settle_dot(a0, a1); accb[t] = a0 + a1; a0 = 0.f; a1 = 0.f; }
+            if constexpr (u == U - 1) { settle_dot(a0, a1); acc[t] = a0 + a1; a0 = 0.f; a1 = 0.f; }
         });
     } else {
         uint32_t v[2][8];
@@ -419,12 +456,31 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
                 if constexpr (BITS == 2) consume8_dot2<0>(v[n & 1], &xr[u * 8], a0, a1);
                 else consume8_fma<0>(v[n & 1], &xr[u * 8], a0, a1);
             }
-            if constexpr (u == U - 1) { acc[t] = a0 + a1; a0 = 0.f; a1 = 0.f; }
+            if constexpr (u == U - 1) { settle_dot(a0, a1); acc[t] = a0 + a1; a0 = 0.f; a1 = 0.f; }
         });
     }
 
     // ---- 6. K-reduction: lanes of the group, then slices through LDS ------------------------------
-    if constexpr (BITS == 1) {
+    // (nothing of what follows may be scheduled into the hand-counted pipeline above)
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (SC) {
+        if constexpr (BITS == 1) {
+            // two blocks per lane: s0*(c0*X0 + d*S0) + s1*(c0*X1 + d*S1), X = the block's sum of x
+            float sx0 = 0.f, sx1 = 0.f;
+#pragma unroll
+            for (int i = 0; i < XR / 2; ++i) {
+                sx0 = dot2_bf16(0x3F803F80u, xr[i], sx0);
+                sx1 = dot2_bf16(0x3F803F80u, xr[XR / 2 + i], sx1);
+            }
+            const float c0 = bf16_to_f32(cpair & 0xFFFFu), d = bf16_to_f32(cpair >> 16) - c0;
+#pragma unroll
+            for (int t = 0; t < RS; ++t)
+                acc[t] = bf16_to_f32(sv[t][0]) * fmaf(d, accb[t], c0 * sx0) + bf16_to_f32(sv[t][1]) * fmaf(d, acc[t], c0 * sx1);
+        } else {
+#pragma unroll
+            for (int t = 0; t < RS; ++t) acc[t] *= bf16_to_f32(sv[t][0]);
+        }
+    } else if constexpr (BITS == 1) {
         float sx = 0.f;
 #pragma unroll
         for (int i = 0; i < XR; ++i) sx = dot2_bf16(0x3F803F80u, xr[i], sx);
@@ -447,7 +503,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
             float s = 0.f;
 #pragma unroll
             for (int k = 0; k < NWK; ++k) s += sm.part[k][rl];
-            if constexpr (BITS == 1) {
+            if constexpr (BITS == 1 && !SC) {
                 float sx = 0.f;
 #pragma unroll
                 for (int k = 0; k < NWK; ++k) sx += sm.sxp[k];
@@ -476,21 +532,25 @@ struct LutEntry {
     int bits;
     int64_t K;
     int rows_wg;
+    bool scaled;             // block scales + tensor-wide codebook
     const char* name;
     void (*launch)(const GemmArgs&, hipStream_t);
 };
 
-template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE>
+template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE, bool SC>
 static void launch_lut(const GemmArgs& a, hipStream_t s) {
     constexpr int rows_wg = NWR * (kWave / LPR) * RS;
     const dim3 grid(static_cast<unsigned>((a.N + rows_wg - 1) / rows_wg)), block(NWK * NWR * 64);
-    hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE>), grid, block, 0, s,
-                       a.W, a.codebook, a.X, a.Y, a.N);
+    hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, SC>), grid, block, 0, s,
+                       a.W, a.codebook, a.X, a.Y, a.N, a.scales);
 }
 
 #define KMQ_LUT(BITS, G, LPR, NWK, NWR, RS, WPE) \
-    { BITS, int64_t(NWK) * LPR * (G * 32 / BITS), NWR * (64 / LPR) * RS, \
-      "lut_b" #BITS "_g" #G "_l" #LPR "_k" #NWK "_r" #NWR "x" #RS, &launch_lut<BITS, G, LPR, NWK, NWR, RS, WPE> }
+    { BITS, int64_t(NWK) * LPR * (G * 32 / BITS), NWR * (64 / LPR) * RS, false, \
+      "lut_b" #BITS "_g" #G "_l" #LPR "_k" #NWK "_r" #NWR "x" #RS, &launch_lut<BITS, G, LPR, NWK, NWR, RS, WPE, false> }
+#define KMQ_LUT_SC(BITS, G, LPR, NWK, NWR, RS, WPE) \
+    { BITS, int64_t(NWK) * LPR * (G * 32 / BITS), NWR * (64 / LPR) * RS, true, \
+      "lut_sc_b" #BITS "_g" #G "_l" #LPR "_k" #NWK "_r" #NWR "x" #RS, &launch_lut<BITS, G, LPR, NWK, NWR, RS, WPE, true> }
 
 static const LutEntry kLut[] = {
     // Several shapes may serve one (bits, K): lut_find takes the one whose grid comes out
@@ -515,17 +575,31 @@ static const LutEntry kLut[] = {
     KMQ_LUT(4, 4, 64, 2, 2, 2, 6),   // K = 4096
     KMQ_LUT(4, 4, 64, 4, 1, 2, 6),   // K = 8192
     KMQ_LUT(4, 4, 64, 7, 1, 2, 6),   // K = 14336
+    // block-scaled format (lane slices of 32, 64 or 128 elements only)
+    KMQ_LUT_SC(1, 4, 16, 1, 4, 1, 4),   // K = 2048
+    KMQ_LUT_SC(1, 4, 16, 1, 2, 1, 4),
+    KMQ_LUT_SC(1, 4, 32, 1, 4, 2, 4),   // K = 4096
+    KMQ_LUT_SC(1, 4, 64, 1, 4, 2, 4),   // K = 8192
+    KMQ_LUT_SC(1, 4, 64, 1, 4, 3, 4),
+    KMQ_LUT_SC(2, 4, 32, 1, 4, 2, 6),   // K = 2048
+    KMQ_LUT_SC(2, 4, 64, 1, 4, 2, 7),   // K = 4096
+    KMQ_LUT_SC(2, 4, 64, 2, 2, 2, 7),   // K = 8192
+    KMQ_LUT_SC(2, 2, 64, 7, 1, 4, 7),   // K = 14336
+    KMQ_LUT_SC(4, 4, 64, 1, 4, 2, 6),   // K = 2048
+    KMQ_LUT_SC(4, 4, 64, 2, 2, 2, 6),   // K = 4096
+    KMQ_LUT_SC(4, 4, 64, 4, 1, 2, 6),   // K = 8192
+    KMQ_LUT_SC(4, 4, 64, 7, 1, 2, 6),   // K = 14336
 };
 constexpr int kLutCount = sizeof(kLut) / sizeof(kLut[0]);
 
 // Cost of a shape for N rows: the most rows any CU gets when the workgroups are dealt
 // round-robin over 256 CUs.
-int lut_find(int64_t N, int64_t K, int bits, int layout) {
+int lut_find(int64_t N, int64_t K, int bits, int layout, bool scaled) {
     if (layout != KMQ_LAYOUT_CANONICAL) return -1;
     int best = -1;
     int64_t best_cost = 0;
     for (int i = 0; i < kLutCount; ++i) {
-        if (kLut[i].bits != bits || kLut[i].K != K) continue;
+        if (kLut[i].bits != bits || kLut[i].K != K || kLut[i].scaled != scaled) continue;
         const int64_t wgs = (N + kLut[i].rows_wg - 1) / kLut[i].rows_wg;
         const int64_t cost = ((wgs + 255) / 256) * kLut[i].rows_wg;
         if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }

@@ -60,6 +60,12 @@ _lib.kmq_dequant.restype = ctypes.c_int32
 _lib.kmq_dequant.argtypes = [_vp, _vp, _vp, _i64, _i64, _int, _int, _vp]
 _lib.kmq_kernel_name.restype = ctypes.c_char_p
 _lib.kmq_kernel_name.argtypes = [_i64, _i64, _int, _int, _int]
+_lib.kmq_gemv_blockscaled.restype = ctypes.c_int32
+_lib.kmq_gemv_blockscaled.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _vp, _sz, _vp]
+_lib.kmq_gemm_smallbatch_blockscaled.restype = ctypes.c_int32
+_lib.kmq_gemm_smallbatch_blockscaled.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp, _sz, _vp]
+_lib.kmq_kernel_name_blockscaled.restype = ctypes.c_char_p
+_lib.kmq_kernel_name_blockscaled.argtypes = [_i64, _i64, _int, _int, _int]
 _lib.kmq_stream_read.restype = ctypes.c_int32
 _lib.kmq_stream_read.argtypes = [_vp, _sz, _vp, _vp]
 _lib.kmq_last_hip_error.restype = ctypes.c_char_p
@@ -172,6 +178,26 @@ def gemm_smallbatch(W, codebook, X, Y, N: int, K: int, M: int, bits: int, layout
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(_lib.kmq_gemm_smallbatch(_ptr(W), _ptr(codebook), _ptr(X), _ptr(Y), N, K, M, bits, layout,
                                     _ptr(workspace), ws_bytes, _stream()))
+
+
+def kernel_name_blockscaled(N: int, K: int, bits: int, M: int, layout: int = 0) -> str:
+    return _lib.kmq_kernel_name_blockscaled(N, K, bits, M, layout).decode()
+
+
+def gemv_blockscaled(W, codebook, scales, x, y, N: int, K: int, bits: int, layout: int = 0, workspace=None):
+    """y[N] = W x in the block-scaled format (codebook: 2^bits shared centroids, scales: N x K/64),
+    on torch's current stream."""
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(_lib.kmq_gemv_blockscaled(_ptr(W), _ptr(codebook), _ptr(scales), _ptr(x), _ptr(y), N, K, bits, layout,
+                                     _ptr(workspace), ws_bytes, _stream()))
+
+
+def gemm_smallbatch_blockscaled(W, codebook, scales, X, Y, N: int, K: int, M: int, bits: int, layout: int = 0,
+                                workspace=None):
+    """Y[M][N] = X[M][K] W^T in the block-scaled format, on torch's current stream."""
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(_lib.kmq_gemm_smallbatch_blockscaled(_ptr(W), _ptr(codebook), _ptr(scales), _ptr(X), _ptr(Y), N, K, M,
+                                                bits, layout, _ptr(workspace), ws_bytes, _stream()))
 
 
 def dequant(W, codebook, Wdense, N: int, K: int, bits: int, layout: int = 0):

@@ -1,0 +1,108 @@
+"""GPU parity of the block-scaled calls (the paper's own weight format: Sec. 2.2
+"Nonlinear k-means quantization", App. E "Kernel implementations") against the oracle,
+through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2602_15563_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    from tests import gpu_util
+    return gpu_util
+
+
+def _case(seed, N, K, bits, M):
+    return (synth.make_indices(seed, 0, N, K, bits), synth.make_shared_codebook(seed, 0, bits),
+            synth.make_scales(seed, 0, N, K), synth.make_x(seed, 0, M, K))
+
+
+@pytest.mark.parametrize("bits", (1, 2, 3, 4))
+@pytest.mark.parametrize("N,K,M", [(1, 64, 1), (5, 128, 1), (64, 320, 3), (333, 192, 16), (17, 4160, 8), (40, 1024, 4)])
+def test_generic_shapes_vs_oracle(gpu, bits, N, K, M):
+    from paper_2602_15563_amd import kmq
+    idx, cb, sc, X = _case(3 * bits + N + K + M, N, K, bits, M)
+    p = kmq.pack(idx, bits)
+    assert kmq.kernel_name_blockscaled(N, K, bits, M) == "blockscaled_generic"
+    Yg = gpu.run_gemm_blockscaled(gpu.dev(p), gpu.dev(cb), gpu.dev(sc), X, N, K, bits)
+    gpu.check_blockscaled_against_oracle(Yg, oracle.pack(idx, bits), cb, sc, X, K, bits, label=f"b{bits} {N}x{K} M{M}")
+
+
+SC_SHAPES = [(1, 2048), (1, 4096), (1, 8192), (2, 2048), (2, 4096), (2, 8192), (2, 14336),
+             (4, 2048), (4, 4096), (4, 8192), (4, 14336)]
+
+
+@pytest.mark.parametrize("bits,K", SC_SHAPES)
+@pytest.mark.parametrize("N", (1, 3, 17, 64, 333))
+def test_specialised_gemv_vs_oracle(gpu, bits, K, N):
+    from paper_2602_15563_amd import kmq
+    idx, cb, sc, X = _case(11 * bits + N + K, N, K, bits, 1)
+    p = kmq.pack(idx, bits)
+    assert kmq.kernel_name_blockscaled(N, K, bits, 1).startswith("lut_sc_"), kmq.kernel_name_blockscaled(N, K, bits, 1)
+    Yg = gpu.run_gemm_blockscaled(gpu.dev(p), gpu.dev(cb), gpu.dev(sc), X[0], N, K, bits)
+    gpu.check_blockscaled_against_oracle(Yg, oracle.pack(idx, bits), cb, sc, X, K, bits, label=f"b{bits} {N}x{K}")
+
+
+@pytest.mark.parametrize("bits,K", [(2, 4096), (4, 8192)])
+def test_unit_scales_reproduce_the_per_row_kernel_bit_for_bit(gpu, bits, K):
+    """scale = 1 and the shared codebook copied to every row: the same table entries, the same
+    products in the same order, one exact multiplication by 1.0 -> identical bf16 outputs."""
+    from paper_2602_15563_amd import kmq
+    N = 96
+    idx, cb, _, X = _case(5 + bits, N, K, bits, 1)
+    p = gpu.dev(kmq.pack(idx, bits))
+    ones = np.full((N, K // 64), 0x3F80, dtype=np.uint16)
+    Ys = gpu.run_gemm_blockscaled(p, gpu.dev(cb), gpu.dev(ones), X[0], N, K, bits)
+    Yr = gpu.run_gemm(p, gpu.dev(np.tile(cb, (N, 1))), X[0], N, K, bits)
+    assert np.array_equal(Ys, Yr)
+
+
+def test_only_the_scaled_block_contributes(gpu):
+    """One non-zero scale: the output is that block's sum alone (block boundaries and the
+    scale's index as the kernels see them)."""
+    from paper_2602_15563_amd import kmq
+    bits, N, K = 4, 24, 8192
+    idx, cb, sc, X = _case(77, N, K, bits, 1)
+    p = gpu.dev(kmq.pack(idx, bits))
+    for r, g in ((0, 0), (5, 63), (23, 127), (7, 64)):
+        z = np.zeros_like(sc)
+        z[r, g] = sc[r, g]
+        Yg = gpu.run_gemm_blockscaled(p, gpu.dev(cb), gpu.dev(z), X[0], N, K, bits)
+        gpu.check_blockscaled_against_oracle(Yg, oracle.pack(idx, bits), cb, z, X, K, bits, strict=False, label=f"r{r} g{g}")
+        assert not np.delete(synth.bf16_to_f32(Yg[0]), r).any()
+
+
+@pytest.mark.parametrize("bits", (4, 1))
+def test_papers_benchmark_shape_full_size(gpu, bits):
+    """App. E, Table "perf_micro_m1_impl": m = 1, h = 8192, 4-bit and 1-bit elements with B = 64
+    scales; sampled row blocks of the full-size product."""
+    from paper_2602_15563_amd import kmq
+    N = K = 8192
+    idx, cb, sc, X = _case(100 + bits, N, K, bits, 1)
+    p = kmq.pack(idx, bits)
+    Yg = gpu.run_gemm_blockscaled(gpu.dev(p), gpu.dev(cb), gpu.dev(sc), X[0], N, K, bits)
+    worst = gpu.check_blockscaled_against_oracle(Yg, oracle.pack(idx, bits), cb, sc, X, K, bits, strict=True,
+                                                 row_ranges=gpu.sample_ranges(N, bits), label=f"h8192 b{bits}")
+    assert worst < 2e-3
+
+
+def test_errors(gpu):
+    from paper_2602_15563_amd import kmq
+    import torch
+    N, K, bits = 8, 128, 2
+    idx, cb, sc, X = _case(1, N, K, bits, 1)
+    p, cbd, scd, xd = gpu.dev(kmq.pack(idx, bits)), gpu.dev(cb), gpu.dev(sc), gpu.dev(X[0])
+    y = torch.zeros(N, dtype=torch.int16, device="cuda")
+    with pytest.raises(kmq.KmqError) as e:
+        kmq.gemv_blockscaled(p, cbd, scd, xd, y, N, K - 32, bits)       # K not a multiple of 64
+    assert e.value.status == 3
+    with pytest.raises(kmq.KmqError) as e:
+        kmq.gemv_blockscaled(p, cbd, scd, xd, y, N, K, bits, layout=1)  # tiled layout not offered
+    assert e.value.status == 7
+    with pytest.raises(kmq.KmqError) as e:
+        kmq.gemv_blockscaled(p, cbd, None, xd, y, N, K, bits)
+    assert e.value.status == 1
