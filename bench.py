@@ -44,7 +44,15 @@ WORKLOADS = {
     "cfg4_qkv_b1_9216x3072_m4": (1, 9216, 3072, 4, 4, 0, True),
     "cfg4_qkv_b1_9216x3072_m16": (1, 9216, 3072, 16, 4, 0, True),
     "cfg4_down_b1_3072x8192_m16": (1, 3072, 8192, 16, 4, 4, True),
+    # the paper's own format and micro-benchmark shape (App. E, table of m = 1, h = 8192):
+    # tensor-wide codebook, one bf16 scale per 64 elements; 8th field = block-scaled
+    "paper_b4s_8192x8192_m1": (4, 8192, 8192, 1, 5, 0, False, True),
+    "paper_b1s_8192x8192_m1": (1, 8192, 8192, 1, 6, 0, False, True),
+    "paper_b2s_8192x8192_m1": (2, 8192, 8192, 1, 7, 0, False, True),
 }
+# The paper's published numbers for those two workloads (App. E, table "perf_micro_m1_impl":
+# Triton kernels on an NVIDIA L40S, 864 GB/s): effective GB/s, us per call.
+PAPER_NUMBERS = {"paper_b4s_8192x8192_m1": (721.0, 49.5), "paper_b1s_8192x8192_m1": (438.0, 24.0)}
 HEADLINE = "cfg2_gateup_b2_14336x4096_m1"
 TRAFFIC_SUMMARIES = {HEADLINE: "gemv_b2_14336x4096_m1_pmc_traffic.txt"}
 
@@ -68,16 +76,19 @@ class Instances:
 
         from paper_2602_15563_amd import kmq, synth
         self.name = name
-        self.bits, self.N, self.K, self.M, seed, matrix, sym = WORKLOADS[name]
+        self.bits, self.N, self.K, self.M, seed, matrix, sym = WORKLOADS[name][:7]
+        self.scaled = len(WORKLOADS[name]) > 7 and WORKLOADS[name][7]
         bits, N, K, M = self.bits, self.N, self.K, self.M
         # batch > 1 runs on the tiled (matrix-core) layout by default: the offline,
         # reversible repack is outside the timed region
         self.layout = (1 if M > 1 else 0) if layout is None else layout
-        self.bytes = synth.algorithmic_bytes(N, K, bits, M)
+        self.bytes = (synth.algorithmic_bytes_blockscaled if self.scaled else synth.algorithmic_bytes)(N, K, bits, M)
         self.R = max(2, -(-2 * LLC_BYTES // self.bytes)) if rotate else 1
         self.R = min(self.R, 2048)
         self.idx = synth.make_indices(seed, matrix, N, K, bits)
-        self.cb = synth.make_codebook(seed, matrix, N, bits, symmetric=sym)
+        self.cb = synth.make_shared_codebook(seed, matrix, bits) if self.scaled else \
+            synth.make_codebook(seed, matrix, N, bits, symmetric=sym)
+        self.sc = synth.make_scales(seed, matrix, N, K) if self.scaled else None
         self.X = synth.make_x(seed, matrix, M, K)
         self.packed = kmq.pack(self.idx, bits)
         wpr = self.packed.shape[1]
@@ -91,9 +102,16 @@ class Instances:
         g = torch.Generator(device="cuda")
         g.manual_seed(1234 + seed)
         self.W, self.C, self.Xd, self.Y = [_dev(stored)], [_dev(self.cb)], [_dev(self.X)], []
+        self.S = [_dev(self.sc)] if self.scaled else None
         for _ in range(1, self.R):
             self.W.append(torch.randint(-2**31, 2**31, (nrows_stored, wpr), dtype=torch.int32, device="cuda", generator=g))
-            if sym:
+            if self.scaled:
+                # same distributions as the host recipe: clipped N(0, 0.45) centroids, block-maximum scales
+                c = torch.sort((torch.randn(1 << bits, device="cuda", generator=g) * 0.45).clamp(-1, 1)).values.to(torch.bfloat16)
+                u = torch.rand((N, K // 64), device="cuda", generator=g, dtype=torch.float64)
+                t = 0.02 * torch.special.ndtri(0.5 * (1.0 + u ** (1.0 / 64)))
+                self.S.append(t.clamp_min(1e-6).to(torch.bfloat16).view(torch.int16).contiguous())
+            elif sym:
                 t = (torch.randn(N, device="cuda", generator=g) * 0.02).abs().to(torch.bfloat16)
                 c = torch.stack([-t, t], dim=1)
             else:
@@ -105,12 +123,15 @@ class Instances:
             self.Y.append(torch.zeros((M, N), dtype=torch.int16, device="cuda"))
         ws = kmq.workspace_bytes(N, K, bits, M, self.layout)
         self.ws = torch.empty(ws, dtype=torch.uint8, device="cuda") if ws else None
-        self.kernel = kmq.kernel_name(N, K, bits, M, self.layout)
+        self.kernel = (kmq.kernel_name_blockscaled if self.scaled else kmq.kernel_name)(N, K, bits, M, self.layout)
 
     def call(self, i):
         from paper_2602_15563_amd import kmq
         r = i % self.R
-        if self.M == 1:
+        if self.scaled:
+            kmq.gemm_smallbatch_blockscaled(self.W[r], self.C[r], self.S[r], self.Xd[r], self.Y[r], self.N, self.K,
+                                            self.M, self.bits, self.layout, self.ws)
+        elif self.M == 1:
             kmq.gemv(self.W[r], self.C[r], self.Xd[r], self.Y[r], self.N, self.K, self.bits, self.layout, self.ws)
         else:
             kmq.gemm_smallbatch(self.W[r], self.C[r], self.Xd[r], self.Y[r], self.N, self.K, self.M,
@@ -130,7 +151,10 @@ class Instances:
         rng = np.random.default_rng(0)
         starts = [0, self.N - 64] + [int(s) for s in rng.integers(0, self.N - 64, size=4)]
         for n0 in starts:
-            Yo, A, _ = oracle.gemm(self.packed, self.cb, self.X, self.K, self.bits, rows=(n0, n0 + 64))
+            if self.scaled:
+                Yo, A, _ = oracle.gemm_blockscaled(self.packed, self.cb, self.sc, self.X, self.K, self.bits, rows=(n0, n0 + 64))
+            else:
+                Yo, A, _ = oracle.gemm(self.packed, self.cb, self.X, self.K, self.bits, rows=(n0, n0 + 64))
             err = np.abs(yg[:, n0:n0 + 64] - Yo[:, n0:n0 + 64])
             if not np.all(err <= 2e-3 * A[:, n0:n0 + 64]):
                 raise SystemExit(f"bench: {self.name} does not match the oracle in rows {n0}..{n0 + 64}")
@@ -218,12 +242,17 @@ def cpu_baseline(inst: Instances):
     import oracle
     best = None
     n_rows = inst.N
-    oracle.gemm(inst.packed, inst.cb, inst.X, inst.K, inst.bits, rows=(0, min(64, n_rows)))   # warm-up
+    def run(rows=None):
+        if inst.scaled:
+            oracle.gemm_blockscaled(inst.packed, inst.cb, inst.sc, inst.X, inst.K, inst.bits, rows=rows)
+        else:
+            oracle.gemm(inst.packed, inst.cb, inst.X, inst.K, inst.bits, rows=rows)
+    run((0, min(64, n_rows)))   # warm-up
     t_total = 0.0
     runs = 0
     while runs < 3 or (t_total < 10.0 and runs < 20):
         t = time.perf_counter()
-        oracle.gemm(inst.packed, inst.cb, inst.X, inst.K, inst.bits)
+        run()
         dt = time.perf_counter() - t
         best = dt if best is None else min(best, dt)
         t_total += dt
@@ -277,7 +306,8 @@ def main():
         "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": round(us * 1e-3, 6), "us_per_call": round(us, 3),
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": round(gbs / PAPER_NUMBERS[args.workload][0], 3) if args.workload in PAPER_NUMBERS else None,
         "dtype": "bf16 in/out, fp32 accumulate", "data": "synthetic",
         "config": {"workload": args.workload, "bits": inst.bits, "N": inst.N, "K": inst.K, "batch": inst.M,
                    "kernel": inst.kernel, "layout": "tiled" if inst.layout else "canonical",
@@ -288,6 +318,9 @@ def main():
                      "note": "achieved = algorithmic bytes per launch / average launch-to-launch time "
                              "(HIP events on the launch stream around the timed region)"},
     }
+    if args.workload in PAPER_NUMBERS:
+        out["config"]["paper"] = {"GB/s": PAPER_NUMBERS[args.workload][0], "us_per_call": PAPER_NUMBERS[args.workload][1],
+                                  "hardware": "NVIDIA L40S (864 GB/s), Triton kernel, paper App. E; another machine: context only"}
     out["roofline"]["read_ceiling"] = time_read_ceiling(inst, min(steps, 5000))
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(inst)

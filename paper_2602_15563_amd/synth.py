@@ -138,6 +138,13 @@ def algorithmic_bytes(N: int, K: int, bits: int, M: int) -> int:
     return 4 * N * wpr + 2 * N * (1 << bits) + 2 * M * K + 2 * M * N
 
 
+def algorithmic_bytes_blockscaled(N: int, K: int, bits: int, M: int, block: int = BLOCK) -> int:
+    """Operand bytes of one block-scaled call: indices, the tensor-wide codebook, one bf16
+    scale per block, X and Y (the paper's "effective bandwidth" numerator, App. E)."""
+    wpr = (K * bits + 31) // 32
+    return 4 * N * wpr + 2 * (1 << bits) + 2 * N * (K // block) + 2 * M * K + 2 * M * N
+
+
 def cases(cfg: int) -> list[Case]:
     """All (shape, batch) instances of configuration ``cfg`` (0..4).
 
