@@ -70,7 +70,7 @@ class Instances:
     oracle; the others are drawn on the device with the same distributions
     (uniform index bits, sorted N(0, 0.02) centroids, N(0, 1) activations)."""
 
-    def __init__(self, name, rotate=True, layout=None):
+    def __init__(self, name, rotate=True, layout=None, R=None, M=None):
         import numpy as np
         import torch
 
@@ -78,13 +78,15 @@ class Instances:
         self.name = name
         self.bits, self.N, self.K, self.M, seed, matrix, sym = WORKLOADS[name][:7]
         self.scaled = len(WORKLOADS[name]) > 7 and WORKLOADS[name][7]
+        if M is not None:
+            self.M = M
         bits, N, K, M = self.bits, self.N, self.K, self.M
         # batch > 1 runs on the tiled (matrix-core) layout by default: the offline,
         # reversible repack is outside the timed region
         self.layout = (1 if M > 1 else 0) if layout is None else layout
         self.bytes = (synth.algorithmic_bytes_blockscaled if self.scaled else synth.algorithmic_bytes)(N, K, bits, M)
         self.R = max(2, -(-2 * LLC_BYTES // self.bytes)) if rotate else 1
-        self.R = min(self.R, 2048)
+        self.R = min(self.R, 2048) if R is None else R
         self.idx = synth.make_indices(seed, matrix, N, K, bits)
         self.cb = synth.make_shared_codebook(seed, matrix, bits) if self.scaled else \
             synth.make_codebook(seed, matrix, N, bits, symmetric=sym)
@@ -196,6 +198,70 @@ def time_workload(inst: Instances, steps: int, warmup: int, use_graph: bool = Tr
     return e0.elapsed_time(e1) * 1e-3, steps
 
 
+SWEEP_LAYERS = 28
+SWEEP_SHAPES = ["cfg4_qkv_b1_9216x3072_m1", "cfg4_o_b1_3072x3072_m1", "cfg4_gate_b1_8192x3072_m1",
+                "cfg4_gate_b1_8192x3072_m1", "cfg4_down_b1_3072x8192_m1"]       # gate and up are two matrices
+
+
+def run_sweep(M: int, replays: int):
+    """The 1-bit decoder-layer sweep of the fifth contract configuration: 28 layers x
+    (fused QKV, O, gate, up, down), every matrix with its own weights (396 MB of indices, so
+    each pass streams from HBM), captured as one HIP graph of 140 calls on one stream."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2602_15563_amd import synth
+    insts = [Instances(n, R=SWEEP_LAYERS, M=M) for n in SWEEP_SHAPES]
+    worst = max(it.check() for it in insts)
+    # one later layer (device-drawn weights) against the oracle as well, on sampled rows
+    layer = 17
+    for it in insts:
+        it.call(layer)
+    torch.cuda.synchronize()
+    for it in insts[:1] + insts[4:]:
+        if it.layout:                     # tiled: bring the words back to canonical order on the host
+            from paper_2602_15563_amd import kmq
+            packed = kmq.unrepack(it.W[layer].cpu().numpy().view(np.uint32).reshape(-1), it.N, it.K, it.bits, 1)
+        else:
+            packed = it.W[layer].cpu().numpy().view(np.uint32)
+        cb = it.C[layer].cpu().numpy().view(np.uint16)
+        X = it.Xd[layer].cpu().numpy().view(np.uint16)
+        yg = synth.bf16_to_f64(it.Y[layer].cpu().numpy().view(np.uint16))
+        for n0 in (0, it.N // 2, it.N - 64):
+            Yo, A, _ = oracle.gemm(packed, cb, X, it.K, it.bits, rows=(n0, n0 + 64))
+            err = np.abs(yg[:, n0:n0 + 64] - Yo[:, n0:n0 + 64])
+            if not np.all(err <= 2e-3 * A[:, n0:n0 + 64]):
+                raise SystemExit(f"bench: sweep layer {layer} of {it.name} does not match the oracle")
+            worst = max(worst, float(np.max(err / np.maximum(A[:, n0:n0 + 64], 1e-300))))
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for layer in range(SWEEP_LAYERS):
+            for it in insts:
+                it.call(layer)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for layer in range(SWEEP_LAYERS):
+                for it in insts:
+                    it.call(layer)
+        graph.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(replays):
+            graph.replay()
+        e1.record(stream)
+        stream.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / replays
+    nbytes = SWEEP_LAYERS * sum(it.bytes for it in insts)
+    calls = SWEEP_LAYERS * len(insts)
+    return {"workload": f"cfg4_sweep_28layers_m{M}", "us_per_sweep": round(us, 2), "us_per_call": round(us / calls, 3),
+            "calls": calls, "GBps": round(nbytes / us * 1e-3, 1), "pct_peak": round(100 * nbytes / us * 1e-3 / HBM_PEAK_GBS, 2),
+            "bytes": nbytes, "kernels": sorted({it.kernel for it in insts}),
+            "layout": "tiled" if insts[0].layout else "canonical", "max_err_over_A": float(f"{worst:.3e}")}
+
+
 def time_read_ceiling(inst: Instances, steps: int):
     """Pure read of the same packed index streams (same rotation, same graph replay)."""
     import torch
@@ -276,6 +342,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the timed region, launch a plain 64 MiB device copy 10 times: a kernel of known "
                          "traffic against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also run the 28-layer 1-bit decoder sweep at batch 1, 4 and 16 -> <out>/bench_sweep.json")
     ap.add_argument("--table", action="store_true", help="also time every contract shape -> <out>/bench_table.json")
     ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out"), help="folder for bench_table.json")
     args = ap.parse_args()
@@ -342,6 +410,17 @@ def main():
         os.makedirs(args.out, exist_ok=True)
         with open(os.path.join(args.out, "bench_table.json"), "w") as f:
             json.dump(rows, f, indent=1)
+
+    if args.sweep:
+        rows = []
+        for M in (1, 4, 16):
+            rows.append(run_sweep(M, 200))
+            print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+            torch.cuda.empty_cache()
+        os.makedirs(args.out, exist_ok=True)
+        with open(os.path.join(args.out, "bench_sweep.json"), "w") as f:
+            json.dump(rows, f, indent=1)
+        out["config"]["decoder_sweep"] = rows
 
     print(json.dumps(out), flush=True)
 
