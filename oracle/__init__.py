@@ -54,6 +54,8 @@ def _load():
         lib.oracle_gemm.argtypes = [vp, vp, vp, i64, i64, ci, i64, i64, i64, vp, vp, vp]
         lib.oracle_gemm_blockscaled.restype = ci
         lib.oracle_gemm_blockscaled.argtypes = [vp, vp, vp, vp, i64, i64, ci, i64, i64, i64, i64, ci, vp, vp, vp]
+        lib.oracle_gemm_dense.restype = ci
+        lib.oracle_gemm_dense.argtypes = [vp, vp, i64, i64, i64, i64, i64, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -167,6 +169,27 @@ def gemm_blockscaled(packed: np.ndarray, codebook: np.ndarray, scales: np.ndarra
     Yb = np.zeros((M, N), dtype=np.uint16)
     if _load().oracle_gemm_blockscaled(_p(packed), _p(codebook), _p(scales), _p(X2), N, K, bits, block, M,
                                        n0, n1, int(deferred), _p(Y), _p(A), _p(Yb)):
+        raise ValueError("bad argument")
+    if vec:
+        return Y[0], A[0], Yb[0]
+    return Y, A, Yb
+
+
+def gemm_dense(W: np.ndarray, X: np.ndarray, rows: tuple[int, int] | None = None):
+    """Y = X W^T for a dense bf16 W (uint16 patterns, N x K), fp64: the unquantised baseline."""
+    W = np.ascontiguousarray(W, dtype=np.uint16)
+    N, K = W.shape
+    X = np.ascontiguousarray(X, dtype=np.uint16)
+    vec = X.ndim == 1
+    X2 = X.reshape(1, -1) if vec else X
+    M = X2.shape[0]
+    if X2.shape[1] != K:
+        raise ValueError("X has the wrong K")
+    n0, n1 = (0, N) if rows is None else rows
+    Y = np.full((M, N), np.nan, dtype=np.float64)
+    A = np.full((M, N), np.nan, dtype=np.float64)
+    Yb = np.zeros((M, N), dtype=np.uint16)
+    if _load().oracle_gemm_dense(_p(W), _p(X2), N, K, M, n0, n1, _p(Y), _p(A), _p(Yb)):
         raise ValueError("bad argument")
     if vec:
         return Y[0], A[0], Yb[0]

@@ -216,4 +216,25 @@ int oracle_gemm_blockscaled(const uint32_t* packed, const uint16_t* codebook, co
     return 0;
 }
 
+// Dense bf16 matrix times bf16 vectors, the unquantised baseline the paper compares
+// against (App. E, Table of m = 1, h = 8192, the 16-bit rows): Y[m][n] = sum_k W[n][k]*X[m][k]
+// in fp64, k ascending.  W is N x K bf16 bit patterns, row-major.
+int oracle_gemm_dense(const uint16_t* W, const uint16_t* X, int64_t N, int64_t K, int64_t M,
+                      int64_t n0, int64_t n1, double* Y, double* A, uint16_t* Ybf16) {
+    if (N < 0 || K < 0 || M < 0 || n0 < 0 || n1 > N || n0 > n1) return 1;
+    for (int64_t n = n0; n < n1; ++n)
+        for (int64_t m = 0; m < M; ++m) {
+            double y = 0.0, a = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                const double t = bf16_to_double(W[n * K + k]) * bf16_to_double(X[m * K + k]);
+                y += t;
+                a += std::fabs(t);
+            }
+            Y[m * N + n] = y;
+            if (A) A[m * N + n] = a;
+            if (Ybf16) Ybf16[m * N + n] = oracle_round_bf16(y);
+        }
+    return 0;
+}
+
 }  // extern "C"
