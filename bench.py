@@ -262,6 +262,53 @@ def run_sweep(M: int, replays: int):
             "layout": "tiled" if insts[0].layout else "canonical", "max_err_over_A": float(f"{worst:.3e}")}
 
 
+def time_bf16_baseline(N: int, K: int, steps: int):
+    """The unquantised product on the same machine: dense bf16 W (2*N*K bytes), rotating
+    instances, same graph replay.  Returns us per call and effective GB/s."""
+    import torch
+
+    from paper_2602_15563_amd import kmq
+    nbytes = 2 * N * K + 2 * K + 2 * N
+    R = max(2, -(-2 * LLC_BYTES // nbytes))
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99)
+    Ws = [(torch.randn((N, K), device="cuda", generator=g) * 0.02).to(torch.bfloat16).view(torch.int16) for _ in range(R)]
+    xs = [torch.randn(K, device="cuda", generator=g).to(torch.bfloat16).view(torch.int16) for _ in range(R)]
+    ys = [torch.zeros(N, dtype=torch.int16, device="cuda") for _ in range(R)]
+    # one instance against the oracle, sampled rows
+    import numpy as np
+
+    import oracle
+    from paper_2602_15563_amd import synth
+    kmq.gemv_bf16(Ws[0], xs[0], ys[0], N, K)
+    torch.cuda.synchronize()
+    yg = synth.bf16_to_f64(ys[0].cpu().numpy().view(np.uint16))
+    Wh, xh = Ws[0][:64].cpu().numpy().view(np.uint16), xs[0].cpu().numpy().view(np.uint16)
+    Yo, A, _ = oracle.gemm_dense(Wh, xh)
+    if not np.all(np.abs(yg[:64] - Yo) <= 2e-3 * A):
+        raise SystemExit("bench: the dense bf16 baseline does not match the oracle")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        graph = torch.cuda.CUDAGraph()
+        for i in range(R):
+            kmq.gemv_bf16(Ws[i], xs[i], ys[i], N, K)
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(CALLS_PER_GRAPH):
+                kmq.gemv_bf16(Ws[i % R], xs[i % R], ys[i % R], N, K)
+        graph.replay()
+        stream.synchronize()
+        n = max(1, steps // CALLS_PER_GRAPH)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(n):
+            graph.replay()
+        e1.record(stream)
+        stream.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (n * CALLS_PER_GRAPH)
+    return {"us_per_call": round(us, 3), "GB/s": round(nbytes / us * 1e-3, 1), "bytes": nbytes, "rotating_instances": R}
+
+
 def time_read_ceiling(inst: Instances, steps: int):
     """Pure read of the same packed index streams (same rotation, same graph replay)."""
     import torch
@@ -389,6 +436,15 @@ def main():
     if args.workload in PAPER_NUMBERS:
         out["config"]["paper"] = {"GB/s": PAPER_NUMBERS[args.workload][0], "us_per_call": PAPER_NUMBERS[args.workload][1],
                                   "hardware": "NVIDIA L40S (864 GB/s), Triton kernel, paper App. E; another machine: context only"}
+    if inst.scaled and inst.M == 1:
+        # speed-up over an unquantised bf16 product on this machine, next to the paper's roofline
+        # model (Sec. 3.3, eq. "theoretical-speedup") evaluated for it: nu = dense bf16 op/s / HBM byte/s
+        from paper_2602_15563_amd import model
+        base = time_bf16_baseline(inst.N, inst.K, 2000)
+        nu = 2.5e15 / (HBM_PEAK_GBS * 1e9)
+        out["config"]["bf16_baseline"] = base
+        out["config"]["speedup_vs_bf16"] = round(base["us_per_call"] / us, 2)
+        out["config"]["model_max_speedup"] = round(model.speedup(16.0, inst.bits + 0.25, inst.M, nu), 2)
     out["roofline"]["read_ceiling"] = time_read_ceiling(inst, min(steps, 5000))
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(inst)

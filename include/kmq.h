@@ -161,6 +161,14 @@ kmq_status kmq_gemm_smallbatch_blockscaled(const uint32_t* W, const uint16_t* co
 /* As kmq_kernel_name, for the block-scaled calls. */
 const char* kmq_kernel_name_blockscaled(int64_t N, int64_t K, int bits, int M, int layout);
 
+/* Dense bf16 GEMV, y = W x with W N x K bf16 bit patterns, row-major: the unquantised
+ * baseline of the paper's micro-benchmark table (App. E, the 16-bit rows), provided so that
+ * speed-ups can be quoted against a bf16 product on the same machine.  fp32 accumulation,
+ * bf16 output.  Device pointers; W and x 16-byte aligned when K % 8 == 0 (else 2-byte),
+ * y 2-byte aligned; 1 <= K <= 32768 (x is staged in 64 KB of LDS), else KMQ_ERR_SHAPE. */
+kmq_status kmq_gemv_bf16(const uint16_t* W, const uint16_t* x, uint16_t* y, int64_t N, int64_t K,
+                         void* hip_stream);
+
 /* Name of the kernel variant the launch heuristic picks for this problem
  * (static string, never NULL; "invalid" on bad arguments).  For reports. */
 const char* kmq_kernel_name(int64_t N, int64_t K, int bits, int M, int layout);

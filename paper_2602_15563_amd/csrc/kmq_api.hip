@@ -134,6 +134,16 @@ kmq_status kmq_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd
     return kmq::hip_status(e);
 }
 
+kmq_status kmq_gemv_bf16(const uint16_t* W, const uint16_t* x, uint16_t* y, int64_t N, int64_t K,
+                         void* hip_stream) {
+    if (!W || !x || !y) return KMQ_ERR_NULL;
+    if (!kmq::dims_valid(N, K) || K > 32768) return KMQ_ERR_SHAPE;
+    const uintptr_t a = (K % 8) == 0 ? 15 : 1;
+    if ((reinterpret_cast<uintptr_t>(W) & a) || (reinterpret_cast<uintptr_t>(x) & a) ||
+        (reinterpret_cast<uintptr_t>(y) & 1)) return KMQ_ERR_ALIGN;
+    return kmq::hip_status(kmq::launch_gemv_bf16(W, x, y, N, K, static_cast<hipStream_t>(hip_stream)));
+}
+
 kmq_status kmq_stream_read(const void* data, size_t bytes, void* sink, void* hip_stream) {
     if (!data) return KMQ_ERR_NULL;
     if (bytes < 16 || bytes > (size_t(1) << 40)) return KMQ_ERR_SHAPE;

@@ -51,6 +51,9 @@ hipError_t launch_rowsplit(int table_index, const GemmArgs& a, hipStream_t s);
 
 hipError_t launch_blockscaled_generic(const GemmArgs& a, hipStream_t s);
 
+// Dense bf16 baseline; K * 2 bytes of LDS, so K <= 32768.
+hipError_t launch_gemv_bf16(const uint16_t* W, const uint16_t* x, uint16_t* y, int64_t N, int64_t K, hipStream_t s);
+
 hipError_t launch_stream_read(const void* p, size_t bytes, void* sink, hipStream_t s);
 
 // Matrix-core kernel (tiled layout only).

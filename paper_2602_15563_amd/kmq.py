@@ -66,6 +66,8 @@ _lib.kmq_gemm_smallbatch_blockscaled.restype = ctypes.c_int32
 _lib.kmq_gemm_smallbatch_blockscaled.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp, _sz, _vp]
 _lib.kmq_kernel_name_blockscaled.restype = ctypes.c_char_p
 _lib.kmq_kernel_name_blockscaled.argtypes = [_i64, _i64, _int, _int, _int]
+_lib.kmq_gemv_bf16.restype = ctypes.c_int32
+_lib.kmq_gemv_bf16.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
 _lib.kmq_stream_read.restype = ctypes.c_int32
 _lib.kmq_stream_read.argtypes = [_vp, _sz, _vp, _vp]
 _lib.kmq_last_hip_error.restype = ctypes.c_char_p
@@ -198,6 +200,11 @@ def gemm_smallbatch_blockscaled(W, codebook, scales, X, Y, N: int, K: int, M: in
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(_lib.kmq_gemm_smallbatch_blockscaled(_ptr(W), _ptr(codebook), _ptr(scales), _ptr(X), _ptr(Y), N, K, M,
                                                 bits, layout, _ptr(workspace), ws_bytes, _stream()))
+
+
+def gemv_bf16(W, x, y, N: int, K: int):
+    """y[N] = W x for a dense bf16 W (N x K, row-major) on torch's current stream: the unquantised baseline."""
+    _check(_lib.kmq_gemv_bf16(_ptr(W), _ptr(x), _ptr(y), N, K, _stream()))
 
 
 def dequant(W, codebook, Wdense, N: int, K: int, bits: int, layout: int = 0):
