@@ -142,6 +142,21 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.kmq_dequant(W, cb, y, 4, 64, 2, 3, None) == 7
     assert lib.kmq_pack(None, 1, 1, 1, W) == 1 and lib.kmq_unpack(W, 1, 1, 9, W) == 2
     assert kmq.workspace_bytes(0, 64, 2, 1) == 0 and kmq.kernel_name(4, 64, 9, 1) == "invalid"
+    # the block-scaled calls and the dense baseline: same rule, checks before any launch
+    sc = a16 + 2048
+
+    def bs(W=W, cb=cb, sc=sc, x=x, y=y, N=4, K=64, bits=2, layout=0, M=1):
+        return lib.kmq_gemm_smallbatch_blockscaled(W, cb, sc, x, y, N, K, M, bits, layout, None, 0, None)
+
+    assert bs(sc=None) == 1 and bs(W=None) == 1 and bs(bits=9) == 2 and bs(M=17) == 3
+    assert bs(K=96) == 3                               # not a whole number of 64-element blocks
+    assert bs(layout=1, K=256) == 7 and bs(sc=sc + 1) == 4
+    assert lib.kmq_gemv_blockscaled(W, cb, None, x, y, 4, 64, 2, 0, None, 0, None) == 1
+    assert kmq.kernel_name_blockscaled(4, 96, 2, 1) == "invalid"
+    assert kmq.kernel_name_blockscaled(8192, 8192, 4, 1).startswith("lut_sc_b4")
+    assert kmq.kernel_name_blockscaled(8192, 8192, 4, 16) == "blockscaled_generic"
+    assert lib.kmq_gemv_bf16(None, x, y, 4, 64, None) == 1 and lib.kmq_gemv_bf16(W, x, y, 4, 40000, None) == 3
+    assert lib.kmq_gemv_bf16(W + 2, x, y, 4, 64, None) == 4 and lib.kmq_gemv_bf16(W, x, y, 0, 64, None) == 3
     for s in range(9):
         assert kmq.status_string(s) and kmq.status_string(s) != "unknown status"
     assert kmq.status_string(99) == "unknown status"

@@ -1,0 +1,72 @@
+"""The device calls are legal inside HIP graph capture (nothing allocates, nothing
+synchronises): capture one call of each kind, replay the graph several times with eager work
+and synchronisations in between, and compare every replay with the eager result bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_15563_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    from tests import gpu_util
+    return gpu_util
+
+
+def test_graph_replays_match_eager(gpu):
+    from paper_2602_15563_amd import kmq
+    dev = gpu.dev
+    # batch-1 table kernel, matrix-core kernel on the tiled layout, block-scaled GEMV, shape-agnostic kernel
+    N1, K1, b1 = 300, 4096, 2
+    N2, K2, b2, M2 = 96, 4096, 3, 8
+    N3, K3, b3 = 130, 8192, 4
+    N4, K4, b4, M4 = 77, 515, 4, 3
+    idx1, cb1, x1 = synth.make_indices(1, 0, N1, K1, b1), synth.make_codebook(1, 0, N1, b1), synth.make_x(1, 0, 1, K1)
+    idx2, cb2, X2 = synth.make_indices(2, 0, N2, K2, b2), synth.make_codebook(2, 0, N2, b2), synth.make_x(2, 0, M2, K2)
+    idx3, cb3, sc3, x3 = (synth.make_indices(3, 0, N3, K3, b3), synth.make_shared_codebook(3, 0, b3),
+                          synth.make_scales(3, 0, N3, K3), synth.make_x(3, 0, 1, K3))
+    idx4, cb4, X4 = synth.make_indices(4, 0, N4, K4, b4), synth.make_codebook(4, 0, N4, b4), synth.make_x(4, 0, M4, K4)
+    W1, C1, Xd1 = dev(kmq.pack(idx1, b1)), dev(cb1), dev(x1)
+    W2, C2, Xd2 = dev(kmq.repack(kmq.pack(idx2, b2), K2, b2, 1)), dev(cb2), dev(X2)
+    W3, C3, S3, Xd3 = dev(kmq.pack(idx3, b3)), dev(cb3), dev(sc3), dev(x3)
+    W4, C4, Xd4 = dev(kmq.pack(idx4, b4)), dev(cb4), dev(X4)
+
+    def outputs():
+        return (torch.full((1, N1), 0x7FC1, dtype=torch.int16, device="cuda"),
+                torch.full((M2, N2), 0x7FC1, dtype=torch.int16, device="cuda"),
+                torch.full((1, N3), 0x7FC1, dtype=torch.int16, device="cuda"),
+                torch.full((M4, N4), 0x7FC1, dtype=torch.int16, device="cuda"))
+
+    def run(Y):
+        kmq.gemv(W1, C1, Xd1, Y[0], N1, K1, b1)
+        kmq.gemm_smallbatch(W2, C2, Xd2, Y[1], N2, K2, M2, b2, 1)
+        kmq.gemv_blockscaled(W3, C3, S3, Xd3, Y[2], N3, K3, b3)
+        kmq.gemm_smallbatch(W4, C4, Xd4, Y[3], N4, K4, M4, b4)
+
+    eager = outputs()
+    run(eager)
+    torch.cuda.synchronize()
+    want = [y.clone() for y in eager]
+
+    captured = outputs()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        run(captured)                         # warm-up on the capture stream
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            run(captured)
+    for replay in range(4):
+        for y in captured:                    # poison the outputs, with a fill kernel
+            y.fill_(0x7FC1)
+        run(eager)                            # eager work of the program between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (y, w) in enumerate(zip(captured, want)):
+            assert torch.equal(y, w), f"replay {replay}, call {i}"
+        for y, w in zip(eager, want):
+            assert torch.equal(y, w)
