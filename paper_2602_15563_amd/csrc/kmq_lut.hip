@@ -34,6 +34,7 @@
 // K-reduction: DPP adds inside the LPR-lane group, then across the NWK slices
 // through LDS; fp32 -> bf16 round-to-nearest-even; one coalesced store per
 // workgroup.
+#include <cstdlib>
 #include <type_traits>
 
 #include "kmq_device.h"
@@ -569,7 +570,7 @@ static const LutEntry kLut[] = {
     KMQ_LUT(2, 3, 64, 1, 4, 2, 6),   // K = 3072
     KMQ_LUT(2, 4, 64, 1, 4, 2, 7),   // K = 4096
     KMQ_LUT(2, 4, 64, 2, 2, 2, 7),   // K = 8192
-    KMQ_LUT(2, 2, 64, 7, 1, 4, 7),   // K = 14336
+    KMQ_LUT(2, 2, 64, 7, 1, 4, 7),   // K = 14336 (8 rows per wave: no faster; 14-wave workgroups: slower)
     // 4-bit
     KMQ_LUT(4, 4, 64, 1, 4, 2, 6),   // K = 2048
     KMQ_LUT(4, 4, 64, 2, 2, 2, 6),   // K = 4096
@@ -596,10 +597,17 @@ constexpr int kLutCount = sizeof(kLut) / sizeof(kLut[0]);
 // round-robin over 256 CUs.
 int lut_find(int64_t N, int64_t K, int bits, int layout, bool scaled) {
     if (layout != KMQ_LAYOUT_CANONICAL) return -1;
+    // tuning override for sweeps: KMQ_LUT_PICK=n takes the n-th shape listed for (bits, K)
+    static const char* const pick_env = std::getenv("KMQ_LUT_PICK");
+    int pick = pick_env ? std::atoi(pick_env) : -1;
     int best = -1;
     int64_t best_cost = 0;
     for (int i = 0; i < kLutCount; ++i) {
         if (kLut[i].bits != bits || kLut[i].K != K || kLut[i].scaled != scaled) continue;
+        if (pick >= 0) {
+            if (pick-- == 0) return i;
+            continue;
+        }
         const int64_t wgs = (N + kLut[i].rows_wg - 1) / kLut[i].rows_wg;
         const int64_t cost = ((wgs + 255) / 256) * kLut[i].rows_wg;
         if (best < 0 || cost < best_cost) { best = i; best_cost = cost; }
