@@ -49,6 +49,8 @@ WORKLOADS = {
     "paper_b4s_8192x8192_m1": (4, 8192, 8192, 1, 5, 0, False, True),
     "paper_b1s_8192x8192_m1": (1, 8192, 8192, 1, 6, 0, False, True),
     "paper_b2s_8192x8192_m1": (2, 8192, 8192, 1, 7, 0, False, True),
+    "paper_b4s_8192x8192_m16": (4, 8192, 8192, 16, 5, 0, False, True),
+    "paper_b1s_8192x8192_m16": (1, 8192, 8192, 16, 6, 0, False, True),
 }
 # The paper's published numbers for those two workloads (App. E, table "perf_micro_m1_impl":
 # Triton kernels on an NVIDIA L40S, 864 GB/s): effective GB/s, us per call.

@@ -146,7 +146,8 @@ kmq_status kmq_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd
  *     Y[m][n] = sum_g scale[n][g] * sum_{k in block g} codebook[idx[n][k]] * X[m][k]
  *
  * with both sums in fp32 and one rounding to bf16 at the end.
- *   W         packed indices, KMQ_LAYOUT_CANONICAL only (else KMQ_ERR_LAYOUT), 16-byte aligned
+ *   W         packed indices, 16-byte aligned; KMQ_LAYOUT_CANONICAL, or KMQ_LAYOUT_TILED (the matrix-core
+ *             kernel, any batch) for K <= 16384 (else KMQ_ERR_LAYOUT)
  *   codebook  2^bits bf16 bit patterns (4-byte aligned)
  *   scales    N x K/64 bf16 bit patterns, row-major (2-byte aligned); K % 64 != 0 -> KMQ_ERR_SHAPE
  *   x / X, y / Y, M, workspace, hip_stream: as kmq_gemv / kmq_gemm_smallbatch.

@@ -15,7 +15,13 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled) {
     if (!bits_valid(bits) || !dims_valid(N, K) || M < 1 || M > KMQ_MAX_BATCH) return p;
     if (layout != KMQ_LAYOUT_CANONICAL && layout != KMQ_LAYOUT_TILED) return p;
     if (scaled) {
-        if (layout != KMQ_LAYOUT_CANONICAL || K % KMQ_BLOCK != 0) return p;
+        if (K % KMQ_BLOCK != 0) return p;
+        if (layout == KMQ_LAYOUT_TILED) {
+            // matrix-core kernel; its LDS holds the scales of at most 256 blocks of K per row
+            if (!tiled_valid(bits, K) || K > 256 * KMQ_BLOCK) return p;
+            static const char* const names[4] = {"mfma_sc_b1", "mfma_sc_b2", "mfma_sc_b3", "mfma_sc_b4"};
+            return Plan{kVariantMfma, -1, 0, names[bits - 1]};
+        }
         if (M == 1) {
             const int l = lut_find(N, K, bits, layout, true);
             if (l >= 0) return Plan{kVariantLut, l, 0, lut_name(l)};
@@ -56,8 +62,8 @@ static kmq_status check_and_run(const GemmArgs& a, void* stream) {
     if (!aligned(a.W, 16) || !aligned(a.X, 16) || !aligned(a.codebook, 4) || !aligned(a.Y, 2)) return KMQ_ERR_ALIGN;
     const bool scaled = a.scales != nullptr;
     if (scaled) {
-        if (a.layout != KMQ_LAYOUT_CANONICAL) return KMQ_ERR_LAYOUT;
         if (a.K % KMQ_BLOCK != 0) return KMQ_ERR_SHAPE;
+        if (a.layout == KMQ_LAYOUT_TILED && a.K > 256 * KMQ_BLOCK) return KMQ_ERR_LAYOUT;
         if (!aligned(a.scales, 2)) return KMQ_ERR_ALIGN;
     }
     const Plan plan = make_plan(a.N, a.K, a.bits, a.M, a.layout, scaled);

@@ -67,10 +67,20 @@ __device__ __forceinline__ uint32_t group_bits(const uint32_t (&g)[GW], int j) {
 // flight across a back edge the compiler's s_waitcnt vmcnt() placement becomes
 // conservative and drains the whole prefetch queue at every iteration.  SPW = 0 is the
 // general (runtime trip count) version.
-template <int BITS, int NWK, int RBW, int SPW>
+//
+// SC selects the paper's own weight format (Sec. 2.2 "Nonlinear k-means quantization"; App. E
+// "Kernel implementations", deferred scaling): `codebook` is one table for the whole tensor and
+// `scales` holds one bf16 per 64 elements of a row.  A block of 64 columns is two MFMA steps:
+// their 16x16 product starts from zero and is added to the running tile multiplied by the
+// scales of its four output rows.  The workgroup's scales are staged once, transposed, in LDS
+// (kMaxScaledBlocks blocks of K at most).
+constexpr int kMaxScaledBlocks = 256;          // K <= 16384 for the scaled matrix-core path
+
+template <int BITS, int NWK, int RBW, int SPW, bool SC>
 __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
-    const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int64_t N, int64_t K, int M) {
+    const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int64_t N, int64_t K, int M,
+    const uint16_t* __restrict__ scales) {
     using T = Tiled<BITS>;
     constexpr int GPG = T::GPG, GW = T::GW, SBE = T::SBE, C = 1 << BITS;
     constexpr int THREADS = NWK * 64;
@@ -82,6 +92,8 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
         // done with them the same memory holds its RBW partial 16x16 tiles ([n][m], 1 KB each)
         u32x4_t xstage[NWK][16 * 17];
         float redx[BITS == 1 ? NWK : 1][16];                // 1-bit: partial sum_k x per batch column
+        // block-scaled: scales of the workgroup's rows, [row block][K block][row in block]
+        uint16_t sct[SC ? RBW * kMaxScaledBlocks * 16 : 1];
     };
     __shared__ Smem sm;
 
@@ -109,7 +121,18 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
             const int r = i / C, e = i % C;
             int64_t row = (rb0 + r / 16) * 16 + (r % 16);
             row = row < N ? row : N - 1;
+            if constexpr (SC) row = 0;
             sm.tbl[r][e] = codebook[row * C + e];
+        }
+    }
+
+    if constexpr (SC) {
+        const int nblk = static_cast<int>(K / KMQ_BLOCK);
+        for (int e = threadIdx.x; e < RBW * 16 * nblk; e += THREADS) {
+            const int rl = e / nblk, blk = e % nblk;            // consecutive threads: consecutive blocks of a row
+            int64_t row = rb0 * 16 + rl;
+            row = row < N ? row : N - 1;
+            sm.sct[((rl >> 4) * nblk + blk) * 16 + (rl & 15)] = scales[row * nblk + blk];
         }
     }
 
@@ -143,6 +166,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
         for (int r = 0; r < RBW; ++r) {
             int64_t row = (rb0 + r) * 16 + n;
             row = row < N ? row : N - 1;
+            if constexpr (SC) row = 0;
             const uint32_t* cw = reinterpret_cast<const uint32_t*>(codebook + row * C);
             // v_perm_b32(S0, S1, sel): selector values 0..3 pick bytes of S1, 4..7 bytes of S0
             lo0[r] = __builtin_amdgcn_perm(cw[1], cw[0], 0x06040200u);
@@ -155,6 +179,13 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
                 hi1[r] = hi0[r];
             }
         }
+    }
+
+    [[maybe_unused]] float c0s = 0.f, cdiff = 0.f;          // 1-bit block-scaled: c0 and c1 - c0 of the tensor-wide pair
+    if constexpr (SC && BITS == 1) {
+        const uint32_t cc2 = *reinterpret_cast<const uint32_t*>(codebook);
+        c0s = bf16_to_f32(cc2 & 0xFFFFu);
+        cdiff = bf16_to_f32(cc2 >> 16) - c0s;
     }
 
     // Activations are fetched kXAhead chunks (of 4 steps) ahead of the chunk being multiplied.
@@ -214,48 +245,78 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
                     u32x4_t xf[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) xf[i] = xtile[n * 17 + q + 4 * i];
+                    auto decode = [&](int r, int j) -> u32x4_t {
+                        u32x4_t a;
+                        if constexpr (BITS == 1) {
+                            const uint32_t gb = group_bits<BITS, GW>(gran[p][r], j);
+                            const u32x2_t lo = sm.masks[gb & 15u], hi = sm.masks[gb >> 4];
+                            a = u32x4_t{lo[0], lo[1], hi[0], hi[1]};
+                        } else if constexpr (BITS == 4) {
+                            const uint32_t gb = group_bits<BITS, GW>(gran[p][r], j);
+                            uint32_t wv[8];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int j = cc * 4 + i;
-                        const bf16x8_t b = __builtin_bit_cast(bf16x8_t, xf[i]);
+                            for (int e = 0; e < 8; ++e) wv[e] = trow[r][(gb >> (4 * e)) & 15u];
+                            a = u32x4_t{wv[0] | (wv[1] << 16), wv[2] | (wv[3] << 16),
+                                        wv[4] | (wv[5] << 16), wv[6] | (wv[7] << 16)};
+                        } else {
 #pragma unroll
-                        for (int r = 0; r < RBW; ++r) {
-                            u32x4_t a;
+                            for (int h = 0; h < 2; ++h) {      // elements 4h..4h+3 of this step
+                                uint32_t sel;
+                                if constexpr (BITS == 2) {
+                                    const int c = 2 * j + h;
+                                    sel = (gran[p][r][c >> 2] >> (2 * (c & 3))) & 0x03030303u;
+                                } else {
+                                    const uint32_t* D = gran[p][r];
+                                    if (j < 3) sel = (h == 0 ? D[j] : D[j] >> 3) & 0x07070707u;
+                                    else if (h == 0) sel = ((D[0] >> 6) & 0x03030303u) | ((D[1] >> 4) & 0x04040404u);
+                                    else sel = ((D[1] >> 7) & 0x01010101u) | ((D[2] >> 5) & 0x06060606u);
+                                }
+                                const uint32_t lo = __builtin_amdgcn_perm(lo1[r], lo0[r], sel);
+                                const uint32_t hi = __builtin_amdgcn_perm(hi1[r], hi0[r], sel);
+                                a[2 * h] = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+                                a[2 * h + 1] = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+                            }
+                        }
+                        return a;
+                    };
+                    const u32x4_t ones = u32x4_t{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+                    if constexpr (!SC) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const int j = cc * 4 + i;
+                            const bf16x8_t b = __builtin_bit_cast(bf16x8_t, xf[i]);
+#pragma unroll
+                            for (int r = 0; r < RBW; ++r)
+                                acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, decode(r, j)), b, acc[r], 0, 0, 0);
+                            if constexpr (BITS == 1)
+                                accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ones), b, accx, 0, 0, 0);
+                        }
+                    } else {
+#pragma unroll
+                        for (int g2 = 0; g2 < 2; ++g2) {           // the chunk's two 64-column blocks
+                            const bf16x8_t b0 = __builtin_bit_cast(bf16x8_t, xf[2 * g2]), b1 = __builtin_bit_cast(bf16x8_t, xf[2 * g2 + 1]);
+                            const int j0 = cc * 4 + 2 * g2;
+                            const int blk = (sb0 + s) * (SBE / KMQ_BLOCK) + cc * 2 + g2;      // wave-uniform
+                            const f32x4_t zero = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                            [[maybe_unused]] f32x4_t tx = zero;
                             if constexpr (BITS == 1) {
-                                const uint32_t gb = group_bits<BITS, GW>(gran[p][r], j);
-                                const u32x2_t lo = sm.masks[gb & 15u], hi = sm.masks[gb >> 4];
-                                a = u32x4_t{lo[0], lo[1], hi[0], hi[1]};
-                            } else if constexpr (BITS == 4) {
-                                const uint32_t gb = group_bits<BITS, GW>(gran[p][r], j);
-                                uint32_t wv[8];
+                                tx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ones), b0, zero, 0, 0, 0);
+                                tx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ones), b1, tx, 0, 0, 0);
+                            }
 #pragma unroll
-                                for (int e = 0; e < 8; ++e) wv[e] = trow[r][(gb >> (4 * e)) & 15u];
-                                a = u32x4_t{wv[0] | (wv[1] << 16), wv[2] | (wv[3] << 16),
-                                            wv[4] | (wv[5] << 16), wv[6] | (wv[7] << 16)};
-                            } else {
+                            for (int r = 0; r < RBW; ++r) {
+                                f32x4_t t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, decode(r, j0)), b0, zero, 0, 0, 0);
+                                t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, decode(r, j0 + 1)), b1, t, 0, 0, 0);
+                                // scales of output rows 4q..4q+3 of this row block, one 8-byte read
+                                const u32x2_t s4 = *reinterpret_cast<const u32x2_t*>(&sm.sct[((r * static_cast<int>(K / KMQ_BLOCK)) + blk) * 16 + 4 * q]);
+                                const float sc[4] = {bf16_to_f32(s4[0] & 0xFFFFu), bf16_to_f32(s4[0] >> 16),
+                                                     bf16_to_f32(s4[1] & 0xFFFFu), bf16_to_f32(s4[1] >> 16)};
 #pragma unroll
-                                for (int h = 0; h < 2; ++h) {      // elements 4h..4h+3 of this step
-                                    uint32_t sel;
-                                    if constexpr (BITS == 2) {
-                                        const int c = 2 * j + h;
-                                        sel = (gran[p][r][c >> 2] >> (2 * (c & 3))) & 0x03030303u;
-                                    } else {
-                                        const uint32_t* D = gran[p][r];
-                                        if (j < 3) sel = (h == 0 ? D[j] : D[j] >> 3) & 0x07070707u;
-                                        else if (h == 0) sel = ((D[0] >> 6) & 0x03030303u) | ((D[1] >> 4) & 0x04040404u);
-                                        else sel = ((D[1] >> 7) & 0x01010101u) | ((D[2] >> 5) & 0x06060606u);
-                                    }
-                                    const uint32_t lo = __builtin_amdgcn_perm(lo1[r], lo0[r], sel);
-                                    const uint32_t hi = __builtin_amdgcn_perm(hi1[r], hi0[r], sel);
-                                    a[2 * h] = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
-                                    a[2 * h + 1] = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+                                for (int i = 0; i < 4; ++i) {
+                                    const float v = BITS == 1 ? fmaf(cdiff, t[i], c0s * tx[i]) : t[i];
+                                    acc[r][i] = fmaf(sc[i], v, acc[r][i]);
                                 }
                             }
-                            acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), b, acc[r], 0, 0, 0);
-                        }
-                        if constexpr (BITS == 1) {
-                            const u32x4_t ones = u32x4_t{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
-                            accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, ones), b, accx, 0, 0, 0);
                         }
                     }
                 }
@@ -274,7 +335,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     for (int r = 0; r < RBW; ++r)
 #pragma unroll
         for (int i = 0; i < 4; ++i) reinterpret_cast<float*>(xtile)[r * 256 + (4 * q + i) * 16 + n] = acc[r][i];
-    if constexpr (BITS == 1) {
+    if constexpr (BITS == 1 && !SC) {
         if (q == 0) sm.redx[wk][n] = accx[0];               // every row of the all-ones tile is sum_k x[m][k]
     }
     __syncthreads();
@@ -287,7 +348,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
         for (int k = 0; k < NWK; ++k) s += reinterpret_cast<const float*>(&sm.xstage[k][0])[r * 256 + nn * 16 + m];
         const int64_t row = (rb0 + r) * 16 + nn;
         if (m < M && row < N) {
-            if constexpr (BITS == 1) {
+            if constexpr (BITS == 1 && !SC) {
                 float sx = 0.f;
 #pragma unroll
                 for (int k = 0; k < NWK; ++k) sx += sm.redx[k][m];
@@ -305,8 +366,12 @@ template <int BITS, int NWK, int RBW, int SPW>
 static void launch_mfma_one(const GemmArgs& a, hipStream_t s) {
     const int64_t nrb = (a.N + 15) / 16;
     const dim3 grid(static_cast<unsigned>((nrb + RBW - 1) / RBW)), block(NWK * 64);
-    hipLaunchKernelGGL((gemm_mfma_kernel<BITS, NWK, RBW, SPW>), grid, block, 0, s,
-                       a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M);
+    if (a.scales)
+        hipLaunchKernelGGL((gemm_mfma_kernel<BITS, NWK, RBW, SPW, true>), grid, block, 0, s,
+                           a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.scales);
+    else
+        hipLaunchKernelGGL((gemm_mfma_kernel<BITS, NWK, RBW, SPW, false>), grid, block, 0, s,
+                           a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.scales);
 }
 
 // Launch shapes (waves along K, row blocks per wave, super-blocks per wave) with a

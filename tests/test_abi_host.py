@@ -150,7 +150,8 @@ def test_argument_errors_are_reported_before_any_launch():
 
     assert bs(sc=None) == 1 and bs(W=None) == 1 and bs(bits=9) == 2 and bs(M=17) == 3
     assert bs(K=96) == 3                               # not a whole number of 64-element blocks
-    assert bs(layout=1, K=256) == 7 and bs(sc=sc + 1) == 4
+    assert bs(layout=1, K=192) == 7 and bs(layout=1, K=32768) == 7 and bs(sc=sc + 1) == 4
+    assert kmq.kernel_name_blockscaled(4096, 4096, 3, 16, 1) == "mfma_sc_b3"
     assert lib.kmq_gemv_blockscaled(W, cb, None, x, y, 4, 64, 2, 0, None, 0, None) == 1
     assert kmq.kernel_name_blockscaled(4, 96, 2, 1) == "invalid"
     assert kmq.kernel_name_blockscaled(8192, 8192, 4, 1).startswith("lut_sc_b4")

@@ -90,6 +90,43 @@ def test_papers_benchmark_shape_full_size(gpu, bits):
     assert worst < 2e-3
 
 
+@pytest.mark.parametrize("bits", (1, 2, 3, 4))
+@pytest.mark.parametrize("N,K,M", [(16, 512, 16), (40, 1024, 4), (97, 4096, 8), (333, 3072, 1), (64, 8192, 16), (130, 2048, 2)])
+def test_tiled_layout_matrix_core_vs_oracle(gpu, bits, N, K, M):
+    """The block-scaled product on the tiled layout (matrix-core kernel), ragged row counts, every
+    batch kind, K with 1..16 super-blocks per wave."""
+    from paper_2602_15563_amd import kmq
+    if kmq.tiled_words(N, K, bits, 1) < 0:
+        pytest.skip("K is not a whole number of super-blocks at this bit-width")
+    idx, cb, sc, X = _case(19 * bits + N + K + M, N, K, bits, M)
+    p = kmq.pack(idx, bits)
+    t = kmq.repack(p, K, bits, 1)
+    assert kmq.kernel_name_blockscaled(N, K, bits, M, 1) == f"mfma_sc_b{bits}"
+    import torch
+    Y = torch.full((M, N), 0x7FC1, dtype=torch.int16, device="cuda")
+    kmq.gemm_smallbatch_blockscaled(gpu.dev(t), gpu.dev(cb), gpu.dev(sc), gpu.dev(X), Y, N, K, M, bits, 1)
+    torch.cuda.synchronize()
+    gpu.check_blockscaled_against_oracle(gpu.host_u16(Y), oracle.pack(idx, bits), cb, sc, X, K, bits,
+                                         label=f"tiled b{bits} {N}x{K} M{M}")
+
+
+def test_tiled_only_the_scaled_block_contributes(gpu):
+    from paper_2602_15563_amd import kmq
+    import torch
+    bits, N, K, M = 3, 48, 4096, 16
+    idx, cb, sc, X = _case(91, N, K, bits, M)
+    t = gpu.dev(kmq.repack(kmq.pack(idx, bits), K, bits, 1))
+    for r, g in ((0, 0), (17, 1), (47, 63), (33, 30)):
+        z = np.zeros_like(sc)
+        z[r, g] = sc[r, g]
+        Y = torch.full((M, N), 0x7FC1, dtype=torch.int16, device="cuda")
+        kmq.gemm_smallbatch_blockscaled(t, gpu.dev(cb), gpu.dev(z), gpu.dev(X), Y, N, K, M, bits, 1)
+        torch.cuda.synchronize()
+        Yg = gpu.host_u16(Y)
+        gpu.check_blockscaled_against_oracle(Yg, oracle.pack(idx, bits), cb, z, X, K, bits, strict=False, label=f"r{r} g{g}")
+        assert not np.delete(synth.bf16_to_f32(Yg), r, axis=1).any()
+
+
 def test_errors(gpu):
     from paper_2602_15563_amd import kmq
     import torch
@@ -101,7 +138,7 @@ def test_errors(gpu):
         kmq.gemv_blockscaled(p, cbd, scd, xd, y, N, K - 32, bits)       # K not a multiple of 64
     assert e.value.status == 3
     with pytest.raises(kmq.KmqError) as e:
-        kmq.gemv_blockscaled(p, cbd, scd, xd, y, N, K, bits, layout=1)  # tiled layout not offered
+        kmq.gemv_blockscaled(p, cbd, scd, xd, y, N, K, bits, layout=1)  # K = 128 is not a whole 2-bit super-block
     assert e.value.status == 7
     with pytest.raises(kmq.KmqError) as e:
         kmq.gemv_blockscaled(p, cbd, None, xd, y, N, K, bits)
