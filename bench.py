@@ -40,6 +40,7 @@ WORKLOADS = {
     "cfg4_qkv_b1_9216x3072_m1": (1, 9216, 3072, 1, 4, 0, True),
     "cfg4_o_b1_3072x3072_m1": (1, 3072, 3072, 1, 4, 1, True),
     "cfg4_gate_b1_8192x3072_m1": (1, 8192, 3072, 1, 4, 2, True),
+    "cfg4_up_b1_8192x3072_m1": (1, 8192, 3072, 1, 4, 3, True),
     "cfg4_down_b1_3072x8192_m1": (1, 3072, 8192, 1, 4, 4, True),
     "cfg4_qkv_b1_9216x3072_m4": (1, 9216, 3072, 4, 4, 0, True),
     "cfg4_qkv_b1_9216x3072_m16": (1, 9216, 3072, 16, 4, 0, True),
@@ -202,10 +203,10 @@ def time_workload(inst: Instances, steps: int, warmup: int, use_graph: bool = Tr
 
 SWEEP_LAYERS = 28
 SWEEP_SHAPES = ["cfg4_qkv_b1_9216x3072_m1", "cfg4_o_b1_3072x3072_m1", "cfg4_gate_b1_8192x3072_m1",
-                "cfg4_gate_b1_8192x3072_m1", "cfg4_down_b1_3072x8192_m1"]       # gate and up are two matrices
+                "cfg4_up_b1_8192x3072_m1", "cfg4_down_b1_3072x8192_m1"]         # gate and up are two matrices
 
 
-def run_sweep(M: int, replays: int):
+def run_sweep(M: int, replays: int, fuse_gate_up: bool = False):
     """The 1-bit decoder-layer sweep of the fifth contract configuration: 28 layers x
     (fused QKV, O, gate, up, down), every matrix with its own weights (396 MB of indices, so
     each pass streams from HBM), captured as one HIP graph of 140 calls on one stream."""
@@ -216,6 +217,27 @@ def run_sweep(M: int, replays: int):
     from paper_2602_15563_amd import synth
     insts = [Instances(n, R=SWEEP_LAYERS, M=M) for n in SWEEP_SHAPES]
     worst = max(it.check() for it in insts)
+    gate, up = insts[2], insts[3]
+    if fuse_gate_up:
+        # gate and up in one launch with the SwiGLU that consumes them (batch 1, canonical layout)
+        from paper_2602_15563_amd import kmq
+        assert M == 1
+        ysw = [torch.zeros(gate.N, dtype=torch.int16, device="cuda") for _ in range(SWEEP_LAYERS)]
+
+        def fused_call(layer):
+            kmq.gemv_swiglu(gate.W[layer], gate.C[layer], up.W[layer], up.C[layer], gate.Xd[layer], ysw[layer],
+                            gate.N, gate.K, gate.bits)
+        fused_call(0)
+        torch.cuda.synchronize()
+        yg = synth.bf16_to_f64(ysw[0].cpu().numpy().view(np.uint16))
+        for n0 in (0, gate.N // 2, gate.N - 64):
+            G, Ag, _ = oracle.gemm(gate.packed, gate.cb, gate.X, gate.K, gate.bits, rows=(n0, n0 + 64))
+            U, Au, _ = oracle.gemm(up.packed, up.cb, gate.X, gate.K, gate.bits, rows=(n0, n0 + 64))
+            G, Ag, U, Au = G[0, n0:n0 + 64], Ag[0, n0:n0 + 64], U[0, n0:n0 + 64], Au[0, n0:n0 + 64]
+            want = oracle.swiglu(G, U)
+            tol = 2e-3 * (1.1 * np.abs(U) * Ag + np.abs(oracle.swiglu(G, np.ones_like(G))) * Au) + 2.0 ** -8 * np.abs(want)
+            if not np.all(np.abs(yg[n0:n0 + 64] - want) <= tol):
+                raise SystemExit("bench: the fused gate/up/SwiGLU call does not match the oracle")
     # one later layer (device-drawn weights) against the oracle as well, on sampled rows
     layer = 17
     for it in insts:
@@ -238,15 +260,21 @@ def run_sweep(M: int, replays: int):
             worst = max(worst, float(np.max(err / np.maximum(A[:, n0:n0 + 64], 1e-300))))
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
-        for layer in range(SWEEP_LAYERS):
-            for it in insts:
-                it.call(layer)
+        def one_pass():
+            for layer in range(SWEEP_LAYERS):
+                if fuse_gate_up:
+                    insts[0].call(layer)
+                    insts[1].call(layer)
+                    fused_call(layer)
+                    insts[4].call(layer)
+                else:
+                    for it in insts:
+                        it.call(layer)
+        one_pass()
         stream.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
-            for layer in range(SWEEP_LAYERS):
-                for it in insts:
-                    it.call(layer)
+            one_pass()
         graph.replay()
         stream.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -257,8 +285,8 @@ def run_sweep(M: int, replays: int):
         stream.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / replays
     nbytes = SWEEP_LAYERS * sum(it.bytes for it in insts)
-    calls = SWEEP_LAYERS * len(insts)
-    return {"workload": f"cfg4_sweep_28layers_m{M}", "us_per_sweep": round(us, 2), "us_per_call": round(us / calls, 3),
+    calls = SWEEP_LAYERS * (len(insts) - (1 if fuse_gate_up else 0))
+    return {"workload": f"cfg4_sweep_28layers_m{M}" + ("_fused_gate_up_swiglu" if fuse_gate_up else ""), "us_per_sweep": round(us, 2), "us_per_call": round(us / calls, 3),
             "calls": calls, "GBps": round(nbytes / us * 1e-3, 1), "pct_peak": round(100 * nbytes / us * 1e-3 / HBM_PEAK_GBS, 2),
             "bytes": nbytes, "kernels": sorted({it.kernel for it in insts}),
             "layout": "tiled" if insts[0].layout else "canonical", "max_err_over_A": float(f"{worst:.3e}")}
@@ -471,8 +499,8 @@ def main():
 
     if args.sweep:
         rows = []
-        for M in (1, 4, 16):
-            rows.append(run_sweep(M, 200))
+        for M, fused in ((1, False), (1, True), (4, False), (16, False)):
+            rows.append(run_sweep(M, 200, fuse_gate_up=fused))
             print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
             torch.cuda.empty_cache()
         os.makedirs(args.out, exist_ok=True)

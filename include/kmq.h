@@ -162,6 +162,18 @@ kmq_status kmq_gemm_smallbatch_blockscaled(const uint32_t* W, const uint16_t* co
 /* As kmq_kernel_name, for the block-scaled calls. */
 const char* kmq_kernel_name_blockscaled(int64_t N, int64_t K, int bits, int M, int layout);
 
+/* Fused gate / up / SwiGLU of a decoder MLP (App. E "Model benchmarks": token generation runs the
+ * backbone's projections one after another, with the activation function between them as extra
+ * cost): y[n] = silu(Wgate[n] . x) * (Wup[n] . x), silu(t) = t / (1 + exp(-t)), both products
+ * and the combination in fp32, one rounding to bf16.  Both matrices are N x K in the per-row-codebook
+ * format, KMQ_LAYOUT_CANONICAL (else KMQ_ERR_LAYOUT), same bits; alignment as kmq_gemv; 2N <= 2^24.
+ * One launch instead of two products and an elementwise pass. */
+kmq_status kmq_gemv_swiglu(const uint32_t* Wgate, const uint16_t* codebook_gate,
+                           const uint32_t* Wup, const uint16_t* codebook_up,
+                           const uint16_t* x, uint16_t* y, int64_t N, int64_t K, int bits, int layout,
+                           void* hip_stream);
+const char* kmq_kernel_name_swiglu(int64_t N, int64_t K, int bits, int layout);
+
 /* Dense bf16 GEMV, y = W x with W N x K bf16 bit patterns, row-major: the unquantised
  * baseline of the paper's micro-benchmark table (App. E, the 16-bit rows), provided so that
  * speed-ups can be quoted against a bf16 product on the same machine.  fp32 accumulation,

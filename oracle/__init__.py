@@ -54,6 +54,8 @@ def _load():
         lib.oracle_gemm.argtypes = [vp, vp, vp, i64, i64, ci, i64, i64, i64, vp, vp, vp]
         lib.oracle_gemm_blockscaled.restype = ci
         lib.oracle_gemm_blockscaled.argtypes = [vp, vp, vp, vp, i64, i64, ci, i64, i64, i64, i64, ci, vp, vp, vp]
+        lib.oracle_swiglu.restype = ci
+        lib.oracle_swiglu.argtypes = [vp, vp, i64, vp]
         lib.oracle_gemm_dense.restype = ci
         lib.oracle_gemm_dense.argtypes = [vp, vp, i64, i64, i64, i64, i64, vp, vp, vp]
         _lib = lib
@@ -194,3 +196,15 @@ def gemm_dense(W: np.ndarray, X: np.ndarray, rows: tuple[int, int] | None = None
     if vec:
         return Y[0], A[0], Yb[0]
     return Y, A, Yb
+
+
+def swiglu(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
+    """silu(gate) * up element-wise on fp64 arrays (the fused call's definition)."""
+    g = np.ascontiguousarray(gate, dtype=np.float64)
+    u = np.ascontiguousarray(up, dtype=np.float64)
+    if g.shape != u.shape:
+        raise ValueError("shapes differ")
+    y = np.empty_like(g)
+    if _load().oracle_swiglu(_p(g), _p(u), g.size, _p(y)):
+        raise ValueError("bad argument")
+    return y

@@ -216,6 +216,15 @@ int oracle_gemm_blockscaled(const uint32_t* packed, const uint16_t* codebook, co
     return 0;
 }
 
+// SwiGLU of a decoder MLP's gate and up projections (Shazeer-style gated unit with the SiLU
+// activation, as in the Llama-3 architecture the paper benchmarks, App. E "Model benchmarks"):
+// y[i] = silu(g[i]) * u[i], silu(t) = t / (1 + exp(-t)), on fp64 inputs.
+int oracle_swiglu(const double* gate, const double* up, int64_t n, double* y) {
+    if (n < 0) return 1;
+    for (int64_t i = 0; i < n; ++i) y[i] = gate[i] / (1.0 + std::exp(-gate[i])) * up[i];
+    return 0;
+}
+
 // Dense bf16 matrix times bf16 vectors, the unquantised baseline the paper compares
 // against (App. E, Table of m = 1, h = 8192, the 16-bit rows): Y[m][n] = sum_k W[n][k]*X[m][k]
 // in fp64, k ascending.  W is N x K bf16 bit patterns, row-major.

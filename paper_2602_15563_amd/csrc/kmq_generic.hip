@@ -95,6 +95,57 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
     }
 }
 
+// Fused pair, any K, canonical layout, batch 1: y[n] = silu(W[n] . x) * (W2[n] . x), the
+// SwiGLU of a decoder MLP's gate and up projections (both products share x).  One wave per
+// output element walks both rows.
+template <int BITS>
+__global__ __launch_bounds__(256) void gemv_pair_generic_kernel(
+    const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
+    const uint32_t* __restrict__ W2, const uint16_t* __restrict__ codebook2,
+    const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int64_t N, int64_t K) {
+    constexpr int C = 1 << BITS;
+    __shared__ float lut[4][2][C];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t n = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+    const bool live = n < N;
+    if (live && lane < 2 * C)
+        lut[wave][lane / C][lane % C] = bf16_to_f32((lane < C ? codebook : codebook2)[n * C + lane % C]);
+    __syncthreads();
+    if (!live) return;
+    const int64_t wpr = words_per_row(BITS, K);
+    const int64_t ngroups = (K + 31) >> 5;
+    float acc[2] = {0.f, 0.f};
+    for (int64_t g = lane; g < ngroups; g += kWave) {
+        const int64_t k0 = g << 5;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t* row = (h ? W2 : W) + n * wpr;
+            uint32_t w[BITS];
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) {
+                const int64_t wi = g * BITS + j;
+                w[j] = wi < wpr ? row[wi] : 0u;
+            }
+#pragma unroll
+            for (int e = 0; e < 32; ++e)
+                if (k0 + e < K) acc[h] = fmaf(lut[wave][h][group_field<BITS>(w, e)], bf16_to_f32(x[k0 + e]), acc[h]);
+        }
+    }
+    const float gate = group_sum<64>(acc[0]), up = group_sum<64>(acc[1]);
+    if (lane == 63) y[n] = f32_to_bf16(gate / (1.f + __expf(-gate)) * up);
+}
+
+hipError_t launch_pair_generic(const GemmArgs& a, hipStream_t s) {
+    const dim3 grid(static_cast<unsigned>((a.N + 3) / 4)), block(256);
+    switch (a.bits) {
+        case 1: hipLaunchKernelGGL(gemv_pair_generic_kernel<1>, grid, block, 0, s, a.W, a.codebook, a.W2, a.codebook2, a.X, a.Y, a.N, a.K); break;
+        case 2: hipLaunchKernelGGL(gemv_pair_generic_kernel<2>, grid, block, 0, s, a.W, a.codebook, a.W2, a.codebook2, a.X, a.Y, a.N, a.K); break;
+        case 3: hipLaunchKernelGGL(gemv_pair_generic_kernel<3>, grid, block, 0, s, a.W, a.codebook, a.W2, a.codebook2, a.X, a.Y, a.N, a.K); break;
+        default: hipLaunchKernelGGL(gemv_pair_generic_kernel<4>, grid, block, 0, s, a.W, a.codebook, a.W2, a.codebook2, a.X, a.Y, a.N, a.K); break;
+    }
+    return hipGetLastError();
+}
+
 // One thread per (row, 32-element group): Wdense[n][k] = codebook[n][idx[n][k]].
 template <int BITS>
 __global__ __launch_bounds__(256) void dequant_kernel(

@@ -19,6 +19,8 @@ struct GemmArgs {
     void* workspace;
     size_t workspace_bytes;
     const uint16_t* scales = nullptr;   // block-scaled format: N x K/64 bf16, and `codebook` is one tensor-wide table
+    const uint32_t* W2 = nullptr;       // fused pair (gate, up): second matrix and its codebooks, same shape and format
+    const uint16_t* codebook2 = nullptr;
 };
 
 // Kernel variants the heuristic can pick (kmq_kernel_name reports them).
@@ -49,6 +51,7 @@ int rowsplit_find(int64_t K, int bits, int layout);
 const char* rowsplit_name(int table_index);
 hipError_t launch_rowsplit(int table_index, const GemmArgs& a, hipStream_t s);
 
+hipError_t launch_pair_generic(const GemmArgs& a, hipStream_t s);
 hipError_t launch_blockscaled_generic(const GemmArgs& a, hipStream_t s);
 
 // Dense bf16 baseline; K * 2 bytes of LDS, so K <= 32768.

@@ -230,11 +230,18 @@ __device__ __forceinline__ void load_words(const uint32_t* p, uint32_t (&w)[G]) 
 // per block of 64 elements of a row; a lane's slice is a whole number of blocks (or half of
 // one), so its fp32 block sums are scaled once, before the reduction over lanes (the
 // deferred-scaling variant of App. E "Kernel implementations").
-template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE, bool SC>
+//
+// PAIR fuses two products that share x, as a decoder MLP's gate and up projections do, with the
+// SwiGLU that consumes them: y[n] = silu(W[n] . x) * (W2[n] . x).  The kernel then walks 2N
+// "virtual" rows, row 2n from (W, codebook) and row 2n + 1 from (W2, codebook2); N is passed as
+// the virtual count, and the thread that would store a pair of outputs stores their combination.
+template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE, bool SC, bool PAIR>
 __global__ __launch_bounds__(NWK * NWR * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
                      const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int64_t N,
-                     const uint16_t* __restrict__ scales) {
+                     const uint16_t* __restrict__ scales,
+                     const uint32_t* __restrict__ W2, const uint16_t* __restrict__ codebook2) {
+    static_assert(!(SC && PAIR), "the fused pair is offered for the per-row-codebook format");
     static_assert(BITS == 1 || BITS == 2 || BITS == 4, "3-bit fields do not align with nibbles");
     constexpr int C = 1 << BITS;
     constexpr int EL = G * 32 / BITS;              // elements per lane and row slice
@@ -280,6 +287,25 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     const int sub = lane / LPR, pos = lane % LPR;
     const int64_t wg_row0 = static_cast<int64_t>(blockIdx.x) * ROWS_WG;
     const int64_t wave_row0 = wg_row0 + wr * ROWS_WAVE;
+    // start of a row's packed words / codebook (PAIR: even virtual rows first matrix, odd rows second)
+    // PAIR: even virtual rows come from the first matrix, odd rows from the second.  The choice
+    // is plain integer arithmetic on the addresses: a select between two pointer arguments can
+    // end up as a two-entry table in scratch memory, and a kernel that uses scratch pays for
+    // its set-up at every launch (measured: +15 us per call).
+    const uintptr_t w_a = reinterpret_cast<uintptr_t>(W), w_d = PAIR ? reinterpret_cast<uintptr_t>(W2) - w_a : 0;
+    const uintptr_t c_a = reinterpret_cast<uintptr_t>(codebook), c_d = PAIR ? reinterpret_cast<uintptr_t>(codebook2) - c_a : 0;
+    auto wrow = [=](int64_t row) -> const uint32_t* {
+        if constexpr (PAIR)
+            return reinterpret_cast<const uint32_t*>(w_a + (w_d & (uintptr_t(0) - uintptr_t(row & 1)))) + (row >> 1) * WPR;
+        else
+            return reinterpret_cast<const uint32_t*>(w_a) + row * WPR;
+    };
+    auto cbrow = [=](int64_t row) -> const uint16_t* {
+        if constexpr (PAIR)
+            return reinterpret_cast<const uint16_t*>(c_a + (c_d & (uintptr_t(0) - uintptr_t(row & 1)))) + (row >> 1) * C;
+        else
+            return reinterpret_cast<const uint16_t*>(c_a) + row * C;
+    };
 
     // ---- 1. small operands first: x chunks, then the codebook rows of this wave's own rows ----
     // Loads return in issue order.  x comes from the L2 and is there early; the codebook
@@ -306,11 +332,11 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         row = row < N ? row : N - 1;
         if constexpr (SC) row = 0;                                     // one table for the whole tensor
         if constexpr (BITS == 2) {
-            const u32x2_t c = *reinterpret_cast<const u32x2_t*>(codebook + row * C);
+            const u32x2_t c = *reinterpret_cast<const u32x2_t*>(cbrow(row));
             cbv[p][0] = c[0];
             cbv[p][1] = c[1];
         } else {
-            cbv[p][0] = codebook[row * C + (lane & 15)];
+            cbv[p][0] = cbrow(row)[lane & 15];
         }
     }
 
@@ -327,7 +353,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     for (int t = 0; t < RS; ++t) {
         int64_t row = wave_row0 + t * RPL + sub;
         row = row < N ? row : N - 1;                                   // clamped: loads stay unconditional
-        load_words<G>(W + row * WPR + (wk * LPR + pos) * G, w[t]);
+        load_words<G>(wrow(row) + (wk * LPR + pos) * G, w[t]);
     }
     // block scales of this lane's slices: last in the queue, used after the lookups
     [[maybe_unused]] uint16_t sv[RS][NSC];
@@ -510,13 +536,18 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
                 for (int k = 0; k < NWK; ++k) sx += sm.sxp[k];
                 int64_t row = wg_row0 + rl;
                 row = row < N ? row : N - 1;
-                const uint32_t cc = *reinterpret_cast<const uint32_t*>(codebook + row * 2);
+                const uint32_t cc = *reinterpret_cast<const uint32_t*>(cbrow(row));
                 const float c0 = bf16_to_f32(cc & 0xFFFFu), c1 = bf16_to_f32(cc >> 16);
                 s = fmaf(c1 - c0, s, c0 * sx);
             }
             out[h] = s;
         }
         const int64_t r2 = wg_row0 + threadIdx.x * 2;
+        if constexpr (PAIR) {
+            // out[0] = gate, out[1] = up of output element r2 / 2: silu(gate) * up in fp32
+            if (r2 < N) y[r2 >> 1] = f32_to_bf16(out[0] / (1.f + __expf(-out[0])) * out[1]);
+            return;
+        }
         const uint32_t packed = static_cast<uint32_t>(f32_to_bf16(out[0])) | (static_cast<uint32_t>(f32_to_bf16(out[1])) << 16);
         if (r2 + 1 < N && (reinterpret_cast<uintptr_t>(y) & 3u) == 0) {
             *reinterpret_cast<uint32_t*>(y + r2) = packed;
@@ -541,9 +572,19 @@ struct LutEntry {
 template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE, bool SC>
 static void launch_lut(const GemmArgs& a, hipStream_t s) {
     constexpr int rows_wg = NWR * (kWave / LPR) * RS;
-    const dim3 grid(static_cast<unsigned>((a.N + rows_wg - 1) / rows_wg)), block(NWK * NWR * 64);
-    hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, SC>), grid, block, 0, s,
-                       a.W, a.codebook, a.X, a.Y, a.N, a.scales);
+    const dim3 block(NWK * NWR * 64);
+    if constexpr (!SC) {
+        if (a.W2) {                                           // fused pair: 2N virtual rows
+            const int64_t nv = 2 * a.N;
+            const dim3 grid(static_cast<unsigned>((nv + rows_wg - 1) / rows_wg));
+            hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, true>), grid, block, 0, s,
+                               a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2);
+            return;
+        }
+    }
+    const dim3 grid(static_cast<unsigned>((a.N + rows_wg - 1) / rows_wg));
+    hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, SC, false>), grid, block, 0, s,
+                       a.W, a.codebook, a.X, a.Y, a.N, a.scales, nullptr, nullptr);
 }
 
 #define KMQ_LUT(BITS, G, LPR, NWK, NWR, RS, WPE) \

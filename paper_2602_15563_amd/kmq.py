@@ -66,6 +66,10 @@ _lib.kmq_gemm_smallbatch_blockscaled.restype = ctypes.c_int32
 _lib.kmq_gemm_smallbatch_blockscaled.argtypes = [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp, _sz, _vp]
 _lib.kmq_kernel_name_blockscaled.restype = ctypes.c_char_p
 _lib.kmq_kernel_name_blockscaled.argtypes = [_i64, _i64, _int, _int, _int]
+_lib.kmq_gemv_swiglu.restype = ctypes.c_int32
+_lib.kmq_gemv_swiglu.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _vp]
+_lib.kmq_kernel_name_swiglu.restype = ctypes.c_char_p
+_lib.kmq_kernel_name_swiglu.argtypes = [_i64, _i64, _int, _int]
 _lib.kmq_gemv_bf16.restype = ctypes.c_int32
 _lib.kmq_gemv_bf16.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
 _lib.kmq_stream_read.restype = ctypes.c_int32
@@ -200,6 +204,16 @@ def gemm_smallbatch_blockscaled(W, codebook, scales, X, Y, N: int, K: int, M: in
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(_lib.kmq_gemm_smallbatch_blockscaled(_ptr(W), _ptr(codebook), _ptr(scales), _ptr(X), _ptr(Y), N, K, M,
                                                 bits, layout, _ptr(workspace), ws_bytes, _stream()))
+
+
+def kernel_name_swiglu(N: int, K: int, bits: int, layout: int = 0) -> str:
+    return _lib.kmq_kernel_name_swiglu(N, K, bits, layout).decode()
+
+
+def gemv_swiglu(Wgate, codebook_gate, Wup, codebook_up, x, y, N: int, K: int, bits: int, layout: int = 0):
+    """y[N] = silu(Wgate x) * (Wup x) in one launch, on torch's current stream."""
+    _check(_lib.kmq_gemv_swiglu(_ptr(Wgate), _ptr(codebook_gate), _ptr(Wup), _ptr(codebook_up), _ptr(x), _ptr(y),
+                                N, K, bits, layout, _stream()))
 
 
 def gemv_bf16(W, x, y, N: int, K: int):

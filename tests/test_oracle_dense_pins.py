@@ -45,3 +45,18 @@ def test_hand_values_and_rows_argument():
     assert Y.tolist() == [0.0, 3.5] and A.tolist() == [6.0, 3.5]
     Yr, _, _ = oracle.gemm_dense(W, x, rows=(1, 2))
     assert np.isnan(Yr[0]) and Yr[1] == 3.5
+
+
+def test_swiglu_pins():
+    """silu by its textbook properties: value at 0 and 1, the identity silu(t) - silu(-t) = t,
+    the limits, the slope 1/2 at the origin, and the product with `up`."""
+    t = np.array([0.0, 1.0, -1.0, 3.5, -3.5, 30.0, -30.0, 1e-6])
+    one = np.ones_like(t)
+    y = oracle.swiglu(t, one)
+    assert y[0] == 0.0
+    assert abs(y[1] - 0.7310585786300049) < 1e-15            # 1 / (1 + e^-1)
+    assert np.allclose(oracle.swiglu(t, one) - oracle.swiglu(-t, one), t, rtol=0, atol=1e-15 * (1 + np.abs(t)))
+    assert abs(y[5] - 30.0) < 1e-11 and abs(y[6]) < 1e-11
+    assert abs(y[7] / 1e-6 - 0.5) < 1e-6
+    assert np.array_equal(oracle.swiglu(t, -2.5 * one), -2.5 * y)
+    assert abs(oracle.swiglu(np.array([2.0]), np.array([3.0]))[0] - 2.0 / (1.0 + np.exp(-2.0)) * 3.0) < 1e-15
