@@ -233,25 +233,11 @@ static void launch_one(const GemmArgs& a, hipStream_t s) {
     { BITS, int64_t(S) * LPR * (G * 32 / BITS), 4 * (64 / LPR) * RS, \
       "rowsplit_b" #BITS "_g" #G "_s" #S "_l" #LPR "_r" #RS, &launch_one<BITS, G, S, LPR, RS> }
 
+// Only the 3-bit shapes are instantiated: 1-, 2- and 4-bit batch-1 products take the
+// hand-scheduled table kernels (kmq_lut.hip), which supersede this kernel's paths for them.
 static const RowsplitEntry kRowsplit[] = {
-    // 1-bit
-    KMQ_ROWSPLIT(1, 4, 1, 16, 2),   // K = 2048
-    KMQ_ROWSPLIT(1, 3, 1, 32, 2),   // K = 3072
-    KMQ_ROWSPLIT(1, 4, 1, 32, 2),   // K = 4096
-    KMQ_ROWSPLIT(1, 4, 1, 64, 4),   // K = 8192
-    // 2-bit
-    KMQ_ROWSPLIT(2, 4, 1, 32, 2),   // K = 2048
-    KMQ_ROWSPLIT(2, 3, 1, 64, 4),   // K = 3072
-    KMQ_ROWSPLIT(2, 4, 1, 64, 4),   // K = 4096
-    KMQ_ROWSPLIT(2, 4, 2, 64, 4),   // K = 8192
-    KMQ_ROWSPLIT(2, 2, 7, 64, 2),   // K = 14336
-    // 3-bit
     KMQ_ROWSPLIT(3, 3, 1, 64, 4),   // K = 2048
     KMQ_ROWSPLIT(3, 3, 2, 64, 4),   // K = 4096
-    // 4-bit
-    KMQ_ROWSPLIT(4, 4, 1, 64, 4),   // K = 2048
-    KMQ_ROWSPLIT(4, 4, 2, 64, 4),   // K = 4096
-    KMQ_ROWSPLIT(4, 4, 4, 64, 2),   // K = 8192
 };
 constexpr int kRowsplitCount = sizeof(kRowsplit) / sizeof(kRowsplit[0]);
 
