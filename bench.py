@@ -453,7 +453,7 @@ def main():
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": round(gbs / PAPER_NUMBERS[args.workload][0], 3) if args.workload in PAPER_NUMBERS else None,
-        "dtype": "bf16 in/out, fp32 accumulate", "data": "synthetic",
+        "dtype": "bf16", "accumulate_dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "bits": inst.bits, "N": inst.N, "K": inst.K, "batch": inst.M,
                    "kernel": inst.kernel, "layout": "tiled" if inst.layout else "canonical",
                    "rotating_instances": inst.R, "hip_graph": not args.no_graph,
