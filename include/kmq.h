@@ -107,7 +107,12 @@ kmq_status kmq_unrepack(const uint32_t* tiled, int64_t N, int64_t K, int bits, i
 int64_t kmq_tiled_words(int64_t N, int64_t K, int bits, int layout);
 
 /* Bytes of device workspace kmq_gemv / kmq_gemm_smallbatch need for this
- * problem (split-K partial sums; 0 when the chosen kernel needs none).
+ * problem: 0 unless the rows are too few to fill the compute units and long
+ * (canonical layout, ceil(N/4) <= 128 and K >= 16384, no shape-specialised
+ * kernel), where K is split over workgroups and the workspace holds
+ * slices * M * N fp32 partial sums, added in slice order by a second kernel
+ * (deterministic).  The workspace need not be initialised and may be reused
+ * by later calls on the same stream.
  * Returns 0 on bad arguments (the compute call then reports the error). */
 size_t kmq_workspace_bytes(int64_t N, int64_t K, int bits, int M, int layout);
 

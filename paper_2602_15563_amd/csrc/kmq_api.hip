@@ -39,6 +39,9 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled) {
         const int i = rowsplit_find(K, bits, layout);
         if (i >= 0) return Plan{kVariantRowsplit, i, 0, rowsplit_name(i)};
     }
+    const int slices = generic_splitk_slices(N, K, layout);
+    if (slices > 1)
+        return Plan{kVariantGeneric, slices, static_cast<size_t>(slices) * M * N * sizeof(float), "generic_splitk"};
     return Plan{kVariantGeneric, -1, 0, "generic"};
 }
 

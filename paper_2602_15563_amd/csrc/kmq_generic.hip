@@ -24,11 +24,17 @@ __device__ __forceinline__ uint32_t group_field(const uint32_t (&w)[BITS], int e
 // 32-element groups (BITS words each, so groups start on a word boundary for
 // every bit-width), looks weights up in the row's codebook (fp32 copy in LDS)
 // and accumulates MT batch columns.
+//
+// Split-K (few rows, long rows: too few workgroups to fill the CUs otherwise): blockIdx.y
+// selects one of gridDim.y slices of K (whole 32-element groups); the slice's fp32 partial
+// sums go to partial[slice][m][n] and splitk_reduce_kernel adds the slices in index order, so
+// the result does not depend on which workgroup finishes first.  partial == nullptr: one
+// slice, bf16 output written directly.
 template <int BITS, int MT>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(
     const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
     const uint16_t* __restrict__ X, uint16_t* __restrict__ Y,
-    int64_t N, int64_t K, int M, int layout) {
+    int64_t N, int64_t K, int M, int layout, float* __restrict__ partial) {
     constexpr int C = 1 << BITS;
     __shared__ float lut[4][C];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -45,7 +51,9 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 #pragma unroll
     for (int m = 0; m < MT; ++m) acc[m] = 0.f;
 
-    for (int64_t g = lane; g < ngroups; g += kWave) {
+    const int64_t gps = (ngroups + gridDim.y - 1) / gridDim.y;     // groups per slice
+    const int64_t g_begin = blockIdx.y * gps, g_end = g_begin + gps < ngroups ? g_begin + gps : ngroups;
+    for (int64_t g = g_begin + lane; g < g_end; g += kWave) {
         const int64_t k0 = g << 5;
         const bool full = k0 + 32 <= K;
         float wt[32];
@@ -91,8 +99,21 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
         const float s = group_sum<64>(acc[m]);
-        if (lane == 63 && m < M) Y[static_cast<int64_t>(m) * N + n] = f32_to_bf16(s);
+        if (lane == 63 && m < M) {
+            if (partial) partial[(static_cast<int64_t>(blockIdx.y) * M + m) * N + n] = s;
+            else Y[static_cast<int64_t>(m) * N + n] = f32_to_bf16(s);
+        }
     }
+}
+
+// Second pass of split-K: Y[m][n] = bf16( partial[0][m][n] + partial[1][m][n] + ... ), slices in order.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, uint16_t* __restrict__ Y,
+                                                            int64_t MN, int slices) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= MN) return;
+    float s = 0.f;
+    for (int k = 0; k < slices; ++k) s += partial[static_cast<int64_t>(k) * MN + i];
+    Y[i] = f32_to_bf16(s);
 }
 
 // Fused pair, any K, canonical layout, batch 1: y[n] = silu(W[n] . x) * (W2[n] . x), the
@@ -210,25 +231,44 @@ hipError_t launch_stream_read(const void* p, size_t bytes, void* sink, hipStream
 }
 
 template <int BITS>
-static hipError_t launch_generic_bits(const GemmArgs& a, hipStream_t s) {
-    const dim3 grid(static_cast<unsigned>((a.N + 3) / 4)), block(256);
-    if (a.M == 1)
-        hipLaunchKernelGGL((gemm_generic_kernel<BITS, 1>), grid, block, 0, s, a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.layout);
-    else if (a.M <= 4)
-        hipLaunchKernelGGL((gemm_generic_kernel<BITS, 4>), grid, block, 0, s, a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.layout);
-    else if (a.M <= 8)
-        hipLaunchKernelGGL((gemm_generic_kernel<BITS, 8>), grid, block, 0, s, a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.layout);
-    else
-        hipLaunchKernelGGL((gemm_generic_kernel<BITS, 16>), grid, block, 0, s, a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.layout);
+static hipError_t launch_generic_bits(const GemmArgs& a, int slices, hipStream_t s) {
+    const dim3 grid(static_cast<unsigned>((a.N + 3) / 4), static_cast<unsigned>(slices)), block(256);
+    float* partial = slices > 1 ? static_cast<float*>(a.workspace) : nullptr;
+#define KMQ_GEN_LAUNCH(MT) \
+    hipLaunchKernelGGL((gemm_generic_kernel<BITS, MT>), grid, block, 0, s, a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.layout, partial)
+    if (a.M == 1) KMQ_GEN_LAUNCH(1);
+    else if (a.M <= 4) KMQ_GEN_LAUNCH(4);
+    else if (a.M <= 8) KMQ_GEN_LAUNCH(8);
+    else KMQ_GEN_LAUNCH(16);
+#undef KMQ_GEN_LAUNCH
+    if (slices > 1) {
+        const int64_t mn = static_cast<int64_t>(a.M) * a.N;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3(static_cast<unsigned>((mn + 255) / 256)), dim3(256), 0, s,
+                           partial, a.Y, mn, slices);
+    }
     return hipGetLastError();
 }
 
+// Slices of K for the shape-agnostic kernel: 1 unless its one-wave-per-row grid would leave more
+// than half of the 256 CUs idle on a product with long rows; then enough slices to fill them, each
+// at least 4096 elements long.
+int generic_splitk_slices(int64_t N, int64_t K, int layout) {
+    if (layout != KMQ_LAYOUT_CANONICAL) return 1;
+    const int64_t wgs = (N + 3) / 4;
+    if (wgs * 2 > 256 || K < 16384) return 1;   // measured: at K = 8192 the second launch costs more than the split saves
+    int64_t s = 256 / wgs;
+    if (s > K / 4096) s = K / 4096;
+    if (s > 64) s = 64;
+    return s < 2 ? 1 : static_cast<int>(s);
+}
+
 hipError_t launch_generic(const GemmArgs& a, hipStream_t s) {
+    const int slices = (a.workspace && a.workspace_bytes > 0) ? generic_splitk_slices(a.N, a.K, a.layout) : 1;
     switch (a.bits) {
-        case 1: return launch_generic_bits<1>(a, s);
-        case 2: return launch_generic_bits<2>(a, s);
-        case 3: return launch_generic_bits<3>(a, s);
-        default: return launch_generic_bits<4>(a, s);
+        case 1: return launch_generic_bits<1>(a, slices, s);
+        case 2: return launch_generic_bits<2>(a, slices, s);
+        case 3: return launch_generic_bits<3>(a, slices, s);
+        default: return launch_generic_bits<4>(a, slices, s);
     }
 }
 

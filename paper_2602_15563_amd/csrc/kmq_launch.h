@@ -42,7 +42,8 @@ struct Plan {
 
 Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled = false);
 
-hipError_t launch_generic(const GemmArgs& a, hipStream_t s);
+hipError_t launch_generic(const GemmArgs& a, hipStream_t s);   // split-K when a.workspace is given and the shape asks for it
+int generic_splitk_slices(int64_t N, int64_t K, int layout);
 hipError_t launch_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd, int64_t N,
                           int64_t K, int bits, int layout, hipStream_t s);
 

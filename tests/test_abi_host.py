@@ -171,3 +171,13 @@ def test_heuristic_names():
     assert kmq.kernel_name(77, 515, 2, 1) == "generic"
     assert kmq.kernel_name(4096, 4096, 3, 16, kmq.LAYOUT_TILED) == "mfma_b3"
     assert kmq.kernel_name(4096, 4000, 3, 16, kmq.LAYOUT_TILED) == "invalid"
+
+
+def test_workspace_bytes_split_k():
+    """Few long rows: the shape-agnostic kernel splits K over workgroups and needs slices * M * N floats."""
+    assert kmq.workspace_bytes(3, 65536, 2, 1) == 16 * 1 * 3 * 4 and kmq.kernel_name(3, 65536, 2, 1) == "generic_splitk"
+    assert kmq.workspace_bytes(128, 16384, 2, 2) == 4 * 2 * 128 * 4 and kmq.workspace_bytes(128, 8192, 2, 2) == 0
+    assert kmq.workspace_bytes(1, 1 << 20, 4, 16) == 64 * 16 * 1 * 4
+    assert kmq.workspace_bytes(600, 16384, 2, 2) == 0       # enough rows
+    assert kmq.workspace_bytes(8, 4100, 2, 2) == 0          # short rows
+    assert kmq.workspace_bytes(16, 65536, 2, 2, 1) == 0     # tiled layout: matrix-core kernel
