@@ -95,7 +95,10 @@ class Instances:
             synth.make_codebook(seed, matrix, N, bits, symmetric=sym)
         self.sc = synth.make_scales(seed, matrix, N, K) if self.scaled else None
         self.X = synth.make_x(seed, matrix, M, K)
+        t0 = time.perf_counter()
         self.packed = kmq.pack(self.idx, bits)
+        self.pack_ms = (time.perf_counter() - t0) * 1e3
+        self.repack_ms = None
         wpr = self.packed.shape[1]
         stored = self.packed
         if self.layout == 1:
@@ -167,8 +170,9 @@ class Instances:
         return worst
 
 
-def time_workload(inst: Instances, steps: int, warmup: int, use_graph: bool = True):
-    """Returns (seconds for `steps` calls, steps actually timed)."""
+def time_workload(inst: Instances, steps: int, warmup: int, use_graph: bool = True, per_replay: list | None = None):
+    """Returns (seconds for `steps` calls, steps actually timed).  per_replay, if given, receives the
+    microseconds per call of every graph replay (an event between replays), for the spread."""
     import torch
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
@@ -186,9 +190,13 @@ def time_workload(inst: Instances, steps: int, warmup: int, use_graph: bool = Tr
             graph.replay()                      # untimed first replay
             stream.synchronize()
             torch.cuda.synchronize()
+            marks = []
             e0.record(stream)
             for _ in range(n_replays):
                 graph.replay()
+                if per_replay is not None:
+                    marks.append(torch.cuda.Event(enable_timing=True))
+                    marks[-1].record(stream)
             e1.record(stream)
         else:
             torch.cuda.synchronize()
@@ -198,7 +206,26 @@ def time_workload(inst: Instances, steps: int, warmup: int, use_graph: bool = Tr
             e1.record(stream)
         stream.synchronize()
         torch.cuda.synchronize()
+    if use_graph and per_replay is not None:
+        prev = e0
+        for m in marks:
+            per_replay.append(prev.elapsed_time(m) * 1e3 / CALLS_PER_GRAPH)
+            prev = m
     return e0.elapsed_time(e1) * 1e-3, steps
+
+
+def clock_snapshot():
+    """Clock and performance-level state of GPU 0 as rocm-smi reports it.  Taken before this process
+    touches the GPU (so: the idle state the run starts from; device settings are read-only here)."""
+    import subprocess
+    try:
+        r = subprocess.run(["rocm-smi", "--showclocks", "--showperflevel", "--json"], capture_output=True, text=True,
+                           timeout=30)
+        line = next(ln for ln in r.stdout.splitlines() if ln.startswith("{"))
+        card = json.loads(line).get("card0", {})
+        return {k.rstrip(":").replace(" clock", ""): v.strip("()") for k, v in card.items()}
+    except Exception as e:   # the tool is absent or refused: say so rather than fail the measurement
+        return {"unavailable": type(e).__name__}
 
 
 SWEEP_LAYERS = 28
@@ -428,6 +455,8 @@ def main():
         raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); "
                          "the path shards by rows or by K across GPUs but no multi-GPU leg exists here")
 
+    clocks = clock_snapshot()
+    import numpy as np
     import torch
 
     from paper_2602_15563_amd import kmq  # noqa: F401  (fails loudly if the HIP library is missing)
@@ -442,7 +471,8 @@ def main():
         for _ in range(10):
             dst.copy_(src)
         torch.cuda.synchronize()
-    secs, steps = time_workload(inst, args.steps, args.warmup, use_graph=not args.no_graph)
+    replay_us = []
+    secs, steps = time_workload(inst, args.steps, args.warmup, use_graph=not args.no_graph, per_replay=replay_us)
     us = secs / steps * 1e6
     gbs = inst.bytes / (secs / steps) / 1e9
     out = {
@@ -450,6 +480,7 @@ def main():
                   if args.workload == HEADLINE else f"effective HBM GB/s, {args.workload}",
         "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": round(us * 1e-3, 6), "us_per_call": round(us, 3),
+        "us_per_call_se": round(float(np.std(replay_us, ddof=1) / np.sqrt(len(replay_us))), 4) if len(replay_us) > 1 else None,
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "higher_is_better": True, "scaling": "weak",
         "vs_baseline": round(gbs / PAPER_NUMBERS[args.workload][0], 3) if args.workload in PAPER_NUMBERS else None,
@@ -457,7 +488,10 @@ def main():
         "config": {"workload": args.workload, "bits": inst.bits, "N": inst.N, "K": inst.K, "batch": inst.M,
                    "kernel": inst.kernel, "layout": "tiled" if inst.layout else "canonical",
                    "rotating_instances": inst.R, "hip_graph": not args.no_graph,
-                   "algorithmic_bytes_per_call": inst.bytes, "max_err_over_A_vs_oracle": float(f"{worst:.3e}")},
+                   "algorithmic_bytes_per_call": inst.bytes, "max_err_over_A_vs_oracle": float(f"{worst:.3e}"),
+                   "clocks_before_run": clocks,
+                   "offline_host_ms": {"kmq_pack": round(inst.pack_ms, 2),
+                                       "kmq_repack": None if inst.repack_ms is None else round(inst.repack_ms, 2)}},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.workload),
                      "note": "achieved = algorithmic bytes per launch / average launch-to-launch time "
@@ -476,6 +510,12 @@ def main():
         out["config"]["speedup_vs_bf16"] = round(base["us_per_call"] / us, 2)
         out["config"]["model_max_speedup"] = round(model.speedup(16.0, inst.bits + 0.25, inst.M, nu), 2)
     out["roofline"]["read_ceiling"] = time_read_ceiling(inst, min(steps, 5000))
+    if not args.no_rotate and not args.no_graph:
+        # secondary figure, NOT the headline: the same matrix every call, so it is served from the caches
+        one = Instances(args.workload, rotate=False, layout=args.layout)
+        s1, n1 = time_workload(one, 5000, 100)
+        out["config"]["cache_resident_us_per_call"] = round(s1 / n1 * 1e6, 3)
+        del one
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(inst)
 
