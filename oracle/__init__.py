@@ -19,17 +19,17 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "kmq_oracle.cpp")
+_SRCS = [os.path.join(_HERE, "kmq_oracle.cpp"), os.path.join(_HERE, "kmq_quantize_oracle.cpp")]
 _LIB = os.path.join(_HERE, "libkmq_oracle.so")
 _lib = None
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with the host compiler (no GPU involved)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(os.path.getmtime(f) for f in _SRCS)
     if force or stale:
         cmd = ["g++", "-std=c++17", "-O2", "-fPIC", "-shared", "-Wall", "-Wextra",
-               "-o", _LIB, _SRC]
+               "-o", _LIB] + _SRCS
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -58,6 +58,14 @@ def _load():
         lib.oracle_swiglu.argtypes = [vp, vp, i64, vp]
         lib.oracle_gemm_dense.restype = ci
         lib.oracle_gemm_dense.argtypes = [vp, vp, i64, i64, i64, i64, i64, vp, vp, vp]
+        lib.oracle_quantize_round_bf16.restype = ctypes.c_uint16
+        lib.oracle_quantize_round_bf16.argtypes = [ctypes.c_double]
+        lib.oracle_lloyd.restype = ci
+        lib.oracle_lloyd.argtypes = [vp, i64, vp, ci, ci]
+        lib.oracle_quantize_rows.restype = ci
+        lib.oracle_quantize_rows.argtypes = [vp, i64, i64, ci, ci, vp, vp, vp, vp]
+        lib.oracle_quantize_blockscaled.restype = ci
+        lib.oracle_quantize_blockscaled.argtypes = [vp, i64, i64, ci, i64, ci, vp, vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -208,3 +216,50 @@ def swiglu(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
     if _load().oracle_swiglu(_p(g), _p(u), g.size, _p(y)):
         raise ValueError("bad argument")
     return y
+
+
+# ---- the quantiser that produces the formats (kmq_quantize_oracle.cpp) ----
+
+def quantize_round_bf16(c: float) -> int:
+    return int(_load().oracle_quantize_round_bf16(float(c)))
+
+
+def lloyd(v, c0, iters: int) -> np.ndarray:
+    """`iters` rounds of 1-D Lloyd on values v from sorted start centroids c0; returns the centroids (fp64)."""
+    v = _arr(v, np.float64)
+    c = np.array(c0, dtype=np.float64, copy=True)
+    if _load().oracle_lloyd(_p(v), v.size, _p(c), c.size, iters):
+        raise ValueError("oracle_lloyd: bad arguments")
+    return c
+
+
+def quantize_rows(W, bits: int, iters: int):
+    """Per-row k-means of dense bf16 weights (uint16 bit patterns, N x K).
+    Returns (idx uint8 N x K, codebook uint16 N x 2^bits, centroid fp64 N x 2^bits, sse fp64 N)."""
+    W = _arr(W, np.uint16)
+    N, K = W.shape
+    C = 1 << bits
+    idx = np.empty((N, K), np.uint8)
+    cb = np.empty((N, C), np.uint16)
+    cen = np.empty((N, C), np.float64)
+    sse = np.empty(N, np.float64)
+    if _load().oracle_quantize_rows(_p(W), N, K, bits, iters, _p(idx), _p(cb), _p(cen), _p(sse)):
+        raise ValueError("oracle_quantize_rows: bad arguments")
+    return idx, cb, cen, sse
+
+
+def quantize_blockscaled(W, bits: int, iters: int, block: int = 64):
+    """The paper's format from dense bf16 weights: absmax scale per block, tensor-wide k-means on the
+    normalised weights.  Returns (idx uint8 N x K, codebook uint16 2^bits, scales uint16 N x K/block,
+    centroid fp64 2^bits, vnorm fp64 N x K)."""
+    W = _arr(W, np.uint16)
+    N, K = W.shape
+    C = 1 << bits
+    idx = np.empty((N, K), np.uint8)
+    cb = np.empty(C, np.uint16)
+    sc = np.empty((N, K // block), np.uint16)
+    cen = np.empty(C, np.float64)
+    vn = np.empty((N, K), np.float64)
+    if _load().oracle_quantize_blockscaled(_p(W), N, K, bits, block, iters, _p(idx), _p(cb), _p(sc), _p(cen), _p(vn)):
+        raise ValueError("oracle_quantize_blockscaled: bad arguments")
+    return idx, cb, sc, cen, vn

@@ -19,7 +19,7 @@ block of such weights would get.
 
 Generator: numpy's counter-based Philox, keyed by (seed, stream) where
 stream = matrix_number * 16 + kind, kind in {0: indices, 1: codebook, 2: x,
-3: block scales, 4: tensor-wide codebook}.
+3: block scales, 4: tensor-wide codebook, 5: dense weights}.
 Normal samples are drawn in fp64, narrowed to fp32, then rounded to bf16 with
 round-to-nearest-even; codebooks are sorted after rounding.
 """
@@ -29,7 +29,7 @@ from dataclasses import dataclass
 
 import numpy as np
 
-KIND_IDX, KIND_CODEBOOK, KIND_X, KIND_SCALE, KIND_SHARED_CODEBOOK = 0, 1, 2, 3, 4
+KIND_IDX, KIND_CODEBOOK, KIND_X, KIND_SCALE, KIND_SHARED_CODEBOOK, KIND_DENSE = 0, 1, 2, 3, 4, 5
 BLOCK = 64      # elements per scale along K
 SIGMA_W = 0.02  # standard deviation of the centroid distribution
 
@@ -83,6 +83,15 @@ def make_codebook(seed: int, matrix: int, N: int, bits: int, symmetric: bool = F
 def make_x(seed: int, matrix: int, M: int, K: int) -> np.ndarray:
     """uint16 bf16 X[M][K] ~ N(0, 1)."""
     return f32_to_bf16(rng(seed, matrix, KIND_X).standard_normal(size=(M, K)).astype(np.float32))
+
+
+def make_dense_weights(seed: int, matrix: int, N: int, K: int) -> np.ndarray:
+    """uint16 bf16 W[N][K]: unquantised weights for the quantiser, N(0, SIGMA_W) with a per-row gain
+    in [0.5, 2) (rows of trained layers differ in scale, which is what per-row codebooks and block
+    scales adapt to)."""
+    g = rng(seed, matrix, KIND_DENSE)
+    gain = g.uniform(0.5, 2.0, size=(N, 1))
+    return f32_to_bf16((g.normal(0.0, SIGMA_W, size=(N, K)) * gain).astype(np.float32))
 
 
 def make_shared_codebook(seed: int, matrix: int, bits: int) -> np.ndarray:
