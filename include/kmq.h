@@ -187,6 +187,43 @@ const char* kmq_kernel_name_swiglu(int64_t N, int64_t K, int bits, int layout);
 kmq_status kmq_gemv_bf16(const uint16_t* W, const uint16_t* x, uint16_t* y, int64_t N, int64_t K,
                          void* hip_stream);
 
+/* ---- The quantiser: dense bf16 weights -> indices + codebooks ------------------------
+ * (paper Sec. 2.1 "Rounding to nearest centroids": the quantiser rounds to the nearest of
+ * 2^bits centroids obtained by 1-D k-means clustering; "Block formats"; Sec. 2.2 "Nonlinear
+ * k-means quantization".)  The paper names Lloyd's algorithm and fixes neither its start nor
+ * its stopping rule; this library's rules, the same for both calls:
+ *   - arithmetic in fp64; the centroids stay sorted ascending;
+ *   - a value belongs to cluster a = number of boundaries (c_i + c_{i+1}) / 2 that lie below it
+ *     (nearest centroid; a value on a boundary goes to the lower cluster);
+ *   - each round replaces a centroid by the mean of its members; a cluster without members
+ *     keeps its centroid; exactly `iters` >= 0 rounds are run (a converged state is a fixed point);
+ *   - start: 2^bits points evenly spaced over the range of the data,
+ *     c_i = lo + (i + 1/2) (hi - lo) / 2^bits;
+ *   - the codebook written is the centroids rounded to bf16 (nearest even) and the indices
+ *     written are nearest centroids OF THAT CODEBOOK, packed in the canonical layout.
+ * Results are deterministic run to run.  Device pointers; asynchronous on hip_stream. */
+
+/* One codebook per row, no scales (the format kmq_gemv takes): row n of Wdense (N x K bf16,
+ * row-major, 2-byte aligned) is clustered on its own, lo / hi = the row's min / max.
+ *   packed    N * kmq_words_per_row(bits, K) words out (4-byte aligned), pad bits zero
+ *   codebook  N x 2^bits bf16 out, ascending per row
+ * Errors: KMQ_ERR_NULL, KMQ_ERR_BITS, KMQ_ERR_SHAPE (N, K < 1, iters < 0), KMQ_ERR_ALIGN. */
+kmq_status kmq_quantize_rows(const uint16_t* Wdense, int64_t N, int64_t K, int bits, int iters,
+                             uint32_t* packed, uint16_t* codebook, void* hip_stream);
+
+/* The paper's format (the one kmq_gemv_blockscaled takes): scale[n][g] = the largest
+ * magnitude of block g of row n (blocks of KMQ_BLOCK elements along K; itself a bf16 value),
+ * normalised weight v = w / scale in fp64 (0 where the scale is 0), ONE clustering over all
+ * N*K normalised weights with lo = -1, hi = 1.
+ *   packed    N * K * bits / 32 words out; codebook 2^bits bf16 out; scales N x K/KMQ_BLOCK bf16 out
+ *   workspace device memory of kmq_quantize_blockscaled_workspace_bytes() bytes, 8-byte aligned
+ *             (partial sums of the clustering rounds; contents undefined before and after)
+ * K % KMQ_BLOCK != 0 -> KMQ_ERR_SHAPE; workspace NULL or too small -> KMQ_ERR_WORKSPACE. */
+size_t kmq_quantize_blockscaled_workspace_bytes(void);
+kmq_status kmq_quantize_blockscaled(const uint16_t* Wdense, int64_t N, int64_t K, int bits, int iters,
+                                    uint32_t* packed, uint16_t* codebook, uint16_t* scales,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Name of the kernel variant the launch heuristic picks for this problem
  * (static string, never NULL; "invalid" on bad arguments).  For reports. */
 const char* kmq_kernel_name(int64_t N, int64_t K, int bits, int M, int layout);

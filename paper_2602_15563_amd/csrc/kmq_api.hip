@@ -178,6 +178,34 @@ kmq_status kmq_gemv_bf16(const uint16_t* W, const uint16_t* x, uint16_t* y, int6
     return kmq::hip_status(kmq::launch_gemv_bf16(W, x, y, N, K, static_cast<hipStream_t>(hip_stream)));
 }
 
+kmq_status kmq_quantize_rows(const uint16_t* Wdense, int64_t N, int64_t K, int bits, int iters,
+                             uint32_t* packed, uint16_t* codebook, void* hip_stream) {
+    if (!Wdense || !packed || !codebook) return KMQ_ERR_NULL;
+    if (!kmq::bits_valid(bits)) return KMQ_ERR_BITS;
+    if (!kmq::dims_valid(N, K) || iters < 0 || N > 0x7FFFFFFF) return KMQ_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(Wdense) & 1) || (reinterpret_cast<uintptr_t>(codebook) & 1) ||
+        (reinterpret_cast<uintptr_t>(packed) & 3)) return KMQ_ERR_ALIGN;
+    return kmq::hip_status(kmq::launch_quantize_rows(Wdense, N, K, bits, iters, packed, codebook,
+                                                     static_cast<hipStream_t>(hip_stream)));
+}
+
+size_t kmq_quantize_blockscaled_workspace_bytes(void) { return kmq::quantize_blockscaled_workspace_bytes(); }
+
+kmq_status kmq_quantize_blockscaled(const uint16_t* Wdense, int64_t N, int64_t K, int bits, int iters,
+                                    uint32_t* packed, uint16_t* codebook, uint16_t* scales,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!Wdense || !packed || !codebook || !scales) return KMQ_ERR_NULL;
+    if (!kmq::bits_valid(bits)) return KMQ_ERR_BITS;
+    if (!kmq::dims_valid(N, K) || iters < 0 || K % KMQ_BLOCK != 0 || N * (K / KMQ_BLOCK) > (int64_t(1) << 32))
+        return KMQ_ERR_SHAPE;
+    if ((reinterpret_cast<uintptr_t>(Wdense) & 1) || (reinterpret_cast<uintptr_t>(codebook) & 1) ||
+        (reinterpret_cast<uintptr_t>(scales) & 1) || (reinterpret_cast<uintptr_t>(packed) & 3) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 7)) return KMQ_ERR_ALIGN;
+    if (!workspace || workspace_bytes < kmq::quantize_blockscaled_workspace_bytes()) return KMQ_ERR_WORKSPACE;
+    return kmq::hip_status(kmq::launch_quantize_blockscaled(Wdense, N, K, bits, iters, packed, codebook, scales,
+                                                            workspace, static_cast<hipStream_t>(hip_stream)));
+}
+
 kmq_status kmq_stream_read(const void* data, size_t bytes, void* sink, void* hip_stream) {
     if (!data) return KMQ_ERR_NULL;
     if (bytes < 16 || bytes > (size_t(1) << 40)) return KMQ_ERR_SHAPE;

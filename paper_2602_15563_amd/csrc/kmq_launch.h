@@ -58,6 +58,14 @@ hipError_t launch_blockscaled_generic(const GemmArgs& a, hipStream_t s);
 // Dense bf16 baseline; K * 2 bytes of LDS, so K <= 32768.
 hipError_t launch_gemv_bf16(const uint16_t* W, const uint16_t* x, uint16_t* y, int64_t N, int64_t K, hipStream_t s);
 
+// Quantiser (dense bf16 -> indices + codebooks): per-row codebooks, and the block-scaled format
+// whose workspace is quantize_blockscaled_workspace_bytes() bytes, 8-byte aligned.
+hipError_t launch_quantize_rows(const uint16_t* W, int64_t N, int64_t K, int bits, int iters, uint32_t* packed,
+                                uint16_t* codebook, hipStream_t s);
+size_t quantize_blockscaled_workspace_bytes();
+hipError_t launch_quantize_blockscaled(const uint16_t* W, int64_t N, int64_t K, int bits, int iters, uint32_t* packed,
+                                       uint16_t* codebook, uint16_t* scales, void* workspace, hipStream_t s);
+
 hipError_t launch_stream_read(const void* p, size_t bytes, void* sink, hipStream_t s);
 
 // Matrix-core kernel (tiled layout only).

@@ -72,6 +72,12 @@ _lib.kmq_kernel_name_swiglu.restype = ctypes.c_char_p
 _lib.kmq_kernel_name_swiglu.argtypes = [_i64, _i64, _int, _int]
 _lib.kmq_gemv_bf16.restype = ctypes.c_int32
 _lib.kmq_gemv_bf16.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
+_lib.kmq_quantize_rows.restype = ctypes.c_int32
+_lib.kmq_quantize_rows.argtypes = [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp]
+_lib.kmq_quantize_blockscaled_workspace_bytes.restype = _sz
+_lib.kmq_quantize_blockscaled_workspace_bytes.argtypes = []
+_lib.kmq_quantize_blockscaled.restype = ctypes.c_int32
+_lib.kmq_quantize_blockscaled.argtypes = [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.kmq_stream_read.restype = ctypes.c_int32
 _lib.kmq_stream_read.argtypes = [_vp, _sz, _vp, _vp]
 _lib.kmq_last_hip_error.restype = ctypes.c_char_p
@@ -219,6 +225,22 @@ def gemv_swiglu(Wgate, codebook_gate, Wup, codebook_up, x, y, N: int, K: int, bi
 def gemv_bf16(W, x, y, N: int, K: int):
     """y[N] = W x for a dense bf16 W (N x K, row-major) on torch's current stream: the unquantised baseline."""
     _check(_lib.kmq_gemv_bf16(_ptr(W), _ptr(x), _ptr(y), N, K, _stream()))
+
+
+def quantize_rows(Wdense, N: int, K: int, bits: int, iters: int, packed, codebook):
+    """Per-row k-means of dense bf16 weights -> canonical packed indices and N x 2^bits codebooks (device tensors)."""
+    _check(_lib.kmq_quantize_rows(_ptr(Wdense), N, K, bits, iters, _ptr(packed), _ptr(codebook), _stream()))
+
+
+def quantize_blockscaled_workspace_bytes() -> int:
+    return int(_lib.kmq_quantize_blockscaled_workspace_bytes())
+
+
+def quantize_blockscaled(Wdense, N: int, K: int, bits: int, iters: int, packed, codebook, scales, workspace):
+    """The paper's format from dense bf16 weights: absmax block scales, one tensor-wide codebook (device tensors)."""
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(_lib.kmq_quantize_blockscaled(_ptr(Wdense), N, K, bits, iters, _ptr(packed), _ptr(codebook), _ptr(scales),
+                                         _ptr(workspace), ws_bytes, _stream()))
 
 
 def dequant(W, codebook, Wdense, N: int, K: int, bits: int, layout: int = 0):
