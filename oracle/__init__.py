@@ -58,6 +58,8 @@ def _load():
         lib.oracle_swiglu.argtypes = [vp, vp, i64, vp]
         lib.oracle_gemm_dense.restype = ci
         lib.oracle_gemm_dense.argtypes = [vp, vp, i64, i64, i64, i64, i64, vp, vp, vp]
+        lib.oracle_rmsnorm.restype = ci
+        lib.oracle_rmsnorm.argtypes = [vp, vp, i64, ctypes.c_double, vp, vp]
         lib.oracle_quantize_round_bf16.restype = ctypes.c_uint16
         lib.oracle_quantize_round_bf16.argtypes = [ctypes.c_double]
         lib.oracle_lloyd.restype = ci
@@ -216,6 +218,34 @@ def swiglu(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
     if _load().oracle_swiglu(_p(g), _p(u), g.size, _p(y)):
         raise ValueError("bad argument")
     return y
+
+
+def rmsnorm(x, g, eps: float):
+    """(xn, r): xn = bf16(x * g) as uint16 patterns, r = 1 / sqrt(mean(x^2) + eps) in fp64; the
+    normalised activations are xn * r (the fused call applies r after the product)."""
+    x = _arr(x, np.uint16).reshape(-1)
+    g = _arr(g, np.uint16, x.shape)
+    xn = np.empty_like(x)
+    r = np.empty(1, np.float64)
+    if _load().oracle_rmsnorm(_p(x), _p(g), x.size, float(eps), _p(xn), _p(r)):
+        raise ValueError("oracle_rmsnorm: bad arguments")
+    return xn, float(r[0])
+
+
+def gemv_fused(packed, codebook, x, K: int, bits: int, norm_weight=None, eps: float = 0.0, residual=None, rows=None):
+    """The fused decoder call's definition, composed from the pieces above:
+    Y[n] = residual[n] + r * sum_k w[n][k] xn[k]; returns (Y, A) with A = |residual| + r * sum |w xn|."""
+    x = _arr(x, np.uint16).reshape(1, -1)
+    r = 1.0
+    if norm_weight is not None:
+        xn, r = rmsnorm(x[0], norm_weight, eps)
+        x = xn.reshape(1, -1)
+    Y, A, _ = gemm(packed, codebook, x, K, bits, rows=rows)
+    Y, A = Y[0] * r, A[0] * r
+    if residual is not None:
+        res = (np.ascontiguousarray(residual, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        Y, A = Y + res, A + np.abs(res)
+    return Y, A
 
 
 # ---- the quantiser that produces the formats (kmq_quantize_oracle.cpp) ----

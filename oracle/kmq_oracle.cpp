@@ -225,6 +225,24 @@ int oracle_swiglu(const double* gate, const double* up, int64_t n, double* y) {
     return 0;
 }
 
+// RMSNorm in front of a product (the normalisation of the Llama-3 decoder layers the paper
+// benchmarks, App. E "Model benchmarks"): rmsnorm(x)[k] = x[k] * g[k] / sqrt(mean(x^2) + eps).
+// The scalar factor r = 1 / sqrt(mean(x^2) + eps) commutes with the product that follows, and
+// the activations the product sees are bf16 (the method's activation type), so the fused call
+// is DEFINED as: xn[k] = bf16( x[k] * g[k] ) (a bf16 x bf16 product is exact in fp64: one
+// rounding), and r returned separately, in fp64, to multiply the product's result.
+int oracle_rmsnorm(const uint16_t* x, const uint16_t* g, int64_t K, double eps, uint16_t* xn, double* r) {
+    if (!x || !g || !xn || !r || K < 1 || !(eps >= 0.0)) return 1;
+    double ss = 0.0;
+    for (int64_t k = 0; k < K; ++k) {
+        const double v = bf16_to_double(x[k]);
+        ss += v * v;
+        xn[k] = oracle_round_bf16(v * bf16_to_double(g[k]));
+    }
+    *r = 1.0 / std::sqrt(ss / static_cast<double>(K) + eps);
+    return 0;
+}
+
 // Dense bf16 matrix times bf16 vectors, the unquantised baseline the paper compares
 // against (App. E, Table of m = 1, h = 8192, the 16-bit rows): Y[m][n] = sum_k W[n][k]*X[m][k]
 // in fp64, k ascending.  W is N x K bf16 bit patterns, row-major.

@@ -21,6 +21,9 @@ struct GemmArgs {
     const uint16_t* scales = nullptr;   // block-scaled format: N x K/64 bf16, and `codebook` is one tensor-wide table
     const uint32_t* W2 = nullptr;       // fused pair (gate, up): second matrix and its codebooks, same shape and format
     const uint16_t* codebook2 = nullptr;
+    const uint16_t* norm_w = nullptr;   // RMSNorm weights (K bf16) applied to x in front of the product, with eps
+    float eps = 0.f;
+    const uint16_t* residual = nullptr; // N bf16 added to the product
 };
 
 // Kernel variants the heuristic can pick (kmq_kernel_name reports them).
@@ -53,6 +56,7 @@ const char* rowsplit_name(int table_index);
 hipError_t launch_rowsplit(int table_index, const GemmArgs& a, hipStream_t s);
 
 hipError_t launch_pair_generic(const GemmArgs& a, hipStream_t s);
+hipError_t launch_fused_generic(const GemmArgs& a, hipStream_t s);   // batch 1, canonical layout, any shape; pair optional
 hipError_t launch_blockscaled_generic(const GemmArgs& a, hipStream_t s);
 
 // Dense bf16 baseline; K * 2 bytes of LDS, so K <= 32768.
@@ -76,6 +80,7 @@ int mfma_row_blocks(int64_t N, int64_t K, int bits);
 // Hand-scheduled table kernels (1/2/4-bit): -1 if (bits, K, layout) has none.
 int lut_find(int64_t N, int64_t K, int bits, int layout, bool scaled = false);
 const char* lut_name(int table_index);
+bool lut_has_fusions(int table_index);   // RMSNorm in front / residual behind (GemmArgs::norm_w, residual)
 hipError_t launch_lut_entry(int table_index, const GemmArgs& a, hipStream_t s);
 
 }  // namespace kmq

@@ -235,13 +235,21 @@ __device__ __forceinline__ void load_words(const uint32_t* p, uint32_t (&w)[G]) 
 // SwiGLU that consumes them: y[n] = silu(W[n] . x) * (W2[n] . x).  The kernel then walks 2N
 // "virtual" rows, row 2n from (W, codebook) and row 2n + 1 from (W2, codebook2); N is passed as
 // the virtual count, and the thread that would store a pair of outputs stores their combination.
-template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE, bool SC, bool PAIR>
+// FUSE: decoder-layer fusions around the product (paper App. E "Model benchmarks": at one bit
+// the elementwise work between the projections is a visible share of a token's time).
+//   bit 0  RMSNorm in front: the activations entering the product are bf16(x * g), and the
+//          result is multiplied by 1 / sqrt(mean(x^2) + eps), a scalar that commutes with the sum;
+//   bit 1  residual behind: y = residual + product.
+template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE, bool SC, bool PAIR, int FUSE>
 __global__ __launch_bounds__(NWK * NWR * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
                      const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int64_t N,
                      const uint16_t* __restrict__ scales,
-                     const uint32_t* __restrict__ W2, const uint16_t* __restrict__ codebook2) {
+                     const uint32_t* __restrict__ W2, const uint16_t* __restrict__ codebook2,
+                     const uint16_t* __restrict__ norm_w, float eps, const uint16_t* __restrict__ residual) {
     static_assert(!(SC && PAIR), "the fused pair is offered for the per-row-codebook format");
+    static_assert(FUSE == 0 || !SC, "decoder fusions are offered for the per-row-codebook format");
+    static_assert(!(PAIR && (FUSE & 2)), "the fused pair has no residual input");
     static_assert(BITS == 1 || BITS == 2 || BITS == 4, "3-bit fields do not align with nibbles");
     constexpr int C = 1 << BITS;
     constexpr int EL = G * 32 / BITS;              // elements per lane and row slice
@@ -278,6 +286,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         u32x4_t xs[(XSLOTS + C16 - 1) / C16 * C16];
         float part[NWK][ROWS_WG];                  // per-slice partial sums
         float sxp[NWK];                            // 1-bit: per-slice sum of x
+        float ssq[NWK * NWR];                      // RMSNorm: per-wave sum of x^2 over the chunks the wave staged
     };
     __shared__ Smem sm;
 
@@ -315,11 +324,23 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     // loads get reordered behind the index loads by instruction selection.
     static_assert(XPT == 1 || XPT == 2 || XPT == 4, "x chunks per thread");
     typedef __attribute__((ext_vector_type(4 * XPT))) uint32_t xwide_t;
+    static_assert(XCHUNKS % XPT == 0, "a thread's chunks are all inside x or all past its end");
     xwide_t xt;
+    [[maybe_unused]] xwide_t gt;                   // RMSNorm weights of the same elements
+    [[maybe_unused]] uint16_t resv[2];             // residual of the two rows this thread stores
     {
         int c = threadIdx.x * XPT;
         c = c < XCHUNKS ? c : XCHUNKS - XPT;
         xt = *reinterpret_cast<const xwide_t*>(x + c * 8);
+        if constexpr ((FUSE & 1) != 0) gt = *reinterpret_cast<const xwide_t*>(norm_w + c * 8);
+        if constexpr ((FUSE & 2) != 0) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {          // fetched with the first loads: long there when the epilogue runs
+                int64_t row = wg_row0 + (threadIdx.x * 2 + h) % ROWS_WG;
+                row = row < N ? row : N - 1;
+                resv[h] = residual[row];
+            }
+        }
     }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
@@ -371,6 +392,21 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- 3. staged activations into LDS ----------------------------------------------------------
+    if constexpr ((FUSE & 1) != 0) {
+        float ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4 * XPT; ++i) {
+            const float x0 = __uint_as_float(xt[i] << 16), x1 = __uint_as_float(xt[i] & 0xFFFF0000u);
+            const float g0 = __uint_as_float(gt[i] << 16), g1 = __uint_as_float(gt[i] & 0xFFFF0000u);
+            ss = fmaf(x0, x0, ss);
+            ss = fmaf(x1, x1, ss);
+            // a product of two bf16 values is exact in fp32: one rounding, to the bf16 activation
+            xt[i] = static_cast<uint32_t>(f32_to_bf16(x0 * g0)) | (static_cast<uint32_t>(f32_to_bf16(x1 * g1)) << 16);
+        }
+        ss = threadIdx.x * XPT < XCHUNKS ? ss : 0.f;       // threads past the end restaged a neighbour's chunks
+        ss = group_sum<64>(ss);
+        if (lane == 63) sm.ssq[wave] = ss;
+    }
 #pragma unroll
     for (int h = 0; h < XPT; ++h) {
         const int c = threadIdx.x * XPT + h;
@@ -524,6 +560,13 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     // ---- 7. epilogue: two rows per thread, one coalesced store per workgroup ----------------------
     if (threadIdx.x < ROWS_WG / 2) {
         float out[2];
+        [[maybe_unused]] float rnorm = 1.f;
+        if constexpr ((FUSE & 1) != 0) {
+            float ss = 0.f;
+#pragma unroll
+            for (int i = 0; i < NWK * NWR; ++i) ss += sm.ssq[i];
+            rnorm = 1.f / sqrtf(ss * (1.f / K) + eps);
+        }
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int rl = threadIdx.x * 2 + h;
@@ -540,6 +583,8 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
                 const float c0 = bf16_to_f32(cc & 0xFFFFu), c1 = bf16_to_f32(cc >> 16);
                 s = fmaf(c1 - c0, s, c0 * sx);
             }
+            if constexpr ((FUSE & 1) != 0) s *= rnorm;
+            if constexpr ((FUSE & 2) != 0) s += bf16_to_f32(resv[h]);
             out[h] = s;
         }
         const int64_t r2 = wg_row0 + threadIdx.x * 2;
@@ -577,14 +622,30 @@ static void launch_lut(const GemmArgs& a, hipStream_t s) {
         if (a.W2) {                                           // fused pair: 2N virtual rows
             const int64_t nv = 2 * a.N;
             const dim3 grid(static_cast<unsigned>((nv + rows_wg - 1) / rows_wg));
-            hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, true>), grid, block, 0, s,
-                               a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2);
+            if constexpr (BITS == 1) {
+                if (a.norm_w) {
+                    hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, true, 1>), grid, block, 0, s,
+                                       a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, a.norm_w, a.eps, nullptr);
+                    return;
+                }
+            }
+            hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, true, 0>), grid, block, 0, s,
+                               a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, nullptr, 0.f, nullptr);
             return;
         }
     }
     const dim3 grid(static_cast<unsigned>((a.N + rows_wg - 1) / rows_wg));
-    hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, SC, false>), grid, block, 0, s,
-                       a.W, a.codebook, a.X, a.Y, a.N, a.scales, nullptr, nullptr);
+    if constexpr (BITS == 1 && !SC) {                         // decoder fusions: the 1-bit shapes carry them
+#define KMQ_LUT_FUSED(F) \
+        hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, false, F>), grid, block, 0, s, \
+                           a.W, a.codebook, a.X, a.Y, a.N, a.scales, nullptr, nullptr, a.norm_w, a.eps, a.residual)
+        if (a.norm_w && a.residual) { KMQ_LUT_FUSED(3); return; }
+        if (a.norm_w) { KMQ_LUT_FUSED(1); return; }
+        if (a.residual) { KMQ_LUT_FUSED(2); return; }
+#undef KMQ_LUT_FUSED
+    }
+    hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, SC, false, 0>), grid, block, 0, s,
+                       a.W, a.codebook, a.X, a.Y, a.N, a.scales, nullptr, nullptr, nullptr, 0.f, nullptr);
 }
 
 #define KMQ_LUT(BITS, G, LPR, NWK, NWR, RS, WPE) \
@@ -657,6 +718,7 @@ int lut_find(int64_t N, int64_t K, int bits, int layout, bool scaled) {
 }
 
 const char* lut_name(int i) { return kLut[i].name; }
+bool lut_has_fusions(int i) { return kLut[i].bits == 1 && !kLut[i].scaled; }
 
 hipError_t launch_lut_entry(int i, const GemmArgs& a, hipStream_t s) {
     kLut[i].launch(a, s);

@@ -72,6 +72,12 @@ _lib.kmq_kernel_name_swiglu.restype = ctypes.c_char_p
 _lib.kmq_kernel_name_swiglu.argtypes = [_i64, _i64, _int, _int]
 _lib.kmq_gemv_bf16.restype = ctypes.c_int32
 _lib.kmq_gemv_bf16.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
+_lib.kmq_gemv_fused.restype = ctypes.c_int32
+_lib.kmq_gemv_fused.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _i64, _i64, _int, _int, _vp]
+_lib.kmq_gemv_swiglu_rmsnorm.restype = ctypes.c_int32
+_lib.kmq_gemv_swiglu_rmsnorm.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _i64, _i64, _int, _int, _vp]
+_lib.kmq_kernel_name_fused.restype = ctypes.c_char_p
+_lib.kmq_kernel_name_fused.argtypes = [_i64, _i64, _int, _int, _int]
 _lib.kmq_quantize_rows.restype = ctypes.c_int32
 _lib.kmq_quantize_rows.argtypes = [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp]
 _lib.kmq_quantize_blockscaled_workspace_bytes.restype = _sz
@@ -225,6 +231,24 @@ def gemv_swiglu(Wgate, codebook_gate, Wup, codebook_up, x, y, N: int, K: int, bi
 def gemv_bf16(W, x, y, N: int, K: int):
     """y[N] = W x for a dense bf16 W (N x K, row-major) on torch's current stream: the unquantised baseline."""
     _check(_lib.kmq_gemv_bf16(_ptr(W), _ptr(x), _ptr(y), N, K, _stream()))
+
+
+def gemv_fused(W, codebook, x, y, N: int, K: int, bits: int, norm_weight=None, eps: float = 0.0, residual=None,
+               layout: int = 0):
+    """y = residual + W rmsnorm(x; norm_weight, eps) on torch's current stream; both fusions optional."""
+    _check(_lib.kmq_gemv_fused(_ptr(W), _ptr(codebook), _ptr(x), _ptr(norm_weight), eps, _ptr(residual), _ptr(y),
+                               N, K, bits, layout, _stream()))
+
+
+def gemv_swiglu_rmsnorm(Wgate, cb_gate, Wup, cb_up, x, norm_weight, eps: float, y, N: int, K: int, bits: int,
+                        layout: int = 0):
+    """y = silu(Wgate xn) * (Wup xn), xn = rmsnorm(x; norm_weight, eps), one launch."""
+    _check(_lib.kmq_gemv_swiglu_rmsnorm(_ptr(Wgate), _ptr(cb_gate), _ptr(Wup), _ptr(cb_up), _ptr(x), _ptr(norm_weight),
+                                        eps, _ptr(y), N, K, bits, layout, _stream()))
+
+
+def kernel_name_fused(N: int, K: int, bits: int, layout: int = 0, pair: bool = False) -> str:
+    return _lib.kmq_kernel_name_fused(N, K, bits, layout, 1 if pair else 0).decode()
 
 
 def quantize_rows(Wdense, N: int, K: int, bits: int, iters: int, packed, codebook):

@@ -19,7 +19,8 @@ block of such weights would get.
 
 Generator: numpy's counter-based Philox, keyed by (seed, stream) where
 stream = matrix_number * 16 + kind, kind in {0: indices, 1: codebook, 2: x,
-3: block scales, 4: tensor-wide codebook, 5: dense weights}.
+3: block scales, 4: tensor-wide codebook, 5: dense weights, 6: RMSNorm gains,
+7: residual stream}.
 Normal samples are drawn in fp64, narrowed to fp32, then rounded to bf16 with
 round-to-nearest-even; codebooks are sorted after rounding.
 """
@@ -29,7 +30,7 @@ from dataclasses import dataclass
 
 import numpy as np
 
-KIND_IDX, KIND_CODEBOOK, KIND_X, KIND_SCALE, KIND_SHARED_CODEBOOK, KIND_DENSE = 0, 1, 2, 3, 4, 5
+KIND_IDX, KIND_CODEBOOK, KIND_X, KIND_SCALE, KIND_SHARED_CODEBOOK, KIND_DENSE, KIND_NORM, KIND_RESIDUAL = range(8)
 BLOCK = 64      # elements per scale along K
 SIGMA_W = 0.02  # standard deviation of the centroid distribution
 
@@ -92,6 +93,16 @@ def make_dense_weights(seed: int, matrix: int, N: int, K: int) -> np.ndarray:
     g = rng(seed, matrix, KIND_DENSE)
     gain = g.uniform(0.5, 2.0, size=(N, 1))
     return f32_to_bf16((g.normal(0.0, SIGMA_W, size=(N, K)) * gain).astype(np.float32))
+
+
+def make_norm_weight(seed: int, matrix: int, K: int, gain: float = 1.0) -> np.ndarray:
+    """uint16 bf16 g[K]: RMSNorm gains, gain * (1 + 0.2 z), z ~ N(0, 1) (trained gains sit around a common level)."""
+    return f32_to_bf16((gain * (1.0 + 0.2 * rng(seed, matrix, KIND_NORM).standard_normal(K))).astype(np.float32))
+
+
+def make_residual(seed: int, matrix: int, N: int) -> np.ndarray:
+    """uint16 bf16 residual[N] ~ N(0, 1): the hidden state a projection's output is added to."""
+    return f32_to_bf16(rng(seed, matrix, KIND_RESIDUAL).standard_normal(N).astype(np.float32))
 
 
 def make_shared_codebook(seed: int, matrix: int, bits: int) -> np.ndarray:

@@ -1,0 +1,156 @@
+"""GPU parity of the decoder-layer fusions (RMSNorm in front of a product, residual behind it, and the
+RMSNorm + gate / up / SwiGLU call) against the oracle's definition, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_15563_amd import synth
+
+pytestmark = pytest.mark.gpu
+EPS = 1e-5
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    from tests import gpu_util
+    return gpu_util
+
+
+def _inputs(seed, bits, N, K):
+    idx = synth.make_indices(seed, 0, N, K, bits)
+    cb = synth.make_codebook(seed, 0, N, bits, symmetric=(bits == 1))
+    x = synth.make_x(seed, 0, 1, K)[0]
+    return idx, cb, x, synth.make_norm_weight(seed, 0, K), synth.make_residual(seed, 0, N)
+
+
+def _run(gpu, idx, cb, x, bits, g=None, res=None, alias=False):
+    from paper_2602_15563_amd import kmq
+    N, K = idx.shape
+    y = gpu.dev(res) if alias else torch.full((N,), 0x7FC1, dtype=torch.int16, device="cuda")
+    kmq.gemv_fused(gpu.dev(kmq.pack(idx, bits)), gpu.dev(cb), gpu.dev(x), y, N, K, bits,
+                   norm_weight=None if g is None else gpu.dev(g), eps=EPS,
+                   residual=None if res is None else (y if alias else gpu.dev(res)))
+    torch.cuda.synchronize()
+    return synth.bf16_to_f64(gpu.host_u16(y))
+
+
+def _check(gpu, yg, idx, cb, x, bits, g, res, label):
+    N, K = idx.shape
+    Y, A = oracle.gemv_fused(oracle.pack(idx, bits), cb, x, K, bits, norm_weight=g, eps=EPS, residual=res)
+    err = np.abs(yg - Y)
+    # fp32 sums in any order, the scalar in fp32 (a few roundings), one bf16 rounding of the result
+    bound = gpu.arithmetic_bound(A, Y, K + 16)
+    bad = err > bound
+    if K >= 512:
+        bad |= err > gpu.TOL * A + 2.0 ** -8 * np.abs(Y)
+    assert not bad.any(), f"{label}: {int(bad.sum())} beyond tolerance, worst err/A {np.max(err / np.maximum(A, 1e-300)):.3e}"
+
+
+MODES = [("norm", True, False), ("res", False, True), ("both", True, True), ("plain", False, False)]
+LUT_1BIT = [(2048, 64), (2048, 333), (3072, 100), (3072, 3072), (4096, 50), (8192, 96), (8192, 3072)]
+
+
+@pytest.mark.parametrize("mode,use_g,use_r", MODES)
+@pytest.mark.parametrize("K,N", LUT_1BIT)
+def test_fused_on_the_one_bit_table_kernels(gpu, K, N, mode, use_g, use_r):
+    from paper_2602_15563_amd import kmq
+    assert kmq.kernel_name_fused(N, K, 1).startswith("lut_b1")
+    idx, cb, x, g, res = _inputs(500 + K // 64 + N, 1, N, K)
+    print(f"fused {mode} b1 {N}x{K}", flush=True)
+    yg = _run(gpu, idx, cb, x, 1, g if use_g else None, res if use_r else None)
+    _check(gpu, yg, idx, cb, x, 1, g if use_g else None, res if use_r else None, f"{mode} b1 {N}x{K}")
+
+
+@pytest.mark.parametrize("mode,use_g,use_r", MODES)
+@pytest.mark.parametrize("bits,N,K", [(2, 40, 4096), (3, 33, 515), (4, 100, 33), (1, 7, 1), (1, 9, 1000), (4, 64, 14336)])
+def test_fused_any_shape(gpu, bits, N, K, mode, use_g, use_r):
+    from paper_2602_15563_amd import kmq
+    assert kmq.kernel_name_fused(N, K, bits) == "fused_generic"
+    idx, cb, x, g, res = _inputs(600 + bits + N, bits, N, K)
+    yg = _run(gpu, idx, cb, x, bits, g if use_g else None, res if use_r else None)
+    _check(gpu, yg, idx, cb, x, bits, g if use_g else None, res if use_r else None, f"{mode} b{bits} {N}x{K}")
+
+
+def test_plain_mode_equals_kmq_gemv_bit_for_bit(gpu):
+    for K, N in [(3072, 200), (8192, 64)]:
+        idx, cb, x, _, _ = _inputs(700 + N, 1, N, K)
+        from paper_2602_15563_amd import kmq
+        a = _run(gpu, idx, cb, x, 1)
+        b = synth.bf16_to_f64(gpu.run_gemm(gpu.dev(kmq.pack(idx, 1)), gpu.dev(cb), x, N, K, 1)[0])
+        assert np.array_equal(a, b)
+
+
+def test_residual_may_alias_the_output(gpu):
+    idx, cb, x, g, res = _inputs(710, 1, 3072, 3072)
+    a = _run(gpu, idx, cb, x, 1, g, res)
+    b = _run(gpu, idx, cb, x, 1, g, res, alias=True)
+    assert np.array_equal(a, b)
+
+
+def test_unit_weights_reduce_to_a_scaled_product(gpu):
+    """g = 1: the activations pass unchanged and the result is the plain product times r."""
+    N, K = 128, 3072
+    idx, cb, x, _, _ = _inputs(720, 1, N, K)
+    one = synth.f32_to_bf16(np.ones(K, np.float32))
+    yg = _run(gpu, idx, cb, x, 1, one, None)
+    Y0, A0, _ = oracle.gemm(oracle.pack(idx, 1), cb, x.reshape(1, -1), K, 1)
+    xd = synth.bf16_to_f64(x)
+    r = 1.0 / np.sqrt(np.mean(xd * xd) + EPS)
+    assert np.all(np.abs(yg - Y0[0] * r) <= gpu.arithmetic_bound(A0[0] * r, Y0[0] * r, K + 16))
+
+
+def _swiglu_norm(gpu, bits, N, K, seed):
+    from paper_2602_15563_amd import kmq
+    ig, iu = synth.make_indices(seed, 0, N, K, bits), synth.make_indices(seed, 1, N, K, bits)
+    sym = bits == 1
+    cg, cu = synth.make_codebook(seed, 0, N, bits, symmetric=sym), synth.make_codebook(seed, 1, N, bits, symmetric=sym)
+    x = synth.f32_to_bf16(synth.bf16_to_f32(synth.make_x(seed, 0, 1, K)[0]) * np.float32(3.0))
+    # gains large enough that the gate spans the non-linear range of silu after normalisation
+    g = synth.make_norm_weight(seed, 0, K, gain=40.0 / np.sqrt(K))
+    y = torch.full((N,), 0x7FC1, dtype=torch.int16, device="cuda")
+    kmq.gemv_swiglu_rmsnorm(gpu.dev(kmq.pack(ig, bits)), gpu.dev(cg), gpu.dev(kmq.pack(iu, bits)), gpu.dev(cu), gpu.dev(x),
+                            gpu.dev(g), EPS, y, N, K, bits)
+    torch.cuda.synchronize()
+    yg = synth.bf16_to_f64(gpu.host_u16(y))
+    G, Ag = oracle.gemv_fused(oracle.pack(ig, bits), cg, x, K, bits, norm_weight=g, eps=EPS)
+    U, Au = oracle.gemv_fused(oracle.pack(iu, bits), cu, x, K, bits, norm_weight=g, eps=EPS)
+    want = oracle.swiglu(G, U)
+    dg, du = (K + 24) * 2.0 ** -23 * Ag, (K + 24) * 2.0 ** -23 * Au
+    silu = oracle.swiglu(G, np.ones_like(G))
+    inner = 1.1 * np.abs(U) * dg + np.abs(silu) * du + 1.1 * dg * du + 8 * 2.0 ** -23 * np.abs(want)
+    bound = inner + 2.0 ** -8 * (np.abs(want) + inner)
+    err = np.abs(yg - want)
+    assert np.all(err <= bound), f"b{bits} {N}x{K}: max err/bound {np.max(err / np.maximum(bound, 1e-300)):.2f}"
+
+
+@pytest.mark.parametrize("K,N", [(2048, 40), (3072, 64), (3072, 8192), (4096, 333), (8192, 17)])
+def test_swiglu_rmsnorm_on_the_one_bit_table_kernels(gpu, K, N):
+    from paper_2602_15563_amd import kmq
+    assert kmq.kernel_name_fused(N, K, 1, pair=True).startswith("lut_b1")
+    _swiglu_norm(gpu, 1, N, K, 800 + N)
+
+
+@pytest.mark.parametrize("bits,N,K", [(2, 40, 4096), (3, 33, 515), (4, 20, 33), (1, 9, 1000)])
+def test_swiglu_rmsnorm_any_shape(gpu, bits, N, K):
+    from paper_2602_15563_amd import kmq
+    assert kmq.kernel_name_fused(N, K, bits, pair=True) == "fused_generic"
+    _swiglu_norm(gpu, bits, N, K, 900 + N)
+
+
+def test_errors(gpu):
+    from paper_2602_15563_amd import kmq
+    idx, cb, x, g, res = _inputs(950, 2, 8, 64)
+    W, cbd, xd, gd = gpu.dev(kmq.pack(idx, 2)), gpu.dev(cb), gpu.dev(x), gpu.dev(g)
+    y = torch.zeros(8, dtype=torch.int16, device="cuda")
+    for call, status in [
+        (lambda: kmq.gemv_fused(W, cbd, xd, y, 8, 64, 2, layout=1), 7),
+        (lambda: kmq.gemv_fused(W, cbd, xd, y, 8, 64, 5), 2),
+        (lambda: kmq.gemv_fused(W, cbd, xd, y, 8, 64, 2, norm_weight=gd, eps=-1.0), 3),
+        (lambda: kmq.gemv_fused(W, cbd, None, y, 8, 64, 2), 1),
+        (lambda: kmq.gemv_swiglu_rmsnorm(W, cbd, W, cbd, xd, None, EPS, y, 8, 64, 2), 1),
+        (lambda: kmq.gemv_fused(W, cbd, xd, y, 8, 64, 2, norm_weight=gd[1:]), 4),
+    ]:
+        with pytest.raises(kmq.KmqError) as e:
+            call()
+        assert e.value.status == status

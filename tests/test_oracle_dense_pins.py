@@ -1,6 +1,7 @@
 """Pins for the oracle's dense bf16 product (the unquantised baseline of the paper's
-App. E micro-benchmark table).  CPU only."""
+App. E micro-benchmark table), SwiGLU, and RMSNorm / residual around a product.  CPU only."""
 import numpy as np
+import pytest
 
 import oracle
 from paper_2602_15563_amd import synth
@@ -60,3 +61,62 @@ def test_swiglu_pins():
     assert abs(y[7] / 1e-6 - 0.5) < 1e-6
     assert np.array_equal(oracle.swiglu(t, -2.5 * one), -2.5 * y)
     assert abs(oracle.swiglu(np.array([2.0]), np.array([3.0]))[0] - 2.0 / (1.0 + np.exp(-2.0)) * 3.0) < 1e-15
+
+
+# ---- RMSNorm in front of a product, residual behind (the fused decoder call's definition) ----
+
+def test_rmsnorm_against_torch_and_numpy():
+    import torch
+    g0 = np.random.default_rng(21)
+    for K, eps in [(64, 1e-5), (3072, 1e-6), (515, 0.0), (8192, 1e-5)]:
+        x = synth.make_x(21, K, 1, K)[0]
+        g = synth.f32_to_bf16((1.0 + 0.1 * g0.standard_normal(K)).astype(np.float32))
+        xn, r = oracle.rmsnorm(x, g, eps)
+        xd, gd = synth.bf16_to_f64(x), synth.bf16_to_f64(g)
+        # the scalar: torch's rms_norm of x with unit weights is x * r
+        ref = torch.nn.functional.rms_norm(torch.from_numpy(xd), (K,), eps=eps).numpy()
+        nz = xd != 0
+        np.testing.assert_allclose(ref[nz] / xd[nz], r, rtol=1e-12)
+        assert abs(r - 1.0 / np.sqrt(np.mean(xd * xd) + eps)) <= 1e-14 * r
+        # the activations: one rounding of the exact product (fp32 holds a bf16 x bf16 product exactly)
+        assert np.array_equal(xn, synth.f32_to_bf16(synth.bf16_to_f32(x) * synth.bf16_to_f32(g)))
+        # together: the library's weighted rms_norm to bf16 rounding of the activations
+        full = torch.nn.functional.rms_norm(torch.from_numpy(xd), (K,), weight=torch.from_numpy(gd), eps=eps).numpy()
+        np.testing.assert_allclose(synth.bf16_to_f64(xn) * r, full, rtol=2.0 ** -8, atol=1e-30)
+
+
+def test_rmsnorm_closed_forms():
+    K = 128
+    c = synth.f32_to_bf16(np.full(K, 0.75, np.float32))
+    one = synth.f32_to_bf16(np.ones(K, np.float32))
+    xn, r = oracle.rmsnorm(c, one, 0.25)
+    assert np.array_equal(xn, c) and r == 1.0 / np.sqrt(0.75 ** 2 + 0.25)
+    x = synth.make_x(22, 0, 1, K)[0]
+    x2 = synth.f32_to_bf16(2.0 * synth.bf16_to_f32(x))                    # exact doubling
+    (_, r1), (_, r2) = oracle.rmsnorm(x, one, 0.0), oracle.rmsnorm(x2, one, 0.0)
+    assert abs(r1 - 2.0 * r2) <= 1e-15 * r1                                 # scale invariance without eps
+    with pytest.raises(ValueError):
+        oracle.rmsnorm(x, one, -1.0)
+
+
+def test_fused_call_is_the_product_with_the_scalar_and_the_residual():
+    bits, N, K = 2, 24, 640
+    idx = synth.make_indices(23, 0, N, K, bits)
+    cb = synth.make_codebook(23, 0, N, bits)
+    x = synth.make_x(23, 0, 1, K)
+    g = synth.f32_to_bf16((1.0 + 0.2 * np.random.default_rng(23).standard_normal(K)).astype(np.float32))
+    res = synth.make_x(23, 1, 1, N)[0]
+    packed = oracle.pack(idx, bits)
+    Y0, A0, _ = oracle.gemm(packed, cb, x, K, bits)
+    Yp, Ap = oracle.gemv_fused(packed, cb, x, K, bits)
+    assert np.array_equal(Yp, Y0[0]) and np.array_equal(Ap, A0[0])          # no fusion: the plain product
+    Yr, _ = oracle.gemv_fused(packed, cb, x, K, bits, residual=res)
+    assert np.array_equal(Yr, Y0[0] + synth.bf16_to_f64(res))
+    # dense restatement: W_hat (xn * r) + res, with W_hat from the uint8 indices
+    Yf, Af = oracle.gemv_fused(packed, cb, x, K, bits, norm_weight=g, eps=1e-5, residual=res)
+    W = np.take_along_axis(synth.bf16_to_f64(cb), idx.astype(np.int64), axis=1)
+    xd = synth.bf16_to_f64(x[0])
+    r = 1.0 / np.sqrt(np.mean(xd * xd) + 1e-5)
+    xn = synth.bf16_to_f64(synth.f32_to_bf16(synth.bf16_to_f32(x[0]) * synth.bf16_to_f32(g)))
+    np.testing.assert_allclose(Yf, W @ xn * r + synth.bf16_to_f64(res), rtol=0, atol=1e-12 * Af.max())
+    np.testing.assert_allclose(Af, np.abs(W * xn[None, :]).sum(axis=1) * r + np.abs(synth.bf16_to_f64(res)), rtol=1e-12)
