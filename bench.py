@@ -233,7 +233,7 @@ SWEEP_SHAPES = ["cfg4_qkv_b1_9216x3072_m1", "cfg4_o_b1_3072x3072_m1", "cfg4_gate
                 "cfg4_up_b1_8192x3072_m1", "cfg4_down_b1_3072x8192_m1"]         # gate and up are two matrices
 
 
-def run_sweep(M: int, replays: int, fuse_gate_up: bool = False):
+def run_sweep(M: int, replays: int, fuse: str = ""):
     """The 1-bit decoder-layer sweep of the fifth contract configuration: 28 layers x
     (fused QKV, O, gate, up, down), every matrix with its own weights (396 MB of indices, so
     each pass streams from HBM), captured as one HIP graph of 140 calls on one stream."""
@@ -245,6 +245,50 @@ def run_sweep(M: int, replays: int, fuse_gate_up: bool = False):
     insts = [Instances(n, R=SWEEP_LAYERS, M=M) for n in SWEEP_SHAPES]
     worst = max(it.check() for it in insts)
     gate, up = insts[2], insts[3]
+    fuse_gate_up = fuse == "gate_up"
+    if fuse == "decoder":
+        # the whole layer's elementwise work folded into four launches (attention itself is not part of
+        # this path): RMSNorm -> QKV; O + residual; RMSNorm -> gate, up -> SwiGLU; down + residual
+        from paper_2602_15563_amd import kmq
+        assert M == 1
+        qkv, o, down = insts[0], insts[1], insts[4]
+        eps = 1e-5
+        gn_host = [synth.make_norm_weight(4, 100 + l, qkv.K) for l in range(2)]
+        res_host = synth.make_residual(4, 100, o.N)
+        gn1 = [_dev(synth.make_norm_weight(4, 100 + 2 * l, qkv.K)) for l in range(SWEEP_LAYERS)]
+        gn2 = [_dev(synth.make_norm_weight(4, 101 + 2 * l, qkv.K)) for l in range(SWEEP_LAYERS)]
+        hres = [_dev(synth.make_residual(4, 100 + l, o.N)) for l in range(SWEEP_LAYERS)]
+        ysw = [torch.zeros(gate.N, dtype=torch.int16, device="cuda") for _ in range(SWEEP_LAYERS)]
+
+        def decoder_layer(l):
+            kmq.gemv_fused(qkv.W[l], qkv.C[l], qkv.Xd[l], qkv.Y[l], qkv.N, qkv.K, qkv.bits, norm_weight=gn1[l], eps=eps)
+            kmq.gemv_fused(o.W[l], o.C[l], o.Xd[l], o.Y[l], o.N, o.K, o.bits, residual=hres[l])
+            kmq.gemv_swiglu_rmsnorm(gate.W[l], gate.C[l], up.W[l], up.C[l], gate.Xd[l], gn2[l], eps, ysw[l],
+                                    gate.N, gate.K, gate.bits)
+            kmq.gemv_fused(down.W[l], down.C[l], down.Xd[l], down.Y[l], down.N, down.K, down.bits, residual=hres[l])
+        decoder_layer(0)
+        torch.cuda.synchronize()
+
+        def close(yg, Y, A, what):
+            if not np.all(np.abs(yg - Y) <= 2e-3 * A + 2.0 ** -8 * np.abs(Y)):
+                raise SystemExit(f"bench: fused decoder call ({what}) does not match the oracle")
+        for it, g_, r_ in ((qkv, gn_host[0], None), (o, None, res_host), (down, None, res_host)):
+            yg = synth.bf16_to_f64(it.Y[0].cpu().numpy().view(np.uint16)).reshape(-1)
+            for n0 in (0, it.N // 2, it.N - 64):
+                Y, A = oracle.gemv_fused(it.packed, it.cb, it.X, it.K, it.bits, norm_weight=g_, eps=eps, residual=r_,
+                                         rows=(n0, n0 + 64))
+                close(yg[n0:n0 + 64], Y[n0:n0 + 64], A[n0:n0 + 64], it.name)
+        yg = synth.bf16_to_f64(ysw[0].cpu().numpy().view(np.uint16))
+        for n0 in (0, gate.N // 2, gate.N - 64):
+            G, Ag = oracle.gemv_fused(gate.packed, gate.cb, gate.X, gate.K, gate.bits, norm_weight=gn_host[1], eps=eps,
+                                      rows=(n0, n0 + 64))
+            U, Au = oracle.gemv_fused(up.packed, up.cb, gate.X, gate.K, gate.bits, norm_weight=gn_host[1], eps=eps,
+                                      rows=(n0, n0 + 64))
+            G, Ag, U, Au = G[n0:n0 + 64], Ag[n0:n0 + 64], U[n0:n0 + 64], Au[n0:n0 + 64]
+            want = oracle.swiglu(G, U)
+            tol = 2e-3 * (1.1 * np.abs(U) * Ag + np.abs(oracle.swiglu(G, np.ones_like(G))) * Au) + 2.0 ** -8 * np.abs(want)
+            if not np.all(np.abs(yg[n0:n0 + 64] - want) <= tol):
+                raise SystemExit("bench: the fused RMSNorm / gate / up / SwiGLU call does not match the oracle")
     if fuse_gate_up:
         # gate and up in one launch with the SwiGLU that consumes them (batch 1, canonical layout)
         from paper_2602_15563_amd import kmq
@@ -289,7 +333,9 @@ def run_sweep(M: int, replays: int, fuse_gate_up: bool = False):
     with torch.cuda.stream(stream):
         def one_pass():
             for layer in range(SWEEP_LAYERS):
-                if fuse_gate_up:
+                if fuse == "decoder":
+                    decoder_layer(layer)
+                elif fuse_gate_up:
                     insts[0].call(layer)
                     insts[1].call(layer)
                     fused_call(layer)
@@ -312,8 +358,10 @@ def run_sweep(M: int, replays: int, fuse_gate_up: bool = False):
         stream.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / replays
     nbytes = SWEEP_LAYERS * sum(it.bytes for it in insts)
-    calls = SWEEP_LAYERS * (len(insts) - (1 if fuse_gate_up else 0))
-    return {"workload": f"cfg4_sweep_28layers_m{M}" + ("_fused_gate_up_swiglu" if fuse_gate_up else ""), "us_per_sweep": round(us, 2), "us_per_call": round(us / calls, 3),
+    calls = SWEEP_LAYERS * (len(insts) - (1 if fuse else 0))
+    suffix = {"": "", "gate_up": "_fused_gate_up_swiglu", "decoder": "_fused_rmsnorm_swiglu_residual"}[fuse]
+    return {"workload": f"cfg4_sweep_28layers_m{M}" + suffix, "us_per_sweep": round(us, 2), "us_per_call": round(us / calls, 3),
+            "passes_per_s": round(1e6 / us, 1),
             "calls": calls, "GBps": round(nbytes / us * 1e-3, 1), "pct_peak": round(100 * nbytes / us * 1e-3 / HBM_PEAK_GBS, 2),
             "bytes": nbytes, "kernels": sorted({it.kernel for it in insts}),
             "layout": "tiled" if insts[0].layout else "canonical", "max_err_over_A": float(f"{worst:.3e}")}
@@ -539,8 +587,8 @@ def main():
 
     if args.sweep:
         rows = []
-        for M, fused in ((1, False), (1, True), (4, False), (16, False)):
-            rows.append(run_sweep(M, 200, fuse_gate_up=fused))
+        for M, fused in ((1, ""), (1, "gate_up"), (1, "decoder"), (4, ""), (16, "")):
+            rows.append(run_sweep(M, 200, fuse=fused))
             print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
             torch.cuda.empty_cache()
         os.makedirs(args.out, exist_ok=True)

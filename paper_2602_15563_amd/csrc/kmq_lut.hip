@@ -398,10 +398,12 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         for (int i = 0; i < 4 * XPT; ++i) {
             const float x0 = __uint_as_float(xt[i] << 16), x1 = __uint_as_float(xt[i] & 0xFFFF0000u);
             const float g0 = __uint_as_float(gt[i] << 16), g1 = __uint_as_float(gt[i] & 0xFFFF0000u);
-            ss = fmaf(x0, x0, ss);
-            ss = fmaf(x1, x1, ss);
-            // a product of two bf16 values is exact in fp32: one rounding, to the bf16 activation
-            xt[i] = static_cast<uint32_t>(f32_to_bf16(x0 * g0)) | (static_cast<uint32_t>(f32_to_bf16(x1 * g1)) << 16);
+            ss = dot2_bf16(xt[i], xt[i], ss);
+            // a product of two bf16 values is exact in fp32: one rounding (to nearest even, the
+            // hardware's packed conversion), to the bf16 activation
+            typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+            const f32x2_t p = {x0 * g0, x1 * g1};
+            xt[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2_t));
         }
         ss = threadIdx.x * XPT < XCHUNKS ? ss : 0.f;       // threads past the end restaged a neighbour's chunks
         ss = group_sum<64>(ss);
