@@ -218,6 +218,9 @@ def clock_snapshot():
     """Clock and performance-level state of GPU 0 as rocm-smi reports it.  Taken before this process
     touches the GPU (so: the idle state the run starts from; device settings are read-only here)."""
     import subprocess
+    # under a profiler the GPU runtime is already up when this process starts: start no child then
+    if "rocprof" in os.environ.get("LD_PRELOAD", "").lower() or any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ):
+        return {"unavailable": "profiler attached"}
     try:
         r = subprocess.run(["rocm-smi", "--showclocks", "--showperflevel", "--json"], capture_output=True, text=True,
                            timeout=30)
@@ -489,6 +492,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch directly instead of replaying a HIP graph")
     ap.add_argument("--no-rotate", action="store_true", help="reuse one instance (cache-resident, NOT the headline)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-cache-resident", action="store_true",
+                    help="skip the secondary same-matrix-every-call timing (keeps a kernel trace to the cold calls)")
     ap.add_argument("--layout", type=int, default=None, choices=(0, 1),
                     help="0 canonical, 1 tiled (default: canonical for batch 1, tiled for batch > 1)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -558,7 +563,7 @@ def main():
         out["config"]["speedup_vs_bf16"] = round(base["us_per_call"] / us, 2)
         out["config"]["model_max_speedup"] = round(model.speedup(16.0, inst.bits + 0.25, inst.M, nu), 2)
     out["roofline"]["read_ceiling"] = time_read_ceiling(inst, min(steps, 5000))
-    if not args.no_rotate and not args.no_graph:
+    if not args.no_rotate and not args.no_graph and not args.no_cache_resident:
         # secondary figure, NOT the headline: the same matrix every call, so it is served from the caches
         one = Instances(args.workload, rotate=False, layout=args.layout)
         s1, n1 = time_workload(one, 5000, 100)
