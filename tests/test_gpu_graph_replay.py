@@ -70,3 +70,61 @@ def test_graph_replays_match_eager(gpu):
             assert torch.equal(y, w), f"replay {replay}, call {i}"
         for y, w in zip(eager, want):
             assert torch.equal(y, w)
+
+
+def test_graph_replays_of_the_multi_kernel_and_fused_calls(gpu):
+    """The calls that launch more than one kernel (split-K with its workspace, the per-tensor quantiser)
+    and the decoder fusions, captured together; every replay against the eager result."""
+    from paper_2602_15563_amd import kmq
+    dev = gpu.dev
+    N1, K1 = 3072, 3072                         # fused RMSNorm + residual on a 1-bit table kernel
+    idx1, cb1 = synth.make_indices(11, 0, N1, K1, 1), synth.make_codebook(11, 0, N1, 1, symmetric=True)
+    x1, g1, r1 = synth.make_x(11, 0, 1, K1), synth.make_norm_weight(11, 0, K1), synth.make_residual(11, 0, N1)
+    N2, K2, b2, M2 = 6, 40000, 3, 2             # split-K: partial sums in the workspace, second kernel adds them
+    idx2, cb2, X2 = synth.make_indices(12, 0, N2, K2, b2), synth.make_codebook(12, 0, N2, b2), synth.make_x(12, 0, M2, K2)
+    N3, K3, b3 = 64, 1024, 2                    # the quantiser in the paper's format: 2 * rounds + 3 kernels
+    Wd3 = synth.make_dense_weights(13, 0, N3, K3)
+    W1, C1, Xd1, G1, R1 = dev(kmq.pack(idx1, 1)), dev(cb1), dev(x1), dev(g1), dev(r1)
+    W2, C2, Xd2 = dev(kmq.pack(idx2, b2)), dev(cb2), dev(X2)
+    ws2 = torch.empty(kmq.workspace_bytes(N2, K2, b2, M2), dtype=torch.uint8, device="cuda")
+    assert ws2.numel() > 0
+    D3 = dev(Wd3)
+    ws3 = torch.empty(kmq.quantize_blockscaled_workspace_bytes(), dtype=torch.uint8, device="cuda")
+
+    def outputs():
+        return (torch.full((N1,), 0x7FC1, dtype=torch.int16, device="cuda"),
+                torch.full((N1,), 0x7FC1, dtype=torch.int16, device="cuda"),
+                torch.full((M2, N2), 0x7FC1, dtype=torch.int16, device="cuda"),
+                torch.full((N3, K3 * b3 // 32), -1, dtype=torch.int32, device="cuda"),
+                torch.full((1 << b3,), 0x7FC1, dtype=torch.int16, device="cuda"),
+                torch.full((N3, K3 // 64), 0x7FC1, dtype=torch.int16, device="cuda"))
+
+    def run(Y):
+        kmq.gemv_fused(W1, C1, Xd1, Y[0], N1, K1, 1, norm_weight=G1, eps=1e-5, residual=R1)
+        kmq.gemv_swiglu_rmsnorm(W1, C1, W1, C1, Xd1, G1, 1e-5, Y[1], N1, K1, 1)
+        kmq.gemm_smallbatch(W2, C2, Xd2, Y[2], N2, K2, M2, b2, 0, ws2)
+        kmq.quantize_blockscaled(D3, N3, K3, b3, 5, Y[3], Y[4], Y[5], ws3)
+
+    eager = outputs()
+    run(eager)
+    torch.cuda.synchronize()
+    want = [y.clone() for y in eager]
+    captured = outputs()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        run(captured)
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            run(captured)
+    for replay in range(3):
+        for y in captured:
+            y.fill_(0x7FC1 if y.dtype == torch.int16 else -1)
+        ws2.fill_(0xFF)                        # the workspaces carry nothing from one call to the next
+        ws3.fill_(0xFF)
+        run(eager)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (y, w) in enumerate(zip(captured, want)):
+            assert torch.equal(y, w), f"replay {replay}, output {i}"
