@@ -210,6 +210,15 @@ const char* kmq_kernel_name_fused(int64_t N, int64_t K, int bits, int layout, in
 kmq_status kmq_gemv_bf16(const uint16_t* W, const uint16_t* x, uint16_t* y, int64_t N, int64_t K,
                          void* hip_stream);
 
+/* kmq_dequant for the block-scaled format (canonical layout, K % KMQ_BLOCK == 0):
+ * Wdense[n][k] = bf16( codebook[idx[n][k]] * scale[n][k / KMQ_BLOCK] ), one rounding to nearest
+ * even of the exact product -- the matrix the reference routine of paper App. E "Kernel
+ * implementations" materialises, and the first half of the separate-dequantise route for large
+ * batches (App. E "Model benchmarks").  Wdense N x K bf16, 16-byte aligned; other pointers as
+ * kmq_gemv_blockscaled.  Device pointers; asynchronous on hip_stream. */
+kmq_status kmq_dequant_blockscaled(const uint32_t* W, const uint16_t* codebook, const uint16_t* scales,
+                                   uint16_t* Wdense, int64_t N, int64_t K, int bits, void* hip_stream);
+
 /* ---- The quantiser: dense bf16 weights -> indices + codebooks ------------------------
  * (paper Sec. 2.1 "Rounding to nearest centroids": the quantiser rounds to the nearest of
  * 2^bits centroids obtained by 1-D k-means clustering; "Block formats"; Sec. 2.2 "Nonlinear

@@ -58,6 +58,8 @@ def _load():
         lib.oracle_swiglu.argtypes = [vp, vp, i64, vp]
         lib.oracle_gemm_dense.restype = ci
         lib.oracle_gemm_dense.argtypes = [vp, vp, i64, i64, i64, i64, i64, vp, vp, vp]
+        lib.oracle_dequant_blockscaled.restype = ci
+        lib.oracle_dequant_blockscaled.argtypes = [vp, vp, vp, i64, i64, ci, i64, vp]
         lib.oracle_rmsnorm.restype = ci
         lib.oracle_rmsnorm.argtypes = [vp, vp, i64, ctypes.c_double, vp, vp]
         lib.oracle_quantize_round_bf16.restype = ctypes.c_uint16
@@ -218,6 +220,18 @@ def swiglu(gate: np.ndarray, up: np.ndarray) -> np.ndarray:
     if _load().oracle_swiglu(_p(g), _p(u), g.size, _p(y)):
         raise ValueError("bad argument")
     return y
+
+
+def dequant_blockscaled(packed, codebook, scales, K: int, bits: int, block: int = 64) -> np.ndarray:
+    """Dense bf16 weights (uint16 patterns, N x K) of the block-scaled format: bf16(codebook[idx] * scale)."""
+    packed = _arr(packed, np.uint32)
+    N = packed.shape[0]
+    codebook = _arr(codebook, np.uint16, (1 << bits,))
+    scales = _arr(scales, np.uint16, (N, K // block))
+    Wd = np.empty((N, K), np.uint16)
+    if _load().oracle_dequant_blockscaled(_p(packed), _p(codebook), _p(scales), N, K, bits, block, _p(Wd)):
+        raise ValueError("oracle_dequant_blockscaled: bad arguments")
+    return Wd
 
 
 def rmsnorm(x, g, eps: float):

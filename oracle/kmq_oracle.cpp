@@ -216,6 +216,22 @@ int oracle_gemm_blockscaled(const uint32_t* packed, const uint16_t* codebook, co
     return 0;
 }
 
+// Dense weights of the block-scaled format (the separate-dequantise route the paper recommends
+// for large batches, App. E "Model benchmarks"; the reference routine of "Kernel implementations"
+// materialises the same matrix): Wd[n][k] = bf16( codebook[idx[n][k]] * scale[n][k / B] ).
+// The product of two bf16 values is exact in fp64, so this is one rounding (to nearest even).
+int oracle_dequant_blockscaled(const uint32_t* packed, const uint16_t* codebook, const uint16_t* scales,
+                               int64_t N, int64_t K, int bits, int64_t B, uint16_t* Wd) {
+    if (!packed || !codebook || !scales || !Wd || bits < 1 || bits > 4 || N < 0 || K < 1 || B < 1 || K % B != 0) return 1;
+    const int64_t wpr = words_per_row(bits, K), G = K / B;
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            const double c = bf16_to_double(codebook[read_field(packed + n * wpr, k, bits)]);
+            Wd[n * K + k] = oracle_round_bf16(c * bf16_to_double(scales[n * G + k / B]));
+        }
+    return 0;
+}
+
 // SwiGLU of a decoder MLP's gate and up projections (Shazeer-style gated unit with the SiLU
 // activation, as in the Llama-3 architecture the paper benchmarks, App. E "Model benchmarks"):
 // y[i] = silu(g[i]) * u[i], silu(t) = t / (1 + exp(-t)), on fp64 inputs.

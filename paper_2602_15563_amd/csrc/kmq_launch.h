@@ -58,6 +58,8 @@ hipError_t launch_rowsplit(int table_index, const GemmArgs& a, hipStream_t s);
 hipError_t launch_pair_generic(const GemmArgs& a, hipStream_t s);
 hipError_t launch_fused_generic(const GemmArgs& a, hipStream_t s);   // batch 1, canonical layout, any shape; pair optional
 hipError_t launch_blockscaled_generic(const GemmArgs& a, hipStream_t s);
+hipError_t launch_dequant_blockscaled(const uint32_t* W, const uint16_t* codebook, const uint16_t* scales, uint16_t* Wd,
+                                      int64_t N, int64_t K, int bits, hipStream_t s);   // canonical, K % 64 == 0
 
 // Dense bf16 baseline; K * 2 bytes of LDS, so K <= 32768.
 hipError_t launch_gemv_bf16(const uint16_t* W, const uint16_t* x, uint16_t* y, int64_t N, int64_t K, hipStream_t s);

@@ -72,6 +72,8 @@ _lib.kmq_kernel_name_swiglu.restype = ctypes.c_char_p
 _lib.kmq_kernel_name_swiglu.argtypes = [_i64, _i64, _int, _int]
 _lib.kmq_gemv_bf16.restype = ctypes.c_int32
 _lib.kmq_gemv_bf16.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
+_lib.kmq_dequant_blockscaled.restype = ctypes.c_int32
+_lib.kmq_dequant_blockscaled.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _int, _vp]
 _lib.kmq_gemv_fused.restype = ctypes.c_int32
 _lib.kmq_gemv_fused.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _i64, _i64, _int, _int, _vp]
 _lib.kmq_gemv_swiglu_rmsnorm.restype = ctypes.c_int32
@@ -270,6 +272,11 @@ def quantize_blockscaled(Wdense, N: int, K: int, bits: int, iters: int, packed, 
 def dequant(W, codebook, Wdense, N: int, K: int, bits: int, layout: int = 0):
     """Wdense[N][K] (bf16 storage) = codebook[n][idx[n][k]] on torch's current stream."""
     _check(_lib.kmq_dequant(_ptr(W), _ptr(codebook), _ptr(Wdense), N, K, bits, layout, _stream()))
+
+
+def dequant_blockscaled(W, codebook, scales, Wdense, N: int, K: int, bits: int):
+    """Wdense[N][K] (bf16 storage) = bf16(codebook[idx] * scale) of the block-scaled format, on torch's current stream."""
+    _check(_lib.kmq_dequant_blockscaled(_ptr(W), _ptr(codebook), _ptr(scales), _ptr(Wdense), N, K, bits, _stream()))
 
 
 def stream_read(t, sink=None):

@@ -143,3 +143,50 @@ def test_errors(gpu):
     with pytest.raises(kmq.KmqError) as e:
         kmq.gemv_blockscaled(p, cbd, None, xd, y, N, K, bits)
     assert e.value.status == 1
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4])
+@pytest.mark.parametrize("N,K", [(1, 64), (7, 640), (300, 4096), (33, 64 * 257)])
+def test_dequant_blockscaled_bit_exact(gpu, N, K, bits):
+    import torch
+    from paper_2602_15563_amd import kmq
+    idx, cb, sc, _ = _case(900 + bits + N, N, K, bits, 1)
+    packed = oracle.pack(idx, bits)
+    Wd = torch.full((N, K), 0x7FC1, dtype=torch.int16, device="cuda")
+    kmq.dequant_blockscaled(gpu.dev(packed), gpu.dev(cb), gpu.dev(sc), Wd, N, K, bits)
+    torch.cuda.synchronize()
+    assert np.array_equal(gpu.host_u16(Wd), oracle.dequant_blockscaled(packed, cb, sc, K, bits))
+
+
+def test_dequant_blockscaled_then_dense_product_matches_the_fused_one(gpu):
+    """The separate-dequantise route: dense weights from kmq_dequant_blockscaled through the dense bf16 GEMV against
+    the fused block-scaled GEMV of the same buffers; they differ by the rounding of the dense weights."""
+    import torch
+    from paper_2602_15563_amd import kmq
+    bits, N, K = 4, 512, 4096
+    idx, cb, sc, x = _case(940, N, K, bits, 1)
+    packed = oracle.pack(idx, bits)
+    Wd = torch.empty((N, K), dtype=torch.int16, device="cuda")
+    kmq.dequant_blockscaled(gpu.dev(packed), gpu.dev(cb), gpu.dev(sc), Wd, N, K, bits)
+    y = torch.empty(N, dtype=torch.int16, device="cuda")
+    kmq.gemv_bf16(Wd, gpu.dev(x), y, N, K)
+    torch.cuda.synchronize()
+    fused = synth.bf16_to_f64(gpu.run_gemm_blockscaled(gpu.dev(packed), gpu.dev(cb), gpu.dev(sc), x, N, K, bits)[0])
+    _, A, _ = oracle.gemm_blockscaled(packed, cb, sc, x, K, bits)
+    dense = synth.bf16_to_f64(gpu.host_u16(y))
+    assert np.all(np.abs(dense - fused) <= 2.0 ** -8 * A[0] + 2.0 ** -7 * np.abs(fused) + 2 * gpu.TOL * A[0])
+
+
+def test_dequant_blockscaled_errors(gpu):
+    import torch
+    from paper_2602_15563_amd import kmq
+    idx, cb, sc, _ = _case(950, 4, 128, 2, 1)
+    W, C, S = gpu.dev(oracle.pack(idx, 2)), gpu.dev(cb), gpu.dev(sc)
+    Wd = torch.zeros((4, 128), dtype=torch.int16, device="cuda")
+    for call, status in [(lambda: kmq.dequant_blockscaled(W, C, S, Wd, 4, 100, 2), 3),
+                         (lambda: kmq.dequant_blockscaled(W, C, S, Wd, 4, 128, 7), 2),
+                         (lambda: kmq.dequant_blockscaled(W, C, None, Wd, 4, 128, 2), 1),
+                         (lambda: kmq.dequant_blockscaled(W, C, S, Wd.view(-1)[1:], 4, 128, 2), 4)]:
+        with pytest.raises(kmq.KmqError) as e:
+            call()
+        assert e.value.status == status

@@ -160,3 +160,23 @@ def test_scale_generator_matches_the_block_maximum_it_stands_for():
         assert abs(np.quantile(s, q) - np.quantile(z, q)) < 0.03 * np.quantile(z, q)
     cb = synth.bf16_to_f64(synth.make_shared_codebook(1, 0, 4))
     assert np.all(np.diff(cb) >= 0) and np.all(np.abs(cb) <= 1.0)
+
+
+def test_dense_weights_of_the_format():
+    """bf16(codebook[idx] * scale): one rounding of an exact product, re-stated with numpy's fp32 product
+    (exact for two bf16 factors) and an independent rounding; unit scales give the bare centroids; and the
+    dense product of these weights is the block-scaled product up to that rounding."""
+    bits, N, K = 3, 9, 640
+    idx = synth.make_indices(31, 0, N, K, bits)
+    cb, sc = synth.make_shared_codebook(31, 0, bits), synth.make_scales(31, 0, N, K)
+    packed = oracle.pack(idx, bits)
+    Wd = oracle.dequant_blockscaled(packed, cb, sc, K, bits)
+    want = synth.f32_to_bf16(synth.bf16_to_f32(cb)[idx] * np.repeat(synth.bf16_to_f32(sc), 64, axis=1))
+    assert np.array_equal(Wd, want)
+    ones = np.full_like(sc, 0x3F80)
+    assert np.array_equal(oracle.dequant_blockscaled(packed, cb, ones, K, bits), cb[idx])
+    X = synth.make_x(31, 0, 2, K)
+    Yb, Ab, _ = oracle.gemm_blockscaled(packed, cb, sc, X, K, bits)
+    Yd, _, _ = oracle.gemm_dense(Wd, X)
+    assert np.all(np.abs(Yb - Yd) <= 2.0 ** -8 * Ab)        # each weight moved by at most half a bf16 ulp
+    assert np.any(Yb != Yd)
