@@ -249,7 +249,8 @@ def run_sweep(M: int, replays: int, fuse: str = ""):
     worst = max(it.check() for it in insts)
     gate, up = insts[2], insts[3]
     fuse_gate_up = fuse == "gate_up"
-    if fuse == "decoder":
+    if fuse in ("decoder", "decoder_unit_gains"):
+        unit = fuse == "decoder_unit_gains"      # gains multiplied into the weights before quantisation: scalar only
         # the whole layer's elementwise work folded into four launches (attention itself is not part of
         # this path): RMSNorm -> QKV; O + residual; RMSNorm -> gate, up -> SwiGLU; down + residual
         from paper_2602_15563_amd import kmq
@@ -264,9 +265,10 @@ def run_sweep(M: int, replays: int, fuse: str = ""):
         ysw = [torch.zeros(gate.N, dtype=torch.int16, device="cuda") for _ in range(SWEEP_LAYERS)]
 
         def decoder_layer(l):
-            kmq.gemv_fused(qkv.W[l], qkv.C[l], qkv.Xd[l], qkv.Y[l], qkv.N, qkv.K, qkv.bits, norm_weight=gn1[l], eps=eps)
+            kmq.gemv_fused(qkv.W[l], qkv.C[l], qkv.Xd[l], qkv.Y[l], qkv.N, qkv.K, qkv.bits,
+                           norm_weight=None if unit else gn1[l], eps=eps, rmsnorm=True)
             kmq.gemv_fused(o.W[l], o.C[l], o.Xd[l], o.Y[l], o.N, o.K, o.bits, residual=hres[l])
-            kmq.gemv_swiglu_rmsnorm(gate.W[l], gate.C[l], up.W[l], up.C[l], gate.Xd[l], gn2[l], eps, ysw[l],
+            kmq.gemv_swiglu_rmsnorm(gate.W[l], gate.C[l], up.W[l], up.C[l], gate.Xd[l], None if unit else gn2[l], eps, ysw[l],
                                     gate.N, gate.K, gate.bits)
             kmq.gemv_fused(down.W[l], down.C[l], down.Xd[l], down.Y[l], down.N, down.K, down.bits, residual=hres[l])
         decoder_layer(0)
@@ -275,18 +277,20 @@ def run_sweep(M: int, replays: int, fuse: str = ""):
         def close(yg, Y, A, what):
             if not np.all(np.abs(yg - Y) <= 2e-3 * A + 2.0 ** -8 * np.abs(Y)):
                 raise SystemExit(f"bench: fused decoder call ({what}) does not match the oracle")
+        if unit:
+            gn_host = [None, None]
         for it, g_, r_ in ((qkv, gn_host[0], None), (o, None, res_host), (down, None, res_host)):
             yg = synth.bf16_to_f64(it.Y[0].cpu().numpy().view(np.uint16)).reshape(-1)
             for n0 in (0, it.N // 2, it.N - 64):
                 Y, A = oracle.gemv_fused(it.packed, it.cb, it.X, it.K, it.bits, norm_weight=g_, eps=eps, residual=r_,
-                                         rows=(n0, n0 + 64))
+                                         rows=(n0, n0 + 64), rmsnorm=it is qkv)
                 close(yg[n0:n0 + 64], Y[n0:n0 + 64], A[n0:n0 + 64], it.name)
         yg = synth.bf16_to_f64(ysw[0].cpu().numpy().view(np.uint16))
         for n0 in (0, gate.N // 2, gate.N - 64):
             G, Ag = oracle.gemv_fused(gate.packed, gate.cb, gate.X, gate.K, gate.bits, norm_weight=gn_host[1], eps=eps,
-                                      rows=(n0, n0 + 64))
+                                      rows=(n0, n0 + 64), rmsnorm=True)
             U, Au = oracle.gemv_fused(up.packed, up.cb, gate.X, gate.K, gate.bits, norm_weight=gn_host[1], eps=eps,
-                                      rows=(n0, n0 + 64))
+                                      rows=(n0, n0 + 64), rmsnorm=True)
             G, Ag, U, Au = G[n0:n0 + 64], Ag[n0:n0 + 64], U[n0:n0 + 64], Au[n0:n0 + 64]
             want = oracle.swiglu(G, U)
             tol = 2e-3 * (1.1 * np.abs(U) * Ag + np.abs(oracle.swiglu(G, np.ones_like(G))) * Au) + 2.0 ** -8 * np.abs(want)
@@ -336,7 +340,7 @@ def run_sweep(M: int, replays: int, fuse: str = ""):
     with torch.cuda.stream(stream):
         def one_pass():
             for layer in range(SWEEP_LAYERS):
-                if fuse == "decoder":
+                if fuse.startswith("decoder"):
                     decoder_layer(layer)
                 elif fuse_gate_up:
                     insts[0].call(layer)
@@ -362,7 +366,8 @@ def run_sweep(M: int, replays: int, fuse: str = ""):
     us = e0.elapsed_time(e1) * 1e3 / replays
     nbytes = SWEEP_LAYERS * sum(it.bytes for it in insts)
     calls = SWEEP_LAYERS * (len(insts) - (1 if fuse else 0))
-    suffix = {"": "", "gate_up": "_fused_gate_up_swiglu", "decoder": "_fused_rmsnorm_swiglu_residual"}[fuse]
+    suffix = {"": "", "gate_up": "_fused_gate_up_swiglu", "decoder": "_fused_rmsnorm_swiglu_residual",
+              "decoder_unit_gains": "_fused_rmsnorm_unit_gains_swiglu_residual"}[fuse]
     return {"workload": f"cfg4_sweep_28layers_m{M}" + suffix, "us_per_sweep": round(us, 2), "us_per_call": round(us / calls, 3),
             "passes_per_s": round(1e6 / us, 1),
             "calls": calls, "GBps": round(nbytes / us * 1e-3, 1), "pct_peak": round(100 * nbytes / us * 1e-3 / HBM_PEAK_GBS, 2),
@@ -592,7 +597,7 @@ def main():
 
     if args.sweep:
         rows = []
-        for M, fused in ((1, ""), (1, "gate_up"), (1, "decoder"), (4, ""), (16, "")):
+        for M, fused in ((1, ""), (1, "gate_up"), (1, "decoder"), (1, "decoder_unit_gains"), (4, ""), (16, "")):
             rows.append(run_sweep(M, 200, fuse=fused))
             print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
             torch.cuda.empty_cache()

@@ -183,18 +183,24 @@ const char* kmq_kernel_name_swiglu(int64_t N, int64_t K, int bits, int layout);
  * layer's projections back to back; Sec. 3.3 "Software formats" attributes part of the 1-bit
  * model's lost speed to the elementwise work on the activations, RMSNorm and the activation
  * function).  One launch computes
- *     xn[k] = bf16( x[k] * norm_weight[k] )                  (norm_weight given; else xn = x)
- *     r     = 1 / sqrt( (1/K) sum_k x[k]^2 + eps )           (norm_weight given; else 1)
+ *     xn[k] = bf16( x[k] * norm_weight[k] )                  (rmsnorm with gains; else xn = x)
+ *     r     = 1 / sqrt( (1/K) sum_k x[k]^2 + eps )           (rmsnorm; else 1)
  *     y[n]  = bf16( residual[n] + r * sum_k w[n][k] xn[k] )  (residual optional)
  * i.e. RMSNorm in front of the product -- its scalar factor commutes with the sum, so the
  * activations enter the product as bf16(x * g) and r multiplies the fp32 result -- and a
- * residual sum behind it.  norm_weight: K bf16, 16-byte aligned, or NULL; eps >= 0;
- * residual: N bf16, 2-byte aligned, or NULL (may alias y); other arguments as kmq_gemv.
- * Canonical layout only (else KMQ_ERR_LAYOUT).  With both NULL it equals kmq_gemv. */
+ * residual sum behind it.
+ *   rmsnorm      0: no normalisation (norm_weight and eps ignored); 1: RMSNorm
+ *   norm_weight  K bf16 gains, 16-byte aligned, or NULL for unit gains -- the cheaper form: gains
+ *                are per input channel and can be multiplied into the dense weights before they are
+ *                quantised, and then no second vector is fetched by every workgroup
+ *   eps          >= 0
+ *   residual     N bf16, 2-byte aligned, or NULL; may alias y
+ * Other arguments as kmq_gemv.  Canonical layout only (else KMQ_ERR_LAYOUT).  With rmsnorm = 0
+ * and residual = NULL it equals kmq_gemv. */
 kmq_status kmq_gemv_fused(const uint32_t* W, const uint16_t* codebook, const uint16_t* x,
-                          const uint16_t* norm_weight, float eps, const uint16_t* residual, uint16_t* y,
-                          int64_t N, int64_t K, int bits, int layout, void* hip_stream);
-/* kmq_gemv_swiglu with the same RMSNorm in front of both products (norm_weight required). */
+                          int rmsnorm, const uint16_t* norm_weight, float eps, const uint16_t* residual,
+                          uint16_t* y, int64_t N, int64_t K, int bits, int layout, void* hip_stream);
+/* kmq_gemv_swiglu with the same RMSNorm in front of both products (norm_weight NULL: unit gains). */
 kmq_status kmq_gemv_swiglu_rmsnorm(const uint32_t* Wgate, const uint16_t* codebook_gate,
                                    const uint32_t* Wup, const uint16_t* codebook_up,
                                    const uint16_t* x, const uint16_t* norm_weight, float eps, uint16_t* y,

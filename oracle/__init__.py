@@ -238,7 +238,7 @@ def rmsnorm(x, g, eps: float):
     """(xn, r): xn = bf16(x * g) as uint16 patterns, r = 1 / sqrt(mean(x^2) + eps) in fp64; the
     normalised activations are xn * r (the fused call applies r after the product)."""
     x = _arr(x, np.uint16).reshape(-1)
-    g = _arr(g, np.uint16, x.shape)
+    g = np.full(x.shape, 0x3F80, np.uint16) if g is None else _arr(g, np.uint16, x.shape)   # None: unit gains
     xn = np.empty_like(x)
     r = np.empty(1, np.float64)
     if _load().oracle_rmsnorm(_p(x), _p(g), x.size, float(eps), _p(xn), _p(r)):
@@ -246,13 +246,20 @@ def rmsnorm(x, g, eps: float):
     return xn, float(r[0])
 
 
-def gemv_fused(packed, codebook, x, K: int, bits: int, norm_weight=None, eps: float = 0.0, residual=None, rows=None):
+_rmsnorm = rmsnorm     # gemv_fused has a parameter of that name
+
+
+def gemv_fused(packed, codebook, x, K: int, bits: int, norm_weight=None, eps: float = 0.0, residual=None, rows=None,
+               rmsnorm=None):
     """The fused decoder call's definition, composed from the pieces above:
-    Y[n] = residual[n] + r * sum_k w[n][k] xn[k]; returns (Y, A) with A = |residual| + r * sum |w xn|."""
+    Y[n] = residual[n] + r * sum_k w[n][k] xn[k]; returns (Y, A) with A = |residual| + r * sum |w xn|.
+    rmsnorm defaults to "gains were given"; rmsnorm=True without gains normalises with unit gains."""
     x = _arr(x, np.uint16).reshape(1, -1)
     r = 1.0
-    if norm_weight is not None:
-        xn, r = rmsnorm(x[0], norm_weight, eps)
+    if rmsnorm is None:
+        rmsnorm = norm_weight is not None
+    if rmsnorm:
+        xn, r = _rmsnorm(x[0], norm_weight, eps)
         x = xn.reshape(1, -1)
     Y, A, _ = gemm(packed, codebook, x, K, bits, rows=rows)
     Y, A = Y[0] * r, A[0] * r

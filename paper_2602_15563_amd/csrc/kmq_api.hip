@@ -136,15 +136,17 @@ const char* kmq_kernel_name_swiglu(int64_t N, int64_t K, int bits, int layout) {
 }
 
 kmq_status kmq_gemv_fused(const uint32_t* W, const uint16_t* codebook, const uint16_t* x,
-                          const uint16_t* norm_weight, float eps, const uint16_t* residual, uint16_t* y,
+                          int rmsnorm, const uint16_t* norm_weight, float eps, const uint16_t* residual, uint16_t* y,
                           int64_t N, int64_t K, int bits, int layout, void* hip_stream) {
     if (!W || !codebook || !x || !y) return KMQ_ERR_NULL;
     if (!kmq::bits_valid(bits)) return KMQ_ERR_BITS;
-    if (!kmq::dims_valid(N, K) || !(eps >= 0.f)) return KMQ_ERR_SHAPE;
+    if (!kmq::dims_valid(N, K) || (rmsnorm && !(eps >= 0.f)) || (rmsnorm != 0 && rmsnorm != 1)) return KMQ_ERR_SHAPE;
+    if (!rmsnorm) norm_weight = nullptr;
     if (layout != KMQ_LAYOUT_CANONICAL) return KMQ_ERR_LAYOUT;
     if (!kmq::aligned(W, 16) || !kmq::aligned(x, 16) || !kmq::aligned(codebook, 4) || !kmq::aligned(y, 2) ||
         (norm_weight && !kmq::aligned(norm_weight, 16)) || (residual && !kmq::aligned(residual, 2))) return KMQ_ERR_ALIGN;
     kmq::GemmArgs a{W, codebook, x, y, N, K, 1, bits, layout, nullptr, 0};
+    a.norm = rmsnorm != 0;
     a.norm_w = norm_weight;
     a.eps = eps;
     a.residual = residual;
@@ -158,15 +160,16 @@ kmq_status kmq_gemv_swiglu_rmsnorm(const uint32_t* Wgate, const uint16_t* codebo
                                    const uint32_t* Wup, const uint16_t* codebook_up,
                                    const uint16_t* x, const uint16_t* norm_weight, float eps, uint16_t* y,
                                    int64_t N, int64_t K, int bits, int layout, void* hip_stream) {
-    if (!Wgate || !codebook_gate || !Wup || !codebook_up || !x || !y || !norm_weight) return KMQ_ERR_NULL;
+    if (!Wgate || !codebook_gate || !Wup || !codebook_up || !x || !y) return KMQ_ERR_NULL;
     if (!kmq::bits_valid(bits)) return KMQ_ERR_BITS;
     if (!kmq::dims_valid(N, K) || 2 * N > kmq::kMaxDim || !(eps >= 0.f)) return KMQ_ERR_SHAPE;
     if (layout != KMQ_LAYOUT_CANONICAL) return KMQ_ERR_LAYOUT;
-    if (!kmq::aligned(Wgate, 16) || !kmq::aligned(Wup, 16) || !kmq::aligned(x, 16) || !kmq::aligned(norm_weight, 16) ||
+    if (!kmq::aligned(Wgate, 16) || !kmq::aligned(Wup, 16) || !kmq::aligned(x, 16) || (norm_weight && !kmq::aligned(norm_weight, 16)) ||
         !kmq::aligned(codebook_gate, 4) || !kmq::aligned(codebook_up, 4) || !kmq::aligned(y, 2)) return KMQ_ERR_ALIGN;
     kmq::GemmArgs a{Wgate, codebook_gate, x, y, N, K, 1, bits, layout, nullptr, 0};
     a.W2 = Wup;
     a.codebook2 = codebook_up;
+    a.norm = true;
     a.norm_w = norm_weight;
     a.eps = eps;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);

@@ -3,8 +3,8 @@
 // at low bit-widths the elementwise work between them -- RMSNorm, the activation function,
 // the residual sums -- is a visible share of the time).  One launch computes
 //
-//     xn[k] = bf16( x[k] * g[k] )                       RMSNorm weights g in front (optional)
-//     r     = 1 / sqrt( mean_k x[k]^2 + eps )           (1 without g)
+//     xn[k] = bf16( x[k] * g[k] )                       RMSNorm in front (optional; xn = x for unit gains)
+//     r     = 1 / sqrt( mean_k x[k]^2 + eps )           (1 without the norm)
 //     p[n]  = r * sum_k w[n][k] * xn[k]                 the product of kmq_gemv
 //     y[n]  = bf16( residual[n] + p[n] )                residual behind (optional), or
 //     y[n]  = bf16( silu(p_gate[n]) * p_up[n] )         for a pair of matrices (gate, up)
@@ -33,7 +33,7 @@ template <int BITS, bool PAIR>
 __global__ __launch_bounds__(256) void gemv_fused_generic_kernel(
     const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
     const uint32_t* __restrict__ W2, const uint16_t* __restrict__ codebook2,
-    const uint16_t* __restrict__ x, const uint16_t* __restrict__ norm_w, float eps,
+    const uint16_t* __restrict__ x, bool norm, const uint16_t* __restrict__ norm_w, float eps,
     const uint16_t* __restrict__ residual, uint16_t* __restrict__ y, int64_t N, int64_t K) {
     constexpr int C = 1 << BITS;
     __shared__ float lut[4][2][C];
@@ -53,9 +53,9 @@ __global__ __launch_bounds__(256) void gemv_fused_generic_kernel(
     float acc0 = 0.f, acc1 = 0.f, ss = 0.f;
     for (int64_t k = lane; k < K; k += kWave) {
         float xv = bf16_to_f32(x[k]);
-        if (norm_w) {
+        if (norm) {
             ss = fmaf(xv, xv, ss);
-            xv = bf16_to_f32(f32_to_bf16(xv * bf16_to_f32(norm_w[k])));
+            if (norm_w) xv = bf16_to_f32(f32_to_bf16(xv * bf16_to_f32(norm_w[k])));
         }
         acc0 = fmaf(lut[wave][0][stream_field<BITS>(r0, k)], xv, acc0);
         if constexpr (PAIR) acc1 = fmaf(lut[wave][1][stream_field<BITS>(r1, k)], xv, acc1);
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void gemv_fused_generic_kernel(
     if constexpr (PAIR) acc1 = group_sum<64>(acc1);
     ss = group_sum<64>(ss);
     if (lane != 63) return;
-    const float r = norm_w ? 1.f / sqrtf(ss * (1.f / static_cast<float>(K)) + eps) : 1.f;
+    const float r = norm ? 1.f / sqrtf(ss * (1.f / static_cast<float>(K)) + eps) : 1.f;
     float out = acc0 * r;
     if constexpr (PAIR) {
         out = out / (1.f + __expf(-out)) * (acc1 * r);
@@ -79,10 +79,10 @@ static hipError_t launch_fused_bits(const GemmArgs& a, hipStream_t s) {
     const dim3 grid(static_cast<unsigned>((a.N + 3) / 4)), block(256);
     if (a.W2)
         hipLaunchKernelGGL((gemv_fused_generic_kernel<BITS, true>), grid, block, 0, s, a.W, a.codebook, a.W2, a.codebook2, a.X,
-                           a.norm_w, a.eps, static_cast<const uint16_t*>(nullptr), a.Y, a.N, a.K);
+                           a.norm, a.norm_w, a.eps, static_cast<const uint16_t*>(nullptr), a.Y, a.N, a.K);
     else
         hipLaunchKernelGGL((gemv_fused_generic_kernel<BITS, false>), grid, block, 0, s, a.W, a.codebook,
-                           static_cast<const uint32_t*>(nullptr), static_cast<const uint16_t*>(nullptr), a.X, a.norm_w, a.eps,
+                           static_cast<const uint32_t*>(nullptr), static_cast<const uint16_t*>(nullptr), a.X, a.norm, a.norm_w, a.eps,
                            a.residual, a.Y, a.N, a.K);
     return hipGetLastError();
 }

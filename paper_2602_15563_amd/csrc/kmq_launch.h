@@ -21,7 +21,8 @@ struct GemmArgs {
     const uint16_t* scales = nullptr;   // block-scaled format: N x K/64 bf16, and `codebook` is one tensor-wide table
     const uint32_t* W2 = nullptr;       // fused pair (gate, up): second matrix and its codebooks, same shape and format
     const uint16_t* codebook2 = nullptr;
-    const uint16_t* norm_w = nullptr;   // RMSNorm weights (K bf16) applied to x in front of the product, with eps
+    bool norm = false;                  // RMSNorm of x in front of the product, with eps ...
+    const uint16_t* norm_w = nullptr;   // ... and these gains (K bf16); nullptr: unit gains
     float eps = 0.f;
     const uint16_t* residual = nullptr; // N bf16 added to the product
 };

@@ -239,7 +239,10 @@ __device__ __forceinline__ void load_words(const uint32_t* p, uint32_t (&w)[G]) 
 // the elementwise work between the projections is a visible share of a token's time).
 //   bit 0  RMSNorm in front: the activations entering the product are bf16(x * g), and the
 //          result is multiplied by 1 / sqrt(mean(x^2) + eps), a scalar that commutes with the sum;
-//   bit 1  residual behind: y = residual + product.
+//   bit 1  residual behind: y = residual + product;
+//   bit 2  RMSNorm with unit gains (gains folded into the weights before quantisation): only the
+//          scalar, taken from the activations the workgroup stages anyway -- no second vector to
+//          fetch per workgroup, which is what bit 0 costs.
 template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE, bool SC, bool PAIR, int FUSE>
 __global__ __launch_bounds__(NWK * NWR * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
@@ -250,6 +253,8 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     static_assert(!(SC && PAIR), "the fused pair is offered for the per-row-codebook format");
     static_assert(FUSE == 0 || !SC, "decoder fusions are offered for the per-row-codebook format");
     static_assert(!(PAIR && (FUSE & 2)), "the fused pair has no residual input");
+    static_assert((FUSE & 5) != 5, "gains or unit gains");
+    constexpr bool NORM_G = (FUSE & 1) != 0, NORM = (FUSE & 5) != 0, RES = (FUSE & 2) != 0;
     static_assert(BITS == 1 || BITS == 2 || BITS == 4, "3-bit fields do not align with nibbles");
     constexpr int C = 1 << BITS;
     constexpr int EL = G * 32 / BITS;              // elements per lane and row slice
@@ -332,8 +337,8 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         int c = threadIdx.x * XPT;
         c = c < XCHUNKS ? c : XCHUNKS - XPT;
         xt = *reinterpret_cast<const xwide_t*>(x + c * 8);
-        if constexpr ((FUSE & 1) != 0) gt = *reinterpret_cast<const xwide_t*>(norm_w + c * 8);
-        if constexpr ((FUSE & 2) != 0) {
+        if constexpr (NORM_G) gt = *reinterpret_cast<const xwide_t*>(norm_w + c * 8);
+        if constexpr (RES) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {          // fetched with the first loads: long there when the epilogue runs
                 int64_t row = wg_row0 + (threadIdx.x * 2 + h) % ROWS_WG;
@@ -392,18 +397,20 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- 3. staged activations into LDS ----------------------------------------------------------
-    if constexpr ((FUSE & 1) != 0) {
+    if constexpr (NORM) {
         float ss = 0.f;
 #pragma unroll
         for (int i = 0; i < 4 * XPT; ++i) {
-            const float x0 = __uint_as_float(xt[i] << 16), x1 = __uint_as_float(xt[i] & 0xFFFF0000u);
-            const float g0 = __uint_as_float(gt[i] << 16), g1 = __uint_as_float(gt[i] & 0xFFFF0000u);
             ss = dot2_bf16(xt[i], xt[i], ss);
-            // a product of two bf16 values is exact in fp32: one rounding (to nearest even, the
-            // hardware's packed conversion), to the bf16 activation
-            typedef __attribute__((ext_vector_type(2))) float f32x2_t;
-            const f32x2_t p = {x0 * g0, x1 * g1};
-            xt[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2_t));
+            if constexpr (NORM_G) {
+                const float x0 = __uint_as_float(xt[i] << 16), x1 = __uint_as_float(xt[i] & 0xFFFF0000u);
+                const float g0 = __uint_as_float(gt[i] << 16), g1 = __uint_as_float(gt[i] & 0xFFFF0000u);
+                // a product of two bf16 values is exact in fp32: one rounding (to nearest even, the
+                // hardware's packed conversion), to the bf16 activation
+                typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+                const f32x2_t p = {x0 * g0, x1 * g1};
+                xt[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2_t));
+            }
         }
         ss = threadIdx.x * XPT < XCHUNKS ? ss : 0.f;       // threads past the end restaged a neighbour's chunks
         ss = group_sum<64>(ss);
@@ -563,7 +570,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     if (threadIdx.x < ROWS_WG / 2) {
         float out[2];
         [[maybe_unused]] float rnorm = 1.f;
-        if constexpr ((FUSE & 1) != 0) {
+        if constexpr (NORM) {
             float ss = 0.f;
 #pragma unroll
             for (int i = 0; i < NWK * NWR; ++i) ss += sm.ssq[i];
@@ -585,8 +592,8 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
                 const float c0 = bf16_to_f32(cc & 0xFFFFu), c1 = bf16_to_f32(cc >> 16);
                 s = fmaf(c1 - c0, s, c0 * sx);
             }
-            if constexpr ((FUSE & 1) != 0) s *= rnorm;
-            if constexpr ((FUSE & 2) != 0) s += bf16_to_f32(resv[h]);
+            if constexpr (NORM) s *= rnorm;
+            if constexpr (RES) s += bf16_to_f32(resv[h]);
             out[h] = s;
         }
         const int64_t r2 = wg_row0 + threadIdx.x * 2;
@@ -624,12 +631,15 @@ static void launch_lut(const GemmArgs& a, hipStream_t s) {
         if (a.W2) {                                           // fused pair: 2N virtual rows
             const int64_t nv = 2 * a.N;
             const dim3 grid(static_cast<unsigned>((nv + rows_wg - 1) / rows_wg));
-            if constexpr (BITS == 1) {
-                if (a.norm_w) {
-                    hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, true, 1>), grid, block, 0, s,
-                                       a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, a.norm_w, a.eps, nullptr);
-                    return;
-                }
+            if (a.norm && a.norm_w) {
+                hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, true, 1>), grid, block, 0, s,
+                                   a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, a.norm_w, a.eps, nullptr);
+                return;
+            }
+            if (a.norm) {
+                hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, true, 4>), grid, block, 0, s,
+                                   a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, nullptr, a.eps, nullptr);
+                return;
             }
             hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, true, 0>), grid, block, 0, s,
                                a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, nullptr, 0.f, nullptr);
@@ -637,13 +647,19 @@ static void launch_lut(const GemmArgs& a, hipStream_t s) {
         }
     }
     const dim3 grid(static_cast<unsigned>((a.N + rows_wg - 1) / rows_wg));
-    if constexpr (BITS == 1 && !SC) {                         // decoder fusions: the 1-bit shapes carry them
+    if constexpr (!SC) {                                      // decoder fusions (per-row-codebook format)
 #define KMQ_LUT_FUSED(F) \
         hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, false, F>), grid, block, 0, s, \
                            a.W, a.codebook, a.X, a.Y, a.N, a.scales, nullptr, nullptr, a.norm_w, a.eps, a.residual)
-        if (a.norm_w && a.residual) { KMQ_LUT_FUSED(3); return; }
-        if (a.norm_w) { KMQ_LUT_FUSED(1); return; }
-        if (a.residual) { KMQ_LUT_FUSED(2); return; }
+        const int fuse = (a.norm ? (a.norm_w ? 1 : 4) : 0) | (a.residual ? 2 : 0);
+        switch (fuse) {
+            case 1: KMQ_LUT_FUSED(1); return;
+            case 2: KMQ_LUT_FUSED(2); return;
+            case 3: KMQ_LUT_FUSED(3); return;
+            case 4: KMQ_LUT_FUSED(4); return;
+            case 6: KMQ_LUT_FUSED(6); return;
+            default: break;
+        }
 #undef KMQ_LUT_FUSED
     }
     hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, SC, false, 0>), grid, block, 0, s,
@@ -720,7 +736,7 @@ int lut_find(int64_t N, int64_t K, int bits, int layout, bool scaled) {
 }
 
 const char* lut_name(int i) { return kLut[i].name; }
-bool lut_has_fusions(int i) { return kLut[i].bits == 1 && !kLut[i].scaled; }
+bool lut_has_fusions(int i) { return !kLut[i].scaled; }
 
 hipError_t launch_lut_entry(int i, const GemmArgs& a, hipStream_t s) {
     kLut[i].launch(a, s);

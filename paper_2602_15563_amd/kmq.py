@@ -75,7 +75,7 @@ _lib.kmq_gemv_bf16.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp]
 _lib.kmq_dequant_blockscaled.restype = ctypes.c_int32
 _lib.kmq_dequant_blockscaled.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _int, _vp]
 _lib.kmq_gemv_fused.restype = ctypes.c_int32
-_lib.kmq_gemv_fused.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _i64, _i64, _int, _int, _vp]
+_lib.kmq_gemv_fused.argtypes = [_vp, _vp, _vp, _int, _vp, ctypes.c_float, _vp, _vp, _i64, _i64, _int, _int, _vp]
 _lib.kmq_gemv_swiglu_rmsnorm.restype = ctypes.c_int32
 _lib.kmq_gemv_swiglu_rmsnorm.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _i64, _i64, _int, _int, _vp]
 _lib.kmq_kernel_name_fused.restype = ctypes.c_char_p
@@ -236,10 +236,13 @@ def gemv_bf16(W, x, y, N: int, K: int):
 
 
 def gemv_fused(W, codebook, x, y, N: int, K: int, bits: int, norm_weight=None, eps: float = 0.0, residual=None,
-               layout: int = 0):
-    """y = residual + W rmsnorm(x; norm_weight, eps) on torch's current stream; both fusions optional."""
-    _check(_lib.kmq_gemv_fused(_ptr(W), _ptr(codebook), _ptr(x), _ptr(norm_weight), eps, _ptr(residual), _ptr(y),
-                               N, K, bits, layout, _stream()))
+               layout: int = 0, rmsnorm=None):
+    """y = residual + W rmsnorm(x; norm_weight, eps) on torch's current stream; both fusions optional.
+    rmsnorm defaults to "gains were given"; rmsnorm=True with norm_weight=None normalises with unit gains."""
+    if rmsnorm is None:
+        rmsnorm = norm_weight is not None
+    _check(_lib.kmq_gemv_fused(_ptr(W), _ptr(codebook), _ptr(x), 1 if rmsnorm else 0, _ptr(norm_weight), eps,
+                               _ptr(residual), _ptr(y), N, K, bits, layout, _stream()))
 
 
 def gemv_swiglu_rmsnorm(Wgate, cb_gate, Wup, cb_up, x, norm_weight, eps: float, y, N: int, K: int, bits: int,

@@ -24,20 +24,21 @@ def _inputs(seed, bits, N, K):
     return idx, cb, x, synth.make_norm_weight(seed, 0, K), synth.make_residual(seed, 0, N)
 
 
-def _run(gpu, idx, cb, x, bits, g=None, res=None, alias=False):
+def _run(gpu, idx, cb, x, bits, g=None, res=None, alias=False, unit=False):
     from paper_2602_15563_amd import kmq
     N, K = idx.shape
     y = gpu.dev(res) if alias else torch.full((N,), 0x7FC1, dtype=torch.int16, device="cuda")
     kmq.gemv_fused(gpu.dev(kmq.pack(idx, bits)), gpu.dev(cb), gpu.dev(x), y, N, K, bits,
                    norm_weight=None if g is None else gpu.dev(g), eps=EPS,
-                   residual=None if res is None else (y if alias else gpu.dev(res)))
+                   residual=None if res is None else (y if alias else gpu.dev(res)), rmsnorm=True if unit else None)
     torch.cuda.synchronize()
     return synth.bf16_to_f64(gpu.host_u16(y))
 
 
-def _check(gpu, yg, idx, cb, x, bits, g, res, label):
+def _check(gpu, yg, idx, cb, x, bits, g, res, label, unit=False):
     N, K = idx.shape
-    Y, A = oracle.gemv_fused(oracle.pack(idx, bits), cb, x, K, bits, norm_weight=g, eps=EPS, residual=res)
+    Y, A = oracle.gemv_fused(oracle.pack(idx, bits), cb, x, K, bits, norm_weight=g, eps=EPS, residual=res,
+                             rmsnorm=True if unit else None)
     err = np.abs(yg - Y)
     # fp32 sums in any order, the scalar in fp32 (a few roundings), one bf16 rounding of the result
     bound = gpu.arithmetic_bound(A, Y, K + 16)
@@ -47,37 +48,44 @@ def _check(gpu, yg, idx, cb, x, bits, g, res, label):
     assert not bad.any(), f"{label}: {int(bad.sum())} beyond tolerance, worst err/A {np.max(err / np.maximum(A, 1e-300)):.3e}"
 
 
-MODES = [("norm", True, False), ("res", False, True), ("both", True, True), ("plain", False, False)]
-LUT_1BIT = [(2048, 64), (2048, 333), (3072, 100), (3072, 3072), (4096, 50), (8192, 96), (8192, 3072)]
+MODES = [("norm", True, False), ("res", False, True), ("both", True, True), ("plain", False, False),
+         ("unit", "unit", False), ("unit+res", "unit", True)]
+LUT_SHAPES = [(1, 2048, 64), (1, 2048, 333), (1, 3072, 100), (1, 3072, 3072), (1, 4096, 50), (1, 8192, 96), (1, 8192, 3072),
+              (2, 2048, 40), (2, 3072, 77), (2, 4096, 1000), (2, 8192, 64), (2, 14336, 130),
+              (4, 2048, 40), (4, 4096, 333), (4, 8192, 64), (4, 14336, 70)]
 
 
 @pytest.mark.parametrize("mode,use_g,use_r", MODES)
-@pytest.mark.parametrize("K,N", LUT_1BIT)
-def test_fused_on_the_one_bit_table_kernels(gpu, K, N, mode, use_g, use_r):
+@pytest.mark.parametrize("bits,K,N", LUT_SHAPES)
+def test_fused_on_the_table_kernels(gpu, bits, K, N, mode, use_g, use_r):
     from paper_2602_15563_amd import kmq
-    assert kmq.kernel_name_fused(N, K, 1).startswith("lut_b1")
-    idx, cb, x, g, res = _inputs(500 + K // 64 + N, 1, N, K)
-    print(f"fused {mode} b1 {N}x{K}", flush=True)
-    yg = _run(gpu, idx, cb, x, 1, g if use_g else None, res if use_r else None)
-    _check(gpu, yg, idx, cb, x, 1, g if use_g else None, res if use_r else None, f"{mode} b1 {N}x{K}")
+    assert kmq.kernel_name_fused(N, K, bits).startswith(f"lut_b{bits}")
+    idx, cb, x, g, res = _inputs(500 + K // 64 + N, bits, N, K)
+    print(f"fused {mode} b{bits} {N}x{K}", flush=True)
+    unit = use_g == "unit"
+    gg = g if use_g is True else None
+    yg = _run(gpu, idx, cb, x, bits, gg, res if use_r else None, unit=unit)
+    _check(gpu, yg, idx, cb, x, bits, gg, res if use_r else None, f"{mode} b{bits} {N}x{K}", unit=unit)
 
 
 @pytest.mark.parametrize("mode,use_g,use_r", MODES)
-@pytest.mark.parametrize("bits,N,K", [(2, 40, 4096), (3, 33, 515), (4, 100, 33), (1, 7, 1), (1, 9, 1000), (4, 64, 14336)])
+@pytest.mark.parametrize("bits,N,K", [(3, 40, 4096), (3, 33, 515), (4, 100, 33), (1, 7, 1), (1, 9, 1000), (2, 64, 1024)])
 def test_fused_any_shape(gpu, bits, N, K, mode, use_g, use_r):
     from paper_2602_15563_amd import kmq
     assert kmq.kernel_name_fused(N, K, bits) == "fused_generic"
     idx, cb, x, g, res = _inputs(600 + bits + N, bits, N, K)
-    yg = _run(gpu, idx, cb, x, bits, g if use_g else None, res if use_r else None)
-    _check(gpu, yg, idx, cb, x, bits, g if use_g else None, res if use_r else None, f"{mode} b{bits} {N}x{K}")
+    unit = use_g == "unit"
+    gg = g if use_g is True else None
+    yg = _run(gpu, idx, cb, x, bits, gg, res if use_r else None, unit=unit)
+    _check(gpu, yg, idx, cb, x, bits, gg, res if use_r else None, f"{mode} b{bits} {N}x{K}", unit=unit)
 
 
 def test_plain_mode_equals_kmq_gemv_bit_for_bit(gpu):
-    for K, N in [(3072, 200), (8192, 64)]:
-        idx, cb, x, _, _ = _inputs(700 + N, 1, N, K)
+    for bits, K, N in [(1, 3072, 200), (1, 8192, 64), (2, 4096, 300), (4, 4096, 100)]:
+        idx, cb, x, _, _ = _inputs(700 + N, bits, N, K)
         from paper_2602_15563_amd import kmq
-        a = _run(gpu, idx, cb, x, 1)
-        b = synth.bf16_to_f64(gpu.run_gemm(gpu.dev(kmq.pack(idx, 1)), gpu.dev(cb), x, N, K, 1)[0])
+        a = _run(gpu, idx, cb, x, bits)
+        b = synth.bf16_to_f64(gpu.run_gemm(gpu.dev(kmq.pack(idx, bits)), gpu.dev(cb), x, N, K, bits)[0])
         assert np.array_equal(a, b)
 
 
@@ -100,21 +108,21 @@ def test_unit_weights_reduce_to_a_scaled_product(gpu):
     assert np.all(np.abs(yg - Y0[0] * r) <= gpu.arithmetic_bound(A0[0] * r, Y0[0] * r, K + 16))
 
 
-def _swiglu_norm(gpu, bits, N, K, seed):
+def _swiglu_norm(gpu, bits, N, K, seed, unit=False):
     from paper_2602_15563_amd import kmq
     ig, iu = synth.make_indices(seed, 0, N, K, bits), synth.make_indices(seed, 1, N, K, bits)
     sym = bits == 1
     cg, cu = synth.make_codebook(seed, 0, N, bits, symmetric=sym), synth.make_codebook(seed, 1, N, bits, symmetric=sym)
     x = synth.f32_to_bf16(synth.bf16_to_f32(synth.make_x(seed, 0, 1, K)[0]) * np.float32(3.0))
     # gains large enough that the gate spans the non-linear range of silu after normalisation
-    g = synth.make_norm_weight(seed, 0, K, gain=40.0 / np.sqrt(K))
+    g = None if unit else synth.make_norm_weight(seed, 0, K, gain=40.0 / np.sqrt(K))
     y = torch.full((N,), 0x7FC1, dtype=torch.int16, device="cuda")
     kmq.gemv_swiglu_rmsnorm(gpu.dev(kmq.pack(ig, bits)), gpu.dev(cg), gpu.dev(kmq.pack(iu, bits)), gpu.dev(cu), gpu.dev(x),
-                            gpu.dev(g), EPS, y, N, K, bits)
+                            None if unit else gpu.dev(g), EPS, y, N, K, bits)
     torch.cuda.synchronize()
     yg = synth.bf16_to_f64(gpu.host_u16(y))
-    G, Ag = oracle.gemv_fused(oracle.pack(ig, bits), cg, x, K, bits, norm_weight=g, eps=EPS)
-    U, Au = oracle.gemv_fused(oracle.pack(iu, bits), cu, x, K, bits, norm_weight=g, eps=EPS)
+    G, Ag = oracle.gemv_fused(oracle.pack(ig, bits), cg, x, K, bits, norm_weight=g, eps=EPS, rmsnorm=True)
+    U, Au = oracle.gemv_fused(oracle.pack(iu, bits), cu, x, K, bits, norm_weight=g, eps=EPS, rmsnorm=True)
     want = oracle.swiglu(G, U)
     dg, du = (K + 24) * 2.0 ** -23 * Ag, (K + 24) * 2.0 ** -23 * Au
     silu = oracle.swiglu(G, np.ones_like(G))
@@ -124,18 +132,21 @@ def _swiglu_norm(gpu, bits, N, K, seed):
     assert np.all(err <= bound), f"b{bits} {N}x{K}: max err/bound {np.max(err / np.maximum(bound, 1e-300)):.2f}"
 
 
-@pytest.mark.parametrize("K,N", [(2048, 40), (3072, 64), (3072, 8192), (4096, 333), (8192, 17)])
-def test_swiglu_rmsnorm_on_the_one_bit_table_kernels(gpu, K, N):
+@pytest.mark.parametrize("bits,K,N", [(1, 2048, 40), (1, 3072, 64), (1, 3072, 8192), (1, 4096, 333), (1, 8192, 17),
+                                      (2, 4096, 14336), (2, 14336, 50), (4, 4096, 100), (4, 8192, 33)])
+def test_swiglu_rmsnorm_on_the_table_kernels(gpu, bits, K, N):
     from paper_2602_15563_amd import kmq
-    assert kmq.kernel_name_fused(N, K, 1, pair=True).startswith("lut_b1")
-    _swiglu_norm(gpu, 1, N, K, 800 + N)
+    assert kmq.kernel_name_fused(N, K, bits, pair=True).startswith(f"lut_b{bits}")
+    _swiglu_norm(gpu, bits, N, K, 800 + N)
+    _swiglu_norm(gpu, bits, N, K, 850 + N, unit=True)
 
 
-@pytest.mark.parametrize("bits,N,K", [(2, 40, 4096), (3, 33, 515), (4, 20, 33), (1, 9, 1000)])
+@pytest.mark.parametrize("bits,N,K", [(3, 40, 4096), (3, 33, 515), (4, 20, 33), (1, 9, 1000)])
 def test_swiglu_rmsnorm_any_shape(gpu, bits, N, K):
     from paper_2602_15563_amd import kmq
     assert kmq.kernel_name_fused(N, K, bits, pair=True) == "fused_generic"
     _swiglu_norm(gpu, bits, N, K, 900 + N)
+    _swiglu_norm(gpu, bits, N, K, 950 + N, unit=True)
 
 
 def test_errors(gpu):
@@ -148,7 +159,8 @@ def test_errors(gpu):
         (lambda: kmq.gemv_fused(W, cbd, xd, y, 8, 64, 5), 2),
         (lambda: kmq.gemv_fused(W, cbd, xd, y, 8, 64, 2, norm_weight=gd, eps=-1.0), 3),
         (lambda: kmq.gemv_fused(W, cbd, None, y, 8, 64, 2), 1),
-        (lambda: kmq.gemv_swiglu_rmsnorm(W, cbd, W, cbd, xd, None, EPS, y, 8, 64, 2), 1),
+        (lambda: kmq.gemv_swiglu_rmsnorm(W, cbd, W, cbd, None, gd, EPS, y, 8, 64, 2), 1),
+        (lambda: kmq.gemv_swiglu_rmsnorm(W, cbd, W, cbd, xd, gd, -1.0, y, 8, 64, 2), 3),
         (lambda: kmq.gemv_fused(W, cbd, xd, y, 8, 64, 2, norm_weight=gd[1:]), 4),
     ]:
         with pytest.raises(kmq.KmqError) as e:
