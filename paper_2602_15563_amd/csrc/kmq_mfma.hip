@@ -160,7 +160,9 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     [[maybe_unused]] uint32_t lo0[RBW], lo1[RBW], hi0[RBW], hi1[RBW];   // perm pools: low / high bytes of the lane's centroids
     if constexpr (BITS == 4) {
 #pragma unroll
-        for (int r = 0; r < RBW; ++r) trow[r] = &sm.tbl[r * 16 + n][0];
+        // tensor-wide codebook: every lane reads the one table, 8 dwords in 8 banks, so a wave's
+        // lookups never collide; per-row tables of rows n and n + 8 share banks
+        for (int r = 0; r < RBW; ++r) trow[r] = &sm.tbl[SC ? 0 : r * 16 + n][0];
     } else if constexpr (BITS == 2 || BITS == 3) {
 #pragma unroll
         for (int r = 0; r < RBW; ++r) {
@@ -415,11 +417,13 @@ static int env_int(const char* name) {
 
 // Waves along K for `rbw` row blocks per wave: the largest of 8, 6, 4, 3, 2, 1 that divides
 // the number of super-blocks and has a kernel.  With two or more row blocks per wave and
-// 2..4-bit decoding, more than 4 waves measured slower (registers).
+// 2- or 3-bit decoding, more than 4 waves measured slower (registers); the 4-bit decode goes
+// through LDS lookups and wants every wave it can get (8192 x 8192, M = 16: 25.6 us with 4
+// waves, 20.8 with 8).
 static int waves_along_k(int64_t K, int bits, int rbw) {
     static const int forced = env_int("KMQ_MFMA_NWK");
     const int nsb = static_cast<int>(K / tiled_superblock_elems(bits));
-    const int cap = forced ? forced : ((bits >= 2 && rbw >= 2) ? 4 : 8);
+    const int cap = forced ? forced : (((bits == 2 || bits == 3) && rbw >= 2) ? 4 : 8);
     static const int kChoices[] = {8, 6, 4, 3, 2};
     for (int w : kChoices)
         if (nsb % w == 0 && w <= cap && mfma_has_shape(w, rbw, nsb / w)) return w;
