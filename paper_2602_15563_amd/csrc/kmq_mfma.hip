@@ -93,6 +93,8 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
         u32x4_t xstage[NWK][16 * 17];
         float redx[BITS == 1 ? NWK : 1][16];                // 1-bit: partial sum_k x per batch column
         // block-scaled: scales of the workgroup's rows, [row block][K block][row in block]
+        // (kept as bf16: an fp32 table saves four conversions per tile and block but doubles the
+        // staging writes and the footprint, and measured slower)
         uint16_t sct[SC ? RBW * kMaxScaledBlocks * 16 : 1];
     };
     __shared__ Smem sm;
@@ -156,6 +158,11 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
 #pragma unroll
     for (int r = 0; r < RBW; ++r) acc[r] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     [[maybe_unused]] f32x4_t accx = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    [[maybe_unused]] f32x4_t accxs[RBW];                    // 1-bit block-scaled: sum over blocks of scale * (block sum of x)
+    if constexpr (SC && BITS == 1) {
+#pragma unroll
+        for (int r = 0; r < RBW; ++r) accxs[r] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
     [[maybe_unused]] const uint16_t* trow[RBW];
     [[maybe_unused]] uint32_t lo0[RBW], lo1[RBW], hi0[RBW], hi1[RBW];   // perm pools: low / high bytes of the lane's centroids
     if constexpr (BITS == 4) {
@@ -315,8 +322,10 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
                                                      bf16_to_f32(s4[1] & 0xFFFFu), bf16_to_f32(s4[1] >> 16)};
 #pragma unroll
                                 for (int i = 0; i < 4; ++i) {
-                                    const float v = BITS == 1 ? fmaf(cdiff, t[i], c0s * tx[i]) : t[i];
-                                    acc[r][i] = fmaf(sc[i], v, acc[r][i]);
+                                    acc[r][i] = fmaf(sc[i], t[i], acc[r][i]);
+                                    // 1-bit: the scaled block sums of x are kept apart and combined with
+                                    // the two centroids once, after the loop
+                                    if constexpr (BITS == 1) accxs[r][i] = fmaf(sc[i], tx[i], accxs[r][i]);
                                 }
                             }
                         }
@@ -333,6 +342,12 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
 
     // ---- K-reduction across the waves, fixed order ---------------------------------------------
     // lane holds D[row 4*q + i][batch column n], i = 0..3
+    if constexpr (SC && BITS == 1) {
+#pragma unroll
+        for (int r = 0; r < RBW; ++r)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[r][i] = fmaf(cdiff, acc[r][i], c0s * accxs[r][i]);
+    }
 #pragma unroll
     for (int r = 0; r < RBW; ++r)
 #pragma unroll
