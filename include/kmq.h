@@ -19,6 +19,12 @@
  * everywhere.  For b in {1,2,4} the byte view of this stream is the paper's
  * uint8 element stream `Wq` with an LSB-first byte table.
  *
+ * BIT-WIDTHS.  b = 1, 2, 3, 4 everywhere.  b = 8 (256 centroids, the widest of the
+ * element formats of the paper's lookup-table kernel, Sec. 3.3 "Software formats") is
+ * accepted on the canonical layout by every product, fusion and dequantisation call
+ * and served by the shape-agnostic kernels; there is no tiled layout for it
+ * (KMQ_ERR_LAYOUT) and the quantiser does not produce it (KMQ_ERR_BITS).
+ *
  * General rules.  No function allocates, frees or synchronises.  Device entry
  * points enqueue on `hip_stream` (a hipStream_t passed as void*, NULL = the
  * null stream) and return; they are legal under stream capture.  The caller
@@ -41,7 +47,7 @@ typedef int32_t kmq_status;
 enum {
     KMQ_OK = 0,
     KMQ_ERR_NULL = 1,        /* a required pointer is NULL */
-    KMQ_ERR_BITS = 2,        /* bits not in {1,2,3,4} */
+    KMQ_ERR_BITS = 2,        /* bits not in {1,2,3,4,8} (the quantiser: {1,2,3,4}) */
     KMQ_ERR_SHAPE = 3,       /* N, K < 1, M outside 1..KMQ_MAX_BATCH, or size overflow */
     KMQ_ERR_ALIGN = 4,       /* pointer alignment (see each function) */
     KMQ_ERR_INDEX_RANGE = 5, /* kmq_pack: an index >= 2^bits */

@@ -64,7 +64,7 @@ double bf16_to_double(uint16_t h) {
     return static_cast<double>(f);
 }
 
-bool bits_ok(int bits) { return bits >= 1 && bits <= 4; }
+bool bits_ok(int bits) { return (bits >= 1 && bits <= 4) || bits == 8; }   // 8: a 256-entry codebook
 
 int64_t words_per_row(int bits, int64_t K) { return (K * bits + 31) / 32; }
 
@@ -222,7 +222,7 @@ int oracle_gemm_blockscaled(const uint32_t* packed, const uint16_t* codebook, co
 // The product of two bf16 values is exact in fp64, so this is one rounding (to nearest even).
 int oracle_dequant_blockscaled(const uint32_t* packed, const uint16_t* codebook, const uint16_t* scales,
                                int64_t N, int64_t K, int bits, int64_t B, uint16_t* Wd) {
-    if (!packed || !codebook || !scales || !Wd || bits < 1 || bits > 4 || N < 0 || K < 1 || B < 1 || K % B != 0) return 1;
+    if (!packed || !codebook || !scales || !Wd || !bits_ok(bits) || N < 0 || K < 1 || B < 1 || K % B != 0) return 1;
     const int64_t wpr = words_per_row(bits, K), G = K / B;
     for (int64_t n = 0; n < N; ++n)
         for (int64_t k = 0; k < K; ++k) {

@@ -230,7 +230,7 @@ kmq_status kmq_gemv_bf16(const uint16_t* W, const uint16_t* x, uint16_t* y, int6
 kmq_status kmq_quantize_rows(const uint16_t* Wdense, int64_t N, int64_t K, int bits, int iters,
                              uint32_t* packed, uint16_t* codebook, void* hip_stream) {
     if (!Wdense || !packed || !codebook) return KMQ_ERR_NULL;
-    if (!kmq::bits_valid(bits)) return KMQ_ERR_BITS;
+    if (!kmq::bits_valid(bits) || bits > 4) return KMQ_ERR_BITS;
     if (!kmq::dims_valid(N, K) || iters < 0 || N > 0x7FFFFFFF) return KMQ_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(Wdense) & 1) || (reinterpret_cast<uintptr_t>(codebook) & 1) ||
         (reinterpret_cast<uintptr_t>(packed) & 3)) return KMQ_ERR_ALIGN;
@@ -244,7 +244,7 @@ kmq_status kmq_quantize_blockscaled(const uint16_t* Wdense, int64_t N, int64_t K
                                     uint32_t* packed, uint16_t* codebook, uint16_t* scales,
                                     void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!Wdense || !packed || !codebook || !scales) return KMQ_ERR_NULL;
-    if (!kmq::bits_valid(bits)) return KMQ_ERR_BITS;
+    if (!kmq::bits_valid(bits) || bits > 4) return KMQ_ERR_BITS;
     if (!kmq::dims_valid(N, K) || iters < 0 || K % KMQ_BLOCK != 0 || N * (K / KMQ_BLOCK) > (int64_t(1) << 32))
         return KMQ_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(Wdense) & 1) || (reinterpret_cast<uintptr_t>(codebook) & 1) ||

@@ -120,6 +120,7 @@ hipError_t launch_dequant_blockscaled(const uint32_t* W, const uint16_t* codeboo
         case 1: hipLaunchKernelGGL(dequant_blockscaled_kernel<1>, grid, block, 0, s, W, codebook, scales, ngroups, Wd); break;
         case 2: hipLaunchKernelGGL(dequant_blockscaled_kernel<2>, grid, block, 0, s, W, codebook, scales, ngroups, Wd); break;
         case 3: hipLaunchKernelGGL(dequant_blockscaled_kernel<3>, grid, block, 0, s, W, codebook, scales, ngroups, Wd); break;
+        case 8: hipLaunchKernelGGL(dequant_blockscaled_kernel<8>, grid, block, 0, s, W, codebook, scales, ngroups, Wd); break;
         default: hipLaunchKernelGGL(dequant_blockscaled_kernel<4>, grid, block, 0, s, W, codebook, scales, ngroups, Wd); break;
     }
     return hipGetLastError();
@@ -143,6 +144,7 @@ hipError_t launch_blockscaled_generic(const GemmArgs& a, hipStream_t s) {
         case 1: return launch_blockscaled_bits<1>(a, s);
         case 2: return launch_blockscaled_bits<2>(a, s);
         case 3: return launch_blockscaled_bits<3>(a, s);
+        case 8: return launch_blockscaled_bits<8>(a, s);
         default: return launch_blockscaled_bits<4>(a, s);
     }
 }

@@ -40,10 +40,11 @@ __global__ __launch_bounds__(256) void gemv_fused_generic_kernel(
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t n = static_cast<int64_t>(blockIdx.x) * 4 + wave;
     const bool live = n < N;
-    if (live && lane < C) {
-        lut[wave][0][lane] = bf16_to_f32(codebook[n * C + lane]);
-        if constexpr (PAIR) lut[wave][1][lane] = bf16_to_f32(codebook2[n * C + lane]);
-    }
+    if (live)
+        for (int e = lane; e < C; e += kWave) {
+            lut[wave][0][e] = bf16_to_f32(codebook[n * C + e]);
+            if constexpr (PAIR) lut[wave][1][e] = bf16_to_f32(codebook2[n * C + e]);
+        }
     __syncthreads();
     if (!live) return;
 
@@ -92,6 +93,7 @@ hipError_t launch_fused_generic(const GemmArgs& a, hipStream_t s) {
         case 1: return launch_fused_bits<1>(a, s);
         case 2: return launch_fused_bits<2>(a, s);
         case 3: return launch_fused_bits<3>(a, s);
+        case 8: return launch_fused_bits<8>(a, s);
         default: return launch_fused_bits<4>(a, s);
     }
 }

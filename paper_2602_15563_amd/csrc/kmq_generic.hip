@@ -40,7 +40,8 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t n = static_cast<int64_t>(blockIdx.x) * 4 + wave;
     const bool live = n < N;
-    if (live && lane < C) lut[wave][lane] = bf16_to_f32(codebook[n * C + lane]);
+    if (live)
+        for (int e = lane; e < C; e += kWave) lut[wave][e] = bf16_to_f32(codebook[n * C + e]);
     __syncthreads();
     if (!live) return;
 
@@ -129,8 +130,9 @@ __global__ __launch_bounds__(256) void gemv_pair_generic_kernel(
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t n = static_cast<int64_t>(blockIdx.x) * 4 + wave;
     const bool live = n < N;
-    if (live && lane < 2 * C)
-        lut[wave][lane / C][lane % C] = bf16_to_f32((lane < C ? codebook : codebook2)[n * C + lane % C]);
+    if (live)
+        for (int e = lane; e < 2 * C; e += kWave)
+            lut[wave][e / C][e % C] = bf16_to_f32((e < C ? codebook : codebook2)[n * C + e % C]);
     __syncthreads();
     if (!live) return;
     const int64_t wpr = words_per_row(BITS, K);
@@ -162,6 +164,7 @@ hipError_t launch_pair_generic(const GemmArgs& a, hipStream_t s) {
         case 1: hipLaunchKernelGGL(gemv_pair_generic_kernel<1>, grid, block, 0, s, a.W, a.codebook, a.W2, a.codebook2, a.X, a.Y, a.N, a.K); break;
         case 2: hipLaunchKernelGGL(gemv_pair_generic_kernel<2>, grid, block, 0, s, a.W, a.codebook, a.W2, a.codebook2, a.X, a.Y, a.N, a.K); break;
         case 3: hipLaunchKernelGGL(gemv_pair_generic_kernel<3>, grid, block, 0, s, a.W, a.codebook, a.W2, a.codebook2, a.X, a.Y, a.N, a.K); break;
+        case 8: hipLaunchKernelGGL(gemv_pair_generic_kernel<8>, grid, block, 0, s, a.W, a.codebook, a.W2, a.codebook2, a.X, a.Y, a.N, a.K); break;
         default: hipLaunchKernelGGL(gemv_pair_generic_kernel<4>, grid, block, 0, s, a.W, a.codebook, a.W2, a.codebook2, a.X, a.Y, a.N, a.K); break;
     }
     return hipGetLastError();
@@ -185,17 +188,24 @@ __global__ __launch_bounds__(256) void dequant_kernel(
             const int64_t wi = g * BITS + j;
             w[j] = (layout == KMQ_LAYOUT_CANONICAL && wi < wpr) ? W[n * wpr + wi] : 0u;
         }
-        uint16_t c[C];
+        [[maybe_unused]] uint16_t c[BITS <= 4 ? C : 1];
+        if constexpr (BITS <= 4) {
 #pragma unroll
-        for (int j = 0; j < C; ++j) c[j] = codebook[n * C + j];
+            for (int j = 0; j < C; ++j) c[j] = codebook[n * C + j];
+        }
         const int64_t k0 = g << 5;
 #pragma unroll
         for (int e = 0; e < 32; ++e) {
             const uint32_t f = layout == KMQ_LAYOUT_CANONICAL ? group_field<BITS>(w, e)
                                                               : tiled_fetch_index(W, BITS, K, n, k0 + e);
-            uint16_t v = c[0];
+            uint16_t v;
+            if constexpr (BITS <= 4) {
+                v = c[0];
 #pragma unroll
-            for (int j = 1; j < C; ++j) v = f == static_cast<uint32_t>(j) ? c[j] : v;
+                for (int j = 1; j < C; ++j) v = f == static_cast<uint32_t>(j) ? c[j] : v;
+            } else {
+                v = codebook[n * C + f];     // 256 entries: read through the caches instead of held in registers
+            }
             if (k0 + e < K) Wd[n * K + k0 + e] = v;
         }
     }
@@ -268,6 +278,7 @@ hipError_t launch_generic(const GemmArgs& a, hipStream_t s) {
         case 1: return launch_generic_bits<1>(a, slices, s);
         case 2: return launch_generic_bits<2>(a, slices, s);
         case 3: return launch_generic_bits<3>(a, slices, s);
+        case 8: return launch_generic_bits<8>(a, slices, s);
         default: return launch_generic_bits<4>(a, slices, s);
     }
 }
@@ -282,6 +293,7 @@ hipError_t launch_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t*
         case 1: hipLaunchKernelGGL(dequant_kernel<1>, grid, block, 0, s, W, codebook, Wd, N, K, layout); break;
         case 2: hipLaunchKernelGGL(dequant_kernel<2>, grid, block, 0, s, W, codebook, Wd, N, K, layout); break;
         case 3: hipLaunchKernelGGL(dequant_kernel<3>, grid, block, 0, s, W, codebook, Wd, N, K, layout); break;
+        case 8: hipLaunchKernelGGL(dequant_kernel<8>, grid, block, 0, s, W, codebook, Wd, N, K, layout); break;
         default: hipLaunchKernelGGL(dequant_kernel<4>, grid, block, 0, s, W, codebook, Wd, N, K, layout); break;
     }
     return hipGetLastError();

@@ -134,7 +134,7 @@ const char* kmq_status_string(kmq_status s) {
     switch (s) {
         case KMQ_OK: return "ok";
         case KMQ_ERR_NULL: return "null pointer";
-        case KMQ_ERR_BITS: return "bits must be 1, 2, 3 or 4";
+        case KMQ_ERR_BITS: return "bits must be 1, 2, 3, 4 or 8";
         case KMQ_ERR_SHAPE: return "bad shape (N, K >= 1; 1 <= M <= 16)";
         case KMQ_ERR_ALIGN: return "misaligned pointer";
         case KMQ_ERR_INDEX_RANGE: return "index out of range for this bit-width";

@@ -16,7 +16,9 @@ namespace kmq {
 constexpr int64_t kMaxDim = int64_t(1) << 24;   // N and K are capped so N*K*bits cannot overflow
 constexpr int64_t kTileRows = 16;               // KMQ_LAYOUT_TILED: rows per block
 
-inline bool bits_valid(int bits) { return bits >= 1 && bits <= 4; }
+// 1..4 bits everywhere; 8 bits (a 256-entry codebook, one of the element widths of the paper's
+// lookup-table kernel, Sec. 3.3) on the canonical layout through the shape-agnostic kernels
+inline bool bits_valid(int bits) { return (bits >= 1 && bits <= 4) || bits == 8; }
 inline bool dims_valid(int64_t N, int64_t K) { return N >= 1 && K >= 1 && N <= kMaxDim && K <= kMaxDim; }
 KMQ_HD inline int64_t words_per_row(int bits, int64_t K) { return (K * bits + 31) >> 5; }
 inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
@@ -26,7 +28,7 @@ inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 // (4*gpg groups) of one row, stored as gpg*bits/4 dwords.
 KMQ_HD inline int tiled_groups_per_granule(int bits) { return bits == 1 ? 16 : bits == 2 ? 8 : 4; }
 KMQ_HD inline int64_t tiled_superblock_elems(int bits) { return 32 * tiled_groups_per_granule(bits); }
-KMQ_HD inline bool tiled_valid(int bits, int64_t K) { return K % tiled_superblock_elems(bits) == 0; }
+KMQ_HD inline bool tiled_valid(int bits, int64_t K) { return bits <= 4 && K % tiled_superblock_elems(bits) == 0; }
 
 // Dword offset in the tiled stream of the granule that holds element k of row n.
 KMQ_HD inline int64_t tiled_granule_dword(int bits, int64_t K, int64_t n, int64_t k) {
