@@ -463,6 +463,73 @@ def measured_traffic(workload: str):
     return None
 
 
+def run_large_batch(h: int = 8192, batches=(16, 64, 256), replays: int = 5):
+    """Batches above the fused kernels' range, by the route the paper recommends there (App. E
+    "Model benchmarks"): dequantise in a separate kernel (kmq_dequant_blockscaled), then a dense bf16
+    GEMM -- the GEMM is torch.matmul, i.e. the vendor library, used here as the stand-in for "any
+    dense GEMM" and timed alone as the unquantised baseline.  Block-scaled format, h x h, rotating
+    weights; eager launches timed with events on the launch stream (library GEMMs pick workspaces
+    at run time, so they are kept out of graphs)."""
+    import numpy as np
+    import torch
+
+    import oracle
+    from paper_2602_15563_amd import kmq, synth
+    rows = []
+    R = 3
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    Wd = [torch.empty((h, h), dtype=torch.bfloat16, device="cuda") for _ in range(R)]
+    dense = [(torch.randn((h, h), device="cuda", generator=g) * 0.02).to(torch.bfloat16) for _ in range(R)]
+    for bits in (4, 1):
+        wpr = h * bits // 32
+        Wp = [torch.randint(-2**31, 2**31, (h, wpr), dtype=torch.int32, device="cuda", generator=g) for _ in range(R)]
+        cb = _dev(synth.make_shared_codebook(5, bits, bits))
+        sc = [_dev(synth.make_scales(5, i, h, h)) for i in range(R)]
+        # the dequantised matrix of instance 0 against the oracle, first rows
+        kmq.dequant_blockscaled(Wp[0], cb, sc[0], Wd[0].view(torch.int16), h, h, bits)
+        torch.cuda.synchronize()
+        want = oracle.dequant_blockscaled(Wp[0][:8].cpu().numpy().view(np.uint32), synth.make_shared_codebook(5, bits, bits),
+                                          sc[0][:8].cpu().numpy().view(np.uint16), h, bits)
+        if not np.array_equal(Wd[0][:8].view(torch.int16).cpu().numpy().view(np.uint16), want):
+            raise SystemExit("bench: kmq_dequant_blockscaled does not match the oracle")
+        for M in batches:
+            X = torch.randn((M, h), device="cuda", generator=g).to(torch.bfloat16)
+            stream = torch.cuda.Stream()
+
+            def timed(fn, n):
+                with torch.cuda.stream(stream):
+                    for i in range(R):
+                        fn(i)
+                    stream.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    for i in range(n):
+                        fn(i % R)
+                    e1.record(stream)
+                    stream.synchronize()
+                return e0.elapsed_time(e1) * 1e3 / n
+
+            def route(i):
+                kmq.dequant_blockscaled(Wp[i], cb, sc[i], Wd[i].view(torch.int16), h, h, bits)
+                torch.matmul(X, Wd[i].t())
+            t_route = timed(route, 30 * replays)
+            t_deq = timed(lambda i: kmq.dequant_blockscaled(Wp[i], cb, sc[i], Wd[i].view(torch.int16), h, h, bits), 30 * replays)
+            t_gemm = timed(lambda i: torch.matmul(X, dense[i].t()), 30 * replays)
+            row = {"workload": f"paper_b{bits}s_{h}x{h}_m{M}_dequant_then_gemm", "us_route": round(t_route, 2),
+                   "us_dequant": round(t_deq, 2), "us_bf16_gemm": round(t_gemm, 2), "speedup_vs_bf16": round(t_gemm / t_route, 3)}
+            if M <= 16:
+                it = Instances(f"paper_b{bits}s_{h}x{h}_m16", M=M)
+                sec, n = time_workload(it, 2000, 50)
+                row["us_fused_tiled"] = round(sec / n * 1e6, 2)
+                row["fused_speedup_vs_bf16"] = round(t_gemm / row["us_fused_tiled"], 3)
+                del it
+            rows.append(row)
+        del Wp, sc
+        torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(inst: Instances):
     """The oracle, as it stands, single-threaded, on the same matrix."""
     import oracle
@@ -506,6 +573,8 @@ def main():
                          "traffic against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
     ap.add_argument("--sweep", action="store_true",
                     help="also run the 28-layer 1-bit decoder sweep at batch 1, 4 and 16 -> <out>/bench_sweep.json")
+    ap.add_argument("--large-batch", action="store_true",
+                    help="also time batches 16 / 64 / 256 at h = 8192 by dequantise + dense GEMM -> <out>/bench_large_batch.json")
     ap.add_argument("--table", action="store_true", help="also time every contract shape -> <out>/bench_table.json")
     ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out"), help="folder for bench_table.json")
     args = ap.parse_args()
@@ -605,6 +674,15 @@ def main():
         with open(os.path.join(args.out, "bench_sweep.json"), "w") as f:
             json.dump(rows, f, indent=1)
         out["config"]["decoder_sweep"] = rows
+
+    if args.large_batch:
+        rows = run_large_batch()
+        for r in rows:
+            print(json.dumps(r), file=sys.stderr, flush=True)
+        os.makedirs(args.out, exist_ok=True)
+        with open(os.path.join(args.out, "bench_large_batch.json"), "w") as f:
+            json.dump(rows, f, indent=1)
+        out["config"]["large_batch"] = rows
 
     print(json.dumps(out), flush=True)
 

@@ -259,7 +259,7 @@ kmq_status kmq_dequant_blockscaled(const uint32_t* W, const uint16_t* codebook, 
                                    uint16_t* Wdense, int64_t N, int64_t K, int bits, void* hip_stream) {
     if (!W || !codebook || !scales || !Wdense) return KMQ_ERR_NULL;
     if (!kmq::bits_valid(bits)) return KMQ_ERR_BITS;
-    if (!kmq::dims_valid(N, K) || K % KMQ_BLOCK != 0 || N * (K / 32) > (int64_t(1) << 38)) return KMQ_ERR_SHAPE;
+    if (!kmq::dims_valid(N, K) || K % KMQ_BLOCK != 0 || N * (K / 8) > (int64_t(1) << 39)) return KMQ_ERR_SHAPE;
     if ((reinterpret_cast<uintptr_t>(W) & 15) || (reinterpret_cast<uintptr_t>(codebook) & 3) ||
         (reinterpret_cast<uintptr_t>(scales) & 1) || (reinterpret_cast<uintptr_t>(Wdense) & 15)) return KMQ_ERR_ALIGN;
     return kmq::hip_status(kmq::launch_dequant_blockscaled(W, codebook, scales, Wdense, N, K, bits,

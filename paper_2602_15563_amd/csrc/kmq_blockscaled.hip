@@ -83,46 +83,51 @@ __global__ __launch_bounds__(256) void gemm_blockscaled_kernel(
 }
 
 // Dense weights of the format, Wd[n][k] = bf16( codebook[idx[n][k]] * scale[n][k / 64] ): one thread per
-// 32 elements (half a block).  The fp32 product of two bf16 values is exact, so the result carries one
-// rounding, to nearest even.
+// 8 consecutive elements, so that a wave's store is 1 KB of consecutive bytes.  The fp32 product of two
+// bf16 values is exact, so the result carries one rounding, to nearest even.
 template <int BITS>
 __global__ __launch_bounds__(256) void dequant_blockscaled_kernel(const uint32_t* __restrict__ W,
                                                                   const uint16_t* __restrict__ codebook,
-                                                                  const uint16_t* __restrict__ scales, int64_t ngroups,
-                                                                  uint16_t* __restrict__ Wd) {
+                                                                  const uint16_t* __restrict__ scales, int64_t nchunks,
+                                                                  int64_t total_words, uint16_t* __restrict__ Wd) {
     constexpr int C = 1 << BITS;
+    constexpr uint32_t mask = C - 1;
     __shared__ float lut[C];
     if (threadIdx.x < C) lut[threadIdx.x] = bf16_to_f32(codebook[threadIdx.x]);
     __syncthreads();
-    const int64_t g = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (g >= ngroups) return;
-    uint32_t w[2 * BITS];
+    const int64_t c8 = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;   // chunk of 8 elements, row-major over N x K/8
+    if (c8 >= nchunks) return;
+    // K % 64 == 0: rows are whole words, so the matrix is one bit stream and chunk c8 starts at bit c8 * 8 * BITS
+    const int64_t bit0 = c8 * (8 * BITS);
+    const int64_t wi = bit0 >> 5;
+    const int sh = static_cast<int>(bit0 & 31);
+    const uint64_t lo = W[wi], hi = wi + 1 < total_words ? W[wi + 1] : 0u;
+    const uint64_t v = (lo | (hi << 32)) >> sh;
+    const float s = bf16_to_f32(scales[c8 >> 3]);
+    uint32_t out[4];
 #pragma unroll
-    for (int j = 0; j < 2 * BITS; ++j) w[j] = j < BITS ? W[g * BITS + j] : 0u;   // this half block's words; fields never leave them
-    const float s = bf16_to_f32(scales[g >> 1]);
-    uint32_t out[16];
-#pragma unroll
-    for (int e = 0; e < 32; e += 2) {
-        const uint32_t lo = f32_to_bf16(lut[block_field<BITS>(w, e)] * s);
-        const uint32_t hi = f32_to_bf16(lut[block_field<BITS>(w, e + 1)] * s);
-        out[e >> 1] = lo | (hi << 16);
+    for (int e = 0; e < 8; e += 2) {
+        const uint32_t a = f32_to_bf16(lut[static_cast<uint32_t>(v >> (e * BITS)) & mask] * s);
+        const uint32_t b = f32_to_bf16(lut[static_cast<uint32_t>(v >> ((e + 1) * BITS)) & mask] * s);
+        out[e >> 1] = a | (b << 16);
     }
-    u32x4_t* dst = reinterpret_cast<u32x4_t*>(Wd + (g << 5));
-#pragma unroll
-    for (int q = 0; q < 4; ++q) dst[q] = u32x4_t{out[4 * q], out[4 * q + 1], out[4 * q + 2], out[4 * q + 3]};
+    // written once and read by a later kernel: no reason to keep it in this kernel's caches
+    __builtin_nontemporal_store(u32x4_t{out[0], out[1], out[2], out[3]}, reinterpret_cast<u32x4_t*>(Wd + (c8 << 3)));
 }
 
 hipError_t launch_dequant_blockscaled(const uint32_t* W, const uint16_t* codebook, const uint16_t* scales, uint16_t* Wd,
                                       int64_t N, int64_t K, int bits, hipStream_t s) {
-    const int64_t ngroups = N * (K / 32);
-    const dim3 grid(static_cast<unsigned>((ngroups + 255) / 256)), block(256);
+    const int64_t nchunks = N * (K / 8), words = N * (K * bits / 32);
+    const dim3 grid(static_cast<unsigned>((nchunks + 255) / 256)), block(256);
+#define KMQ_DQ(B) hipLaunchKernelGGL(dequant_blockscaled_kernel<B>, grid, block, 0, s, W, codebook, scales, nchunks, words, Wd)
     switch (bits) {
-        case 1: hipLaunchKernelGGL(dequant_blockscaled_kernel<1>, grid, block, 0, s, W, codebook, scales, ngroups, Wd); break;
-        case 2: hipLaunchKernelGGL(dequant_blockscaled_kernel<2>, grid, block, 0, s, W, codebook, scales, ngroups, Wd); break;
-        case 3: hipLaunchKernelGGL(dequant_blockscaled_kernel<3>, grid, block, 0, s, W, codebook, scales, ngroups, Wd); break;
-        case 8: hipLaunchKernelGGL(dequant_blockscaled_kernel<8>, grid, block, 0, s, W, codebook, scales, ngroups, Wd); break;
-        default: hipLaunchKernelGGL(dequant_blockscaled_kernel<4>, grid, block, 0, s, W, codebook, scales, ngroups, Wd); break;
+        case 1: KMQ_DQ(1); break;
+        case 2: KMQ_DQ(2); break;
+        case 3: KMQ_DQ(3); break;
+        case 8: KMQ_DQ(8); break;
+        default: KMQ_DQ(4); break;
     }
+#undef KMQ_DQ
     return hipGetLastError();
 }
 

@@ -211,6 +211,37 @@ __global__ __launch_bounds__(256) void dequant_kernel(
     }
 }
 
+// The same for the canonical layout with K % 8 == 0: one thread per 8 consecutive elements, one 16-byte
+// store per thread (a wave writes 1 KB of consecutive bytes, past the caches: the matrix is read by a later
+// kernel).  The row's centroids are read through the caches.
+template <int BITS>
+__global__ __launch_bounds__(256) void dequant_rows8_kernel(const uint32_t* __restrict__ W,
+                                                            const uint16_t* __restrict__ codebook,
+                                                            uint16_t* __restrict__ Wd, int64_t N, int64_t K) {
+    constexpr int C = 1 << BITS;
+    constexpr uint32_t mask = C - 1;
+    const int64_t cpr = K >> 3;                                   // chunks per row
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= N * cpr) return;
+    const int64_t n = i / cpr, c8 = i % cpr;
+    const int64_t wpr = words_per_row(BITS, K);
+    const int64_t bit0 = c8 * (8 * BITS);
+    const int64_t wi = bit0 >> 5;
+    const int sh = static_cast<int>(bit0 & 31);
+    const uint32_t* row = W + n * wpr;
+    const uint64_t lo = row[wi], hi = wi + 1 < wpr ? row[wi + 1] : 0u;
+    const uint64_t v = (lo | (hi << 32)) >> sh;
+    const uint16_t* c = codebook + n * C;
+    uint32_t out[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+        const uint32_t a = c[static_cast<uint32_t>(v >> (e * BITS)) & mask];
+        const uint32_t b = c[static_cast<uint32_t>(v >> ((e + 1) * BITS)) & mask];
+        out[e >> 1] = a | (b << 16);
+    }
+    __builtin_nontemporal_store(u32x4_t{out[0], out[1], out[2], out[3]}, reinterpret_cast<u32x4_t*>(Wd + n * K + (c8 << 3)));
+}
+
 // Measurement aid: reads `nvec` 16-byte vectors once with the same access shape
 // as the GEMV kernels (four 1 KB wave-loads in flight per wave) and keeps
 // nothing; `sink` is written only if the xor of all data equals a magic value.
@@ -285,6 +316,19 @@ hipError_t launch_generic(const GemmArgs& a, hipStream_t s) {
 
 hipError_t launch_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd, int64_t N,
                           int64_t K, int bits, int layout, hipStream_t s) {
+    if (layout == KMQ_LAYOUT_CANONICAL && (K & 7) == 0 && (reinterpret_cast<uintptr_t>(Wd) & 15) == 0 &&
+        N * (K >> 3) <= (int64_t(1) << 38)) {                  // one workgroup per 256 chunks must fit the grid
+        const int64_t chunks = N * (K >> 3);
+        const dim3 grid8(static_cast<unsigned>((chunks + 255) / 256)), block8(256);
+        switch (bits) {
+            case 1: hipLaunchKernelGGL(dequant_rows8_kernel<1>, grid8, block8, 0, s, W, codebook, Wd, N, K); break;
+            case 2: hipLaunchKernelGGL(dequant_rows8_kernel<2>, grid8, block8, 0, s, W, codebook, Wd, N, K); break;
+            case 3: hipLaunchKernelGGL(dequant_rows8_kernel<3>, grid8, block8, 0, s, W, codebook, Wd, N, K); break;
+            case 8: hipLaunchKernelGGL(dequant_rows8_kernel<8>, grid8, block8, 0, s, W, codebook, Wd, N, K); break;
+            default: hipLaunchKernelGGL(dequant_rows8_kernel<4>, grid8, block8, 0, s, W, codebook, Wd, N, K); break;
+        }
+        return hipGetLastError();
+    }
     const int64_t total = N * ((K + 31) >> 5);
     int64_t blocks = (total + 255) / 256;
     if (blocks > 65536) blocks = 65536;
