@@ -213,7 +213,8 @@ __device__ __forceinline__ void load_words(const uint32_t* p, uint32_t (&w)[G]) 
     if constexpr (G == 1) {
         w[0] = __builtin_nontemporal_load(p);
     } else if constexpr (G == 3) {
-        const V v = *reinterpret_cast<const V*>(p);
+        typedef u32x3_t __attribute__((aligned(4))) u32x3_a4_t;      // 12-byte slices sit 4-byte aligned
+        const u32x3_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x3_a4_t*>(p));
 #pragma unroll
         for (int j = 0; j < G; ++j) w[j] = v[j];
     } else {
