@@ -391,7 +391,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
             int64_t row = wave_row0 + t * RPL + sub;
             row = row < N ? row : N - 1;
 #pragma unroll
-            for (int i = 0; i < NSC; ++i) sv[t][i] = scales[row * (K / KMQ_BLOCK) + blk0 + i];
+            for (int i = 0; i < NSC; ++i) sv[t][i] = __builtin_nontemporal_load(&scales[row * (K / KMQ_BLOCK) + blk0 + i]);
         }
     }
     asm volatile("" ::: "memory");
