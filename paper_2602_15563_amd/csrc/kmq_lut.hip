@@ -283,6 +283,15 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     static_assert(!SC || EL % KMQ_BLOCK == 0 || KMQ_BLOCK % EL == 0, "lane slices must not straddle blocks");
     static_assert(!SC || NSC == 1 || (BITS == 1 && NSC == 2), "block sums kept by the pipeline");
 
+    // Staged x is swizzled per lane slice so that a wave's 16-byte reads spread over the banks: chunk q of
+    // slice sl sits at position q ^ (sl mod C16) when C16 is a power of two (one XOR per read address),
+    // else at (q + sl) mod C16.
+    constexpr bool C16_POW2 = (C16 & (C16 - 1)) == 0;
+    auto swz = [](int q, int sl) -> int {
+        if constexpr (C16_POW2) return q ^ (sl & (C16 - 1));
+        else return (q + sl) % C16;
+    };
+
     struct alignas(256) Smem {
         // 2/4-bit: per wave and row group, RS tables of 16 x 4 B; 1-bit: lut[0] holds the 16 x 8 B mask table
         uint32_t lut[LUT_GROUPS][TBL];
@@ -394,6 +403,17 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
             for (int i = 0; i < NSC; ++i) sv[t][i] = __builtin_nontemporal_load(&scales[row * (K / KMQ_BLOCK) + blk0 + i]);
         }
     }
+    // where this lane will read its slice of x from: computed now, while the loads are in flight,
+    // and pinned here so that it is not scheduled behind the wait for x
+    int xidx[C16];
+    {
+        const int sl = wk * LPR + pos;
+#pragma unroll
+        for (int q = 0; q < C16; ++q) {
+            xidx[q] = sl * C16 + swz(q, sl);
+            asm volatile("" : "+v"(xidx[q]));
+        }
+    }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
 
@@ -421,7 +441,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     for (int h = 0; h < XPT; ++h) {
         const int c = threadIdx.x * XPT + h;
         const int sl = c / C16, q = c % C16;
-        sm.xs[sl * C16 + (q + sl) % C16] = u32x4_t{xt[4 * h], xt[4 * h + 1], xt[4 * h + 2], xt[4 * h + 3]};
+        sm.xs[sl * C16 + swz(q, sl)] = u32x4_t{xt[4 * h], xt[4 * h + 1], xt[4 * h + 2], xt[4 * h + 3]};
     }
     if constexpr (BITS == 1) {
         if (threadIdx.x < 16) {
@@ -437,10 +457,9 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     // ---- 4. this lane's activations into registers ---------------------------------------------
     uint32_t xr[XR];
     {
-        const int sl = wk * LPR + pos;
 #pragma unroll
         for (int q = 0; q < C16; ++q) {
-            const u32x4_t v = sm.xs[sl * C16 + (q + sl) % C16];
+            const u32x4_t v = sm.xs[xidx[q]];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if constexpr (BITS == 4) {
