@@ -53,6 +53,12 @@ WORKLOADS = {
     "paper_b4s_8192x8192_m16": (4, 8192, 8192, 16, 5, 0, False, True),
     "paper_b1s_8192x8192_m16": (1, 8192, 8192, 16, 6, 0, False, True),
 }
+TABLE_WORKLOADS = list(WORKLOADS)      # what --table times: the contract's shapes and the paper's h = 8192 rows
+# the rest of the paper's micro-benchmark grid (square h x h, block-scaled format), used by --micro-sweep
+for _h in (2048, 4096, 8192):
+    for _b, _seed in ((4, 5), (2, 7), (1, 6)):
+        WORKLOADS.setdefault(f"paper_b{_b}s_{_h}x{_h}_m1", (_b, _h, _h, 1, _seed, 0, False, True))
+        WORKLOADS.setdefault(f"paper_b{_b}s_{_h}x{_h}_m16", (_b, _h, _h, 16, _seed, 0, False, True))
 # The paper's published numbers for those two workloads (App. E, table "perf_micro_m1_impl":
 # Triton kernels on an NVIDIA L40S, 864 GB/s): effective GB/s, us per call.
 PAPER_NUMBERS = {"paper_b4s_8192x8192_m1": (721.0, 49.5), "paper_b1s_8192x8192_m1": (438.0, 24.0)}
@@ -530,6 +536,64 @@ def run_large_batch(h: int = 8192, batches=(16, 64, 256), replays: int = 5):
     return rows
 
 
+def run_micro_sweep():
+    """The paper's micro-benchmark grid on this machine (App. E "Micro-benchmarks": square h x h products swept
+    over batch, hidden size and bit-width, figure only): block-scaled format, h in {2048, 4096, 8192}, bits in
+    {4, 2, 1}, batch 1 (canonical layout, against the dense bf16 GEMV) and batch 16 (tiled layout, against the
+    vendor library's bf16 GEMM through torch.matmul), with the paper's roofline model evaluated beside each."""
+    import torch
+
+    from paper_2602_15563_amd import model
+    nu = 2.5e15 / (HBM_PEAK_GBS * 1e9)
+    rows = []
+    for h in (2048, 4096, 8192):
+        base1 = time_bf16_baseline(h, h, 2000)["us_per_call"]
+        g = torch.Generator(device="cuda")
+        g.manual_seed(11)
+        R = max(2, -(-2 * LLC_BYTES // (2 * h * h)))
+        Wd = [(torch.randn((h, h), device="cuda", generator=g) * 0.02).to(torch.bfloat16) for _ in range(R)]
+        X = torch.randn((16, h), device="cuda", generator=g).to(torch.bfloat16)
+        # the library GEMM replayed from a graph like everything else here (its results are not used: eager
+        # launches of it are bound by the host at these sizes, which would flatter the comparison)
+        Yb = [torch.empty((16, h), dtype=torch.bfloat16, device="cuda") for _ in range(R)]
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            for i in range(R):
+                torch.matmul(X, Wd[i].t(), out=Yb[i])
+            stream.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                for i in range(CALLS_PER_GRAPH):
+                    torch.matmul(X, Wd[i % R].t(), out=Yb[i % R])
+            graph.replay()
+            stream.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(10):
+                graph.replay()
+            e1.record(stream)
+            stream.synchronize()
+        base16 = e0.elapsed_time(e1) * 1e3 / (10 * CALLS_PER_GRAPH)
+        del graph, Yb
+        del Wd
+        torch.cuda.empty_cache()
+        for bits in (4, 2, 1):
+            for M, base in ((1, base1), (16, base16)):
+                it = Instances(f"paper_b{bits}s_{h}x{h}_m{M}")
+                w = it.check()
+                sec, n = time_workload(it, 3000, 100)
+                us = sec / n * 1e6
+                rows.append({"h": h, "bits": bits, "P_w": bits + 0.25, "batch": M, "kernel": it.kernel,
+                             "us_per_call": round(us, 3), "GBps": round(it.bytes / us * 1e-3, 1),
+                             "us_bf16": round(base, 3), "speedup_vs_bf16": round(base / us, 2),
+                             "model_max_speedup": round(model.speedup(16.0, bits + 0.25, M, nu), 2),
+                             "max_err_over_A": float(f"{w:.3e}")})
+                print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+                del it
+                torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(inst: Instances):
     """The oracle, as it stands, single-threaded, on the same matrix."""
     import oracle
@@ -573,6 +637,8 @@ def main():
                          "traffic against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
     ap.add_argument("--sweep", action="store_true",
                     help="also run the 28-layer 1-bit decoder sweep at batch 1, 4 and 16 -> <out>/bench_sweep.json")
+    ap.add_argument("--micro-sweep", action="store_true",
+                    help="also run the paper's micro-benchmark grid (h x bits x batch 1 / 16) -> <out>/bench_micro_sweep.json")
     ap.add_argument("--large-batch", action="store_true",
                     help="also time batches 16 / 64 / 256 at h = 8192 by dequantise + dense GEMM -> <out>/bench_large_batch.json")
     ap.add_argument("--table", action="store_true", help="also time every contract shape -> <out>/bench_table.json")
@@ -648,7 +714,7 @@ def main():
 
     if args.table:
         rows = []
-        for name in WORKLOADS:
+        for name in TABLE_WORKLOADS:
             it = Instances(name)
             w = it.check()
             s, n = time_workload(it, 5000, 100)
@@ -674,6 +740,13 @@ def main():
         with open(os.path.join(args.out, "bench_sweep.json"), "w") as f:
             json.dump(rows, f, indent=1)
         out["config"]["decoder_sweep"] = rows
+
+    if args.micro_sweep:
+        rows = run_micro_sweep()
+        os.makedirs(args.out, exist_ok=True)
+        with open(os.path.join(args.out, "bench_micro_sweep.json"), "w") as f:
+            json.dump(rows, f, indent=1)
+        out["config"]["micro_sweep"] = rows
 
     if args.large_batch:
         rows = run_large_batch()
