@@ -181,3 +181,49 @@ def test_workspace_bytes_split_k():
     assert kmq.workspace_bytes(600, 16384, 2, 2) == 0       # enough rows
     assert kmq.workspace_bytes(8, 4100, 2, 2) == 0          # short rows
     assert kmq.workspace_bytes(16, 65536, 2, 2, 1) == 0     # tiled layout: matrix-core kernel
+
+
+def test_argument_errors_of_the_later_calls_and_the_size_limits():
+    """Fused decoder calls, quantiser, block-scaled dequantisation: host-side checks only, nothing is launched."""
+    lib = kmq.raw()
+    buf = (ctypes.c_uint8 * 8192)()
+    a16 = (ctypes.addressof(buf) + 15) & ~15
+    W, cb, x, y, g, res, sc, ws = a16, a16 + 256, a16 + 512, a16 + 1024, a16 + 1536, a16 + 2048, a16 + 2560, a16 + 3072
+    f32 = ctypes.c_float
+
+    def fused(W=W, x=x, norm=1, g=g, eps=1e-5, res=res, y=y, N=4, K=64, bits=2, layout=0):
+        return lib.kmq_gemv_fused(W, cb, x, norm, g, f32(eps), res, y, N, K, bits, layout, None)
+
+    assert fused(W=None) == 1 and fused(x=None) == 1 and fused(y=None) == 1
+    assert fused(bits=6) == 2 and fused(N=0) == 3 and fused(eps=-1.0) == 3 and fused(norm=2) == 3
+    assert fused(layout=1) == 7 and fused(g=g + 2) == 4 and fused(res=res + 1) == 4
+    assert fused(norm=0, eps=-1.0, g=None, res=None, N=0) == 3            # still a bad shape
+    assert lib.kmq_gemv_swiglu_rmsnorm(W, cb, None, cb, x, g, f32(1e-5), y, 4, 64, 2, 0, None) == 1
+    assert lib.kmq_gemv_swiglu_rmsnorm(W, cb, W, cb, x, g, f32(1e-5), y, 4, 64, 2, 1, None) == 7
+    assert kmq.kernel_name_fused(8192, 3072, 1).startswith("lut_b1") and kmq.kernel_name_fused(8, 100, 3) == "fused_generic"
+    assert kmq.kernel_name_fused(8, 100, 7) == "invalid"
+
+    def qrows(Wd=W, N=4, K=64, bits=2, iters=3, packed=x, cbk=cb):
+        return lib.kmq_quantize_rows(Wd, N, K, bits, iters, packed, cbk, None)
+
+    assert qrows(Wd=None) == 1 and qrows(bits=8) == 2 and qrows(bits=0) == 2 and qrows(iters=-1) == 3 and qrows(K=0) == 3
+    assert qrows(packed=x + 2) == 4 and qrows(Wd=W + 1) == 4
+    need = kmq.quantize_blockscaled_workspace_bytes()
+    assert need > 0 and need % 8 == 0
+
+    def qbs(Wd=W, N=4, K=64, bits=2, iters=3, ws=ws, wsb=need, scales=sc):
+        return lib.kmq_quantize_blockscaled(Wd, N, K, bits, iters, x, cb, scales, ws, wsb, None)
+
+    assert qbs(scales=None) == 1 and qbs(bits=8) == 2 and qbs(K=96) == 3 and qbs(ws=None) == 6 and qbs(wsb=need - 1) == 6
+    assert qbs(ws=ws + 4) == 4
+    assert lib.kmq_dequant_blockscaled(W, cb, None, y, 4, 64, 2, None) == 1
+    assert lib.kmq_dequant_blockscaled(W, cb, sc, y, 4, 96, 2, None) == 3
+    assert lib.kmq_dequant_blockscaled(W, cb, sc, y + 2, 4, 64, 2, None) == 4
+    # size limits: N and K up to 2^24 each
+    top = 1 << 24
+    assert kmq.words_per_row(4, top) == top // 8 and kmq.words_per_row(8, top) == top // 4
+    assert lib.kmq_words_per_row(4, top + 1) == -1
+    assert lib.kmq_gemv(W, cb, x, y, top + 1, 64, 2, 0, None, 0, None) == 3
+    assert lib.kmq_gemv(W, cb, x, y, 4, top + 1, 2, 0, None, 0, None) == 3
+    assert kmq.kernel_name(top, 4096, 2, 1).startswith("lut_b2") and kmq.kernel_name(top + 1, 4096, 2, 1) == "invalid"
+    assert kmq.workspace_bytes(1, top, 2, 16) == 64 * 16 * 1 * 4
