@@ -35,6 +35,7 @@ enum Variant {
     kVariantLut,         // batch 1, 1/2/4-bit, K from a table: hand-scheduled LDS-table kernel
     kVariantMfma,        // tiled layout, batch 1..16: matrix-core kernel
     kVariantBlockGeneric,  // block-scaled format, any shape with K % 64 == 0
+    kVariantPerColumn,     // canonical layout, batch 2..4, shape with a batch-1 table kernel: that kernel once per batch column
 };
 
 struct Plan {

@@ -227,3 +227,13 @@ def test_argument_errors_of_the_later_calls_and_the_size_limits():
     assert lib.kmq_gemv(W, cb, x, y, 4, top + 1, 2, 0, None, 0, None) == 3
     assert kmq.kernel_name(top, 4096, 2, 1).startswith("lut_b2") and kmq.kernel_name(top + 1, 4096, 2, 1) == "invalid"
     assert kmq.workspace_bytes(1, top, 2, 16) == 64 * 16 * 1 * 4
+
+
+def test_per_column_choice_follows_the_cost_model():
+    assert kmq.kernel_name(9216, 3072, 1, 4).startswith("lut_b1")          # table kernel per column
+    assert kmq.kernel_name(14336, 4096, 2, 4).startswith("lut_b2")
+    assert kmq.kernel_name(4096, 4096, 4, 4) == "generic"                   # small 4-bit matrix: one pass of the generic kernel is cheaper
+    assert kmq.kernel_name(9216, 3072, 1, 5) == "generic" and kmq.kernel_name(9216, 3072, 1, 16) == "generic"
+    assert kmq.kernel_name(100, 515, 2, 2) == "generic"                     # no table kernel for this K
+    assert kmq.kernel_name_blockscaled(8192, 8192, 4, 4).startswith("lut_sc_b4")
+    assert kmq.kernel_name_blockscaled(8192, 8192, 4, 8) == "blockscaled_generic"

@@ -232,3 +232,25 @@ def test_degenerate_inputs(gpu):
         p = kmq.pack(idx, bits)
         Yg = gpu.run_gemm(gpu.dev(p), gpu.dev(cb), X[0], N, K, bits)
         gpu.check_against_oracle(Yg, p, cb, X, K, bits, label="all-max indices")
+
+
+@pytest.mark.parametrize("bits,N,K,M", [(1, 9216, 3072, 4), (1, 300, 3072, 2), (2, 1000, 4096, 3), (2, 333, 14336, 4),
+                                        (4, 4096, 4096, 2), (4, 77, 8192, 4), (1, 64, 8192, 3)])
+def test_small_batches_on_the_canonical_layout_per_column(gpu, bits, N, K, M):
+    """Batches 2..4 on the canonical layout may run the batch-1 table kernel once per column (a cost model in
+    the heuristic decides): whatever is chosen must match the oracle, and a per-column result is the batch-1
+    result of each column bit for bit."""
+    from paper_2602_15563_amd import kmq
+    seed = 900 + bits + M
+    idx = synth.make_indices(seed, 0, N, K, bits)
+    cb = synth.make_codebook(seed, 0, N, bits, symmetric=(bits == 1))
+    X = synth.make_x(seed, 0, M, K)
+    packed = oracle.pack(idx, bits)
+    name = kmq.kernel_name(N, K, bits, M)
+    Wd, cbd = gpu.dev(packed), gpu.dev(cb)
+    Yg = gpu.run_gemm(Wd, cbd, X, N, K, bits)
+    ranges = gpu.sample_ranges(N, seed)
+    gpu.check_against_oracle(Yg, packed, cb, X, K, bits, row_ranges=ranges, label=f"b{bits} {N}x{K} M{M} ({name})")
+    if name.startswith("lut_"):
+        for m in range(M):
+            assert np.array_equal(Yg[m], gpu.run_gemm(Wd, cbd, X[m], N, K, bits)[0])
