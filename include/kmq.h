@@ -259,6 +259,7 @@ kmq_status kmq_quantize_rows(const uint16_t* Wdense, int64_t N, int64_t K, int b
  * magnitude of block g of row n (blocks of KMQ_BLOCK elements along K; itself a bf16 value),
  * normalised weight v = w / scale in fp64 (0 where the scale is 0), ONE clustering over all
  * N*K normalised weights with lo = -1, hi = 1.
+ *   Wdense    N x K bf16, row-major, 16-byte aligned for this call
  *   packed    N * K * bits / 32 words out; codebook 2^bits bf16 out; scales N x K/KMQ_BLOCK bf16 out
  *   workspace device memory of kmq_quantize_blockscaled_workspace_bytes() bytes, 8-byte aligned
  *             (partial sums of the clustering rounds; contents undefined before and after)

@@ -277,7 +277,7 @@ kmq_status kmq_quantize_blockscaled(const uint16_t* Wdense, int64_t N, int64_t K
     if (!kmq::bits_valid(bits) || bits > 4) return KMQ_ERR_BITS;
     if (!kmq::dims_valid(N, K) || iters < 0 || K % KMQ_BLOCK != 0 || N * (K / KMQ_BLOCK) > (int64_t(1) << 32))
         return KMQ_ERR_SHAPE;
-    if ((reinterpret_cast<uintptr_t>(Wdense) & 1) || (reinterpret_cast<uintptr_t>(codebook) & 1) ||
+    if ((reinterpret_cast<uintptr_t>(Wdense) & 15) || (reinterpret_cast<uintptr_t>(codebook) & 1) ||
         (reinterpret_cast<uintptr_t>(scales) & 1) || (reinterpret_cast<uintptr_t>(packed) & 3) ||
         (reinterpret_cast<uintptr_t>(workspace) & 7)) return KMQ_ERR_ALIGN;
     if (!workspace || workspace_bytes < kmq::quantize_blockscaled_workspace_bytes()) return KMQ_ERR_WORKSPACE;

@@ -58,7 +58,7 @@ template <int C>
 struct Clusters {
     double b[C > 1 ? C - 1 : 1];   // boundaries
     double s[C];
-    long long n[C];
+    int n[C];                      // per lane: at most a few thousand members, widened when lanes are added up
     __device__ __forceinline__ void begin(const double* c) {
 #pragma unroll
         for (int i = 0; i + 1 < C; ++i) b[i] = 0.5 * (c[i] + c[i + 1]);
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t* __re
 #pragma unroll
         for (int j = 0; j < C; ++j) {
             const double s = wave_sum(cl.s[j]);
-            const long long m = wave_sum(cl.n[j]);
+            const long long m = wave_sum(static_cast<long long>(cl.n[j]));
             if (lane == 0) { ps[wave][j] = s; pn[wave][j] = m; }
         }
         __syncthreads();
@@ -231,12 +231,22 @@ __global__ __launch_bounds__(256) void bs_lloyd_pass_kernel(const uint16_t* __re
     for (int j = 0; j < C; ++j) c[j] = q->cent[j];
     Clusters<C> cl;
     cl.begin(c);
-    for (int64_t blk = static_cast<int64_t>(blockIdx.x) * 4 + wave; blk < nblocks; blk += static_cast<int64_t>(gridDim.x) * 4)
-        cl.add(normalised(W[blk * KMQ_BLOCK + lane], scales[blk]));
+    // a lane takes 8 consecutive elements (one 16-byte load; eight lanes share a block's scale), a wave 8 blocks
+    const int64_t nchunks = nblocks * (KMQ_BLOCK / 8);
+    for (int64_t c = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * kWave + lane; c < nchunks;
+         c += static_cast<int64_t>(gridDim.x) * 4 * kWave) {
+        const u32x4_t w8 = *reinterpret_cast<const u32x4_t*>(W + c * 8);
+        const uint32_t scale = scales[c >> 3];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            cl.add(normalised(w8[e] & 0xFFFFu, scale));
+            cl.add(normalised(w8[e] >> 16, scale));
+        }
+    }
 #pragma unroll
     for (int j = 0; j < C; ++j) {
         const double s = wave_sum(cl.s[j]);
-        const long long m = wave_sum(cl.n[j]);
+        const long long m = wave_sum(static_cast<long long>(cl.n[j]));
         if (lane == 0) { ps[wave][j] = s; pn[wave][j] = m; }
     }
     __syncthreads();
@@ -309,7 +319,7 @@ static hipError_t quantize_blockscaled_bits(const uint16_t* W, int64_t N, int64_
                                             uint16_t* codebook, uint16_t* scales, QuantScratch* q, hipStream_t s) {
     constexpr int C = 1 << BITS;
     const int64_t nblocks = N * (K / KMQ_BLOCK), ngroups = nblocks * 2;
-    const int64_t want = (nblocks + 3) / 4;
+    const int64_t want = (nblocks + 31) / 32;          // a wave takes 8 blocks at a time
     const int partials = static_cast<int>(want < kQuantPartials ? want : kQuantPartials);
     hipLaunchKernelGGL(bs_scales_kernel, dim3(static_cast<unsigned>((nblocks + 3) / 4)), dim3(256), 0, s, W, nblocks, scales, q, C);
     for (int t = 0; t < iters; ++t) {
