@@ -343,6 +343,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     xwide_t xt;
     [[maybe_unused]] xwide_t gt;                   // RMSNorm weights of the same elements
     [[maybe_unused]] uint16_t resv[2];             // residual of the two rows this thread stores
+    [[maybe_unused]] uint32_t ccv[2];              // 1-bit: centroid pair of the two rows this thread stores
     {
         int c = threadIdx.x * XPT;
         c = c < XCHUNKS ? c : XCHUNKS - XPT;
@@ -354,6 +355,16 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
                 int64_t row = wg_row0 + (threadIdx.x * 2 + h) % ROWS_WG;
                 row = row < N ? row : N - 1;
                 resv[h] = residual[row];
+            }
+        }
+        if constexpr (BITS == 1 && !SC) {
+            // the two centroids of the rows this thread stores: the epilogue's closed form needs them, and a
+            // load issued there would put a whole memory latency behind the last reduction
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                int64_t row = wg_row0 + (threadIdx.x * 2 + h) % ROWS_WG;
+                row = row < N ? row : N - 1;
+                ccv[h] = *reinterpret_cast<const uint32_t*>(cbrow(row));
             }
         }
     }
@@ -606,9 +617,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
                 float sx = 0.f;
 #pragma unroll
                 for (int k = 0; k < NWK; ++k) sx += sm.sxp[k];
-                int64_t row = wg_row0 + rl;
-                row = row < N ? row : N - 1;
-                const uint32_t cc = *reinterpret_cast<const uint32_t*>(cbrow(row));
+                const uint32_t cc = ccv[h];
                 const float c0 = bf16_to_f32(cc & 0xFFFFu), c1 = bf16_to_f32(cc >> 16);
                 s = fmaf(c1 - c0, s, c0 * sx);
             }
