@@ -93,6 +93,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
         // done with them the same memory holds its RBW partial 16x16 tiles ([n][m], 1 KB each)
         u32x4_t xstage[NWK][16 * 17];
         float redx[BITS == 1 ? NWK : 1][16];                // 1-bit: partial sum_k x per batch column
+        uint32_t cpair[BITS == 1 ? RBW * 16 : 1];           // 1-bit: the rows' centroid pairs, fetched at the start for the epilogue
         // block-scaled: scales of the workgroup's rows, [row block][K block][row in block]
         // (kept as bf16: an fp32 table saves four conversions per tile and block but doubles the
         // staging writes and the footprint, and measured slower)
@@ -118,6 +119,14 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
             m[0] = ((e & 1u) ? 0x3F80u : 0u) | ((e & 2u) ? 0x3F800000u : 0u);
             m[1] = ((e & 4u) ? 0x3F80u : 0u) | ((e & 8u) ? 0x3F800000u : 0u);
             sm.masks[e] = m;
+        }
+        if constexpr (!SC) {
+            // a load issued in the epilogue would put a whole memory latency behind the last reduction
+            if (threadIdx.x < RBW * 16) {
+                int64_t row = rb0 * 16 + threadIdx.x;
+                row = row < N ? row : N - 1;
+                sm.cpair[threadIdx.x] = *reinterpret_cast<const uint32_t*>(codebook + row * 2);
+            }
         }
     } else if constexpr (BITS == 4) {
         for (int i = threadIdx.x; i < RBW * 16 * C; i += THREADS) {
@@ -387,7 +396,8 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
                 float sx = 0.f;
 #pragma unroll
                 for (int k = 0; k < NWK; ++k) sx += sm.redx[k][m];
-                const float c0 = bf16_to_f32(codebook[row * 2]), c1 = bf16_to_f32(codebook[row * 2 + 1]);
+                const uint32_t cc = sm.cpair[nl];
+                const float c0 = bf16_to_f32(cc & 0xFFFFu), c1 = bf16_to_f32(cc >> 16);
                 s = fmaf(c1 - c0, s, c0 * sx);
             }
             Y[static_cast<int64_t>(m) * N + row] = f32_to_bf16(s);
