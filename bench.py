@@ -642,7 +642,7 @@ def main():
     ap.add_argument("--large-batch", action="store_true",
                     help="also time batches 16 / 64 / 256 at h = 8192 by dequantise + dense GEMM -> <out>/bench_large_batch.json")
     ap.add_argument("--table", action="store_true", help="also time every contract shape -> <out>/bench_table.json")
-    ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out"), help="folder for bench_table.json")
+    ap.add_argument("--out", default=os.path.join(ROOT, "bench_out"), help="folder for the json files of --table, --sweep, --micro-sweep and --large-batch")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on exactly one GPU (--gpus 1); "

@@ -270,7 +270,6 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
 #pragma unroll
                 for (int cc = 0; cc < CPG; ++cc) {
                     // this chunk: registers -> LDS tile -> B fragments; chunk + kXAhead: global -> registers
-                    constexpr int slot_dummy = 0; (void)slot_dummy;
                     const int slot = (p * CPG + cc) % kXAhead;
 #pragma unroll
                     for (int i = 0; i < 4; ++i) xtile[(4 * i + q) * 17 + n] = xg[slot][i];
