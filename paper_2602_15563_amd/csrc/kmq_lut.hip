@@ -718,13 +718,17 @@ static const LutEntry kLut[] = {
     KMQ_LUT(2, 4, 32, 1, 4, 2, 6),   // K = 2048
     KMQ_LUT(2, 3, 64, 1, 4, 2, 6),   // K = 3072
     KMQ_LUT(2, 4, 64, 1, 4, 2, 7),   // K = 4096
-    KMQ_LUT(2, 4, 64, 2, 2, 2, 7),   // K = 8192
-    KMQ_LUT(2, 2, 64, 7, 1, 4, 7),   // K = 14336 (8 rows per wave: no faster; 14-wave workgroups: slower)
+    KMQ_LUT(2, 4, 64, 2, 2, 4, 4),   // K = 8192: 16 rows per workgroup (x, staged once per workgroup, is 16 KB here)
+    KMQ_LUT(2, 4, 64, 2, 2, 2, 7),   //            8
+    KMQ_LUT(2, 4, 32, 7, 1, 4, 4),   // K = 14336: 16-byte loads, 8 rows per workgroup (6.6 us on 4096 rows; 7.1 with 3 or 8 rows per wave)
+    KMQ_LUT(2, 2, 64, 7, 1, 4, 7),   //            8-byte loads, 4 rows per workgroup (7.05 us; taken for few rows)
     // 4-bit
     KMQ_LUT(4, 4, 64, 1, 4, 2, 6),   // K = 2048
     KMQ_LUT(4, 4, 64, 2, 2, 2, 6),   // K = 4096
-    KMQ_LUT(4, 4, 64, 4, 1, 2, 6),   // K = 8192
-    KMQ_LUT(4, 4, 64, 7, 1, 2, 6),   // K = 14336
+    KMQ_LUT(4, 4, 64, 4, 1, 4, 4),   // K = 8192: 4 rows per workgroup (4096 rows: 6.6 us; 7.0 with 2 or 6)
+    KMQ_LUT(4, 4, 64, 4, 1, 2, 6),   //           2
+    KMQ_LUT(4, 4, 64, 7, 1, 4, 4),   // K = 14336: 4 rows per workgroup (4096 rows: 10.5 us; 12.2 with 2, 10.9 with 6)
+    KMQ_LUT(4, 4, 64, 7, 1, 2, 6),   //            2
     // block-scaled format (lane slices of 32, 64 or 128 elements only)
     KMQ_LUT_SC(1, 4, 16, 1, 4, 1, 4),   // K = 2048
     KMQ_LUT_SC(1, 4, 16, 1, 2, 1, 4),
@@ -733,12 +737,16 @@ static const LutEntry kLut[] = {
     KMQ_LUT_SC(1, 4, 64, 1, 4, 3, 4),
     KMQ_LUT_SC(2, 4, 32, 1, 4, 2, 6),   // K = 2048
     KMQ_LUT_SC(2, 4, 64, 1, 4, 2, 7),   // K = 4096
-    KMQ_LUT_SC(2, 4, 64, 2, 2, 2, 7),   // K = 8192
-    KMQ_LUT_SC(2, 2, 64, 7, 1, 4, 7),   // K = 14336
+    KMQ_LUT_SC(2, 4, 64, 2, 2, 4, 4),   // K = 8192
+    KMQ_LUT_SC(2, 4, 64, 2, 2, 2, 7),
+    KMQ_LUT_SC(2, 4, 32, 7, 1, 4, 4),   // K = 14336
+    KMQ_LUT_SC(2, 2, 64, 7, 1, 4, 7),
     KMQ_LUT_SC(4, 4, 64, 1, 4, 2, 6),   // K = 2048
     KMQ_LUT_SC(4, 4, 64, 2, 2, 2, 6),   // K = 4096
-    KMQ_LUT_SC(4, 4, 64, 4, 1, 2, 6),   // K = 8192
-    KMQ_LUT_SC(4, 4, 64, 7, 1, 2, 6),   // K = 14336
+    KMQ_LUT_SC(4, 4, 64, 4, 1, 4, 4),   // K = 8192
+    KMQ_LUT_SC(4, 4, 64, 4, 1, 2, 6),
+    KMQ_LUT_SC(4, 4, 64, 7, 1, 4, 4),   // K = 14336
+    KMQ_LUT_SC(4, 4, 64, 7, 1, 2, 6),
 };
 constexpr int kLutCount = sizeof(kLut) / sizeof(kLut[0]);
 
