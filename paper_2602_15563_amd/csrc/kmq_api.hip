@@ -56,10 +56,6 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled) {
         const int l = lut_find(N, K, bits, layout);
         if (l >= 0) return Plan{M == 1 ? kVariantLut : kVariantPerColumn, l, 0, lut_name(l)};
     }
-    if (M == 1) {
-        const int i = rowsplit_find(K, bits, layout);
-        if (i >= 0) return Plan{kVariantRowsplit, i, 0, rowsplit_name(i)};
-    }
     const int slices = generic_splitk_slices(N, K, layout);
     if (slices > 1)
         return Plan{kVariantGeneric, slices, static_cast<size_t>(slices) * M * N * sizeof(float), "generic_splitk"};
@@ -107,7 +103,6 @@ static kmq_status check_and_run(const GemmArgs& a, void* stream) {
                 e = launch_lut_entry(plan.table_index, col, s);
             }
             break;
-        case kVariantRowsplit: e = launch_rowsplit(plan.table_index, a, s); break;
         case kVariantBlockGeneric: e = launch_blockscaled_generic(a, s); break;
         default: e = launch_generic(a, s); break;
     }

@@ -31,8 +31,7 @@ struct GemmArgs {
 enum Variant {
     kVariantInvalid = 0,
     kVariantGeneric,     // any shape: wave per row, fp32 codebook in LDS
-    kVariantRowsplit,    // batch 1, K from a table: x in registers, LUT in LDS (compiler-scheduled; 3-bit)
-    kVariantLut,         // batch 1, 1/2/4-bit, K from a table: hand-scheduled LDS-table kernel
+    kVariantLut,         // batch 1, K from a table: hand-scheduled LDS-table kernel
     kVariantMfma,        // tiled layout, batch 1..16: matrix-core kernel
     kVariantBlockGeneric,  // block-scaled format, any shape with K % 64 == 0
     kVariantPerColumn,     // canonical layout, batch 2..4, shape with a batch-1 table kernel: that kernel once per batch column
@@ -51,11 +50,6 @@ hipError_t launch_generic(const GemmArgs& a, hipStream_t s);   // split-K when a
 int generic_splitk_slices(int64_t N, int64_t K, int layout);
 hipError_t launch_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd, int64_t N,
                           int64_t K, int bits, int layout, hipStream_t s);
-
-// Rowsplit specialisations: -1 if (bits, K, layout) has none.
-int rowsplit_find(int64_t K, int bits, int layout);
-const char* rowsplit_name(int table_index);
-hipError_t launch_rowsplit(int table_index, const GemmArgs& a, hipStream_t s);
 
 hipError_t launch_pair_generic(const GemmArgs& a, hipStream_t s);
 hipError_t launch_fused_generic(const GemmArgs& a, hipStream_t s);   // batch 1, canonical layout, any shape; pair optional

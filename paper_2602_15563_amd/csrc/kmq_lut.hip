@@ -89,6 +89,62 @@ __device__ __forceinline__ void issue4_b32(uint32_t word, uint32_t& re, uint32_t
     }
 }
 
+// 3-bit: two neighbouring fields (6 bits) index a table of 64 centroid pairs, so the lookups and
+// dot instructions per weight are those of the 2-bit kernel.  Three words hold 16 such pairs;
+// quarter Q (0..3) issues pairs 4Q..4Q+3 into v[0..3].  A pair's six bits are moved to bits 2..7
+// of some byte by a shift (or a funnel shift where the pair straddles two words), from where the
+// byte-select AND drops them into the address.  Pair p starts at bit 6p of the 96:
+//   Q0: 0, 6, 12, 18 of w0      Q1: 24 of w0, 30 (w0|w1), 4 and 10 of w1
+//   Q2: 16, 22 of w1, 28 (w1|w2), 2 of w2      Q3: 8, 14, 20, 26 of w2
+template <int OFF, int Q>
+__device__ __forceinline__ void issue4_p6(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t (&a)[4], uint32_t* v,
+                                          uint32_t mask) {
+    uint32_t t0, t1, t2;
+#define KMQ_SDWA(dst, src, byte) \
+    "v_and_b32_sdwa " dst ", " src ", %11 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_" byte " src1_sel:DWORD\n\t"
+#define KMQ_READ4 \
+    "ds_read_b32 %0, %7 offset:%c12\n\t" \
+    "ds_read_b32 %1, %8 offset:%c12\n\t" \
+    "ds_read_b32 %2, %9 offset:%c12\n\t" \
+    "ds_read_b32 %3, %10 offset:%c12"
+#define KMQ_OPERANDS \
+    : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "=&v"(t0), "=&v"(t1), "=&v"(t2), \
+      "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]) \
+    : "v"(mask), "n"(OFF)
+    if constexpr (Q == 0) {
+        asm volatile(
+            "v_lshlrev_b32 %4, 2, %13\n\t"
+            "v_lshlrev_b32 %5, 4, %13\n\t"
+            "v_lshlrev_b32 %6, 6, %13\n\t"
+            KMQ_SDWA("%7", "%4", "0") KMQ_SDWA("%8", "%5", "1") KMQ_SDWA("%9", "%6", "2") KMQ_SDWA("%10", "%13", "2")
+            KMQ_READ4 KMQ_OPERANDS, "v"(w0));
+    } else if constexpr (Q == 1) {
+        asm volatile(
+            "v_lshlrev_b32 %4, 2, %13\n\t"
+            "v_alignbit_b32 %5, %14, %13, 28\n\t"
+            "v_lshrrev_b32 %6, 2, %14\n\t"
+            KMQ_SDWA("%7", "%4", "3") KMQ_SDWA("%8", "%5", "0") KMQ_SDWA("%9", "%6", "0") KMQ_SDWA("%10", "%14", "1")
+            KMQ_READ4 KMQ_OPERANDS, "v"(w0), "v"(w1));
+    } else if constexpr (Q == 2) {
+        asm volatile(
+            "v_lshlrev_b32 %4, 2, %13\n\t"
+            "v_lshlrev_b32 %5, 4, %13\n\t"
+            "v_alignbit_b32 %6, %14, %13, 26\n\t"
+            KMQ_SDWA("%7", "%4", "2") KMQ_SDWA("%8", "%5", "3") KMQ_SDWA("%9", "%6", "0") KMQ_SDWA("%10", "%14", "0")
+            KMQ_READ4 KMQ_OPERANDS, "v"(w1), "v"(w2));
+    } else {
+        asm volatile(
+            "v_lshlrev_b32 %4, 2, %13\n\t"
+            "v_lshlrev_b32 %5, 4, %13\n\t"
+            "v_lshlrev_b32 %6, 6, %13\n\t"
+            KMQ_SDWA("%7", "%4", "1") KMQ_SDWA("%8", "%5", "2") KMQ_SDWA("%9", "%6", "3") KMQ_SDWA("%10", "%13", "3")
+            KMQ_READ4 KMQ_OPERANDS, "v"(w2));
+    }
+#undef KMQ_SDWA
+#undef KMQ_READ4
+#undef KMQ_OPERANDS
+}
+
 // A dot instruction's result may feed the accumulator of the next dot at once, but any OTHER
 // vector instruction reading it needs three wait states (gfx90a and later).  The compiler
 // inserts those for its own code; it cannot see inside an asm block, so accumulators written
@@ -209,15 +265,18 @@ template <> struct WordVec<4> { using type = u32x4_t; };
 
 template <int G>
 __device__ __forceinline__ void load_words(const uint32_t* p, uint32_t (&w)[G]) {
-    using V = typename WordVec<G>::type;
     if constexpr (G == 1) {
         w[0] = __builtin_nontemporal_load(p);
-    } else if constexpr (G == 3) {
+    } else if constexpr (G % 3 == 0) {
         typedef u32x3_t __attribute__((aligned(4))) u32x3_a4_t;      // 12-byte slices sit 4-byte aligned
-        const u32x3_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x3_a4_t*>(p));
 #pragma unroll
-        for (int j = 0; j < G; ++j) w[j] = v[j];
+        for (int i = 0; i < G / 3; ++i) {
+            const u32x3_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x3_a4_t*>(p + 3 * i));   // (a 3-vector is 16 bytes wide as a type)
+#pragma unroll
+            for (int j = 0; j < 3; ++j) w[3 * i + j] = v[j];
+        }
     } else {
+        using V = typename WordVec<G>::type;
         const V v = __builtin_nontemporal_load(reinterpret_cast<const V*>(p));
 #pragma unroll
         for (int j = 0; j < G; ++j) w[j] = v[j];
@@ -256,7 +315,8 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     static_assert(!(PAIR && (FUSE & 2)), "the fused pair has no residual input");
     static_assert((FUSE & 5) != 5, "gains or unit gains");
     constexpr bool NORM_G = (FUSE & 1) != 0, NORM = (FUSE & 5) != 0, RES = (FUSE & 2) != 0;
-    static_assert(BITS == 1 || BITS == 2 || BITS == 4, "3-bit fields do not align with nibbles");
+    static_assert(BITS >= 1 && BITS <= 4, "bit-width");
+    static_assert(BITS != 3 || G % 3 == 0, "3-bit: lane slices are whole groups of three words");
     constexpr int C = 1 << BITS;
     constexpr int EL = G * 32 / BITS;              // elements per lane and row slice
     constexpr int K = NWK * LPR * EL;
@@ -265,15 +325,16 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     constexpr int ROWS_WAVE = RPL * RS;
     constexpr int ROWS_WG = NWR * ROWS_WAVE;
     constexpr int THREADS = NWK * NWR * 64;
-    constexpr int U = BITS == 1 ? 2 * G : G;       // lookup units (8 activation registers each) per row slice
-    constexpr int XR = 8 * U;                      // activation registers: bf16 pairs (1/2-bit) or fp32 (4-bit)
+    constexpr int U = BITS == 1 ? 2 * G : BITS == 3 ? 2 * G / 3 : G;   // lookup units (8 activation registers each) per row slice
+    constexpr int XR = 8 * U;                      // activation registers: bf16 pairs (1/2/3-bit) or fp32 (4-bit)
     constexpr int C16 = EL * 2 / 16;               // 16-byte chunks of x per lane slice
-    // Every wave builds the tables of its own rows (16 lanes per row, LUT_PASSES passes of 64
+    // Every wave builds the tables of its own rows (ENT lanes per row, LUT_PASSES passes of 64
     // lanes) in its own row groups; lanes past the last row write into padding: no branch.
-    constexpr int LUT_PASSES = BITS == 1 ? 0 : (ROWS_WAVE * 16 + 63) / 64;
-    constexpr int LUT_TABLES = BITS == 1 ? 1 : (LUT_PASSES * 4 + RPL - 1) / RPL;   // tables per row group incl. padding
+    constexpr int ENT = BITS == 3 ? 64 : 16;       // table entries per row (3-bit: one per PAIR of fields)
+    constexpr int LUT_PASSES = BITS == 1 ? 0 : (ROWS_WAVE * ENT + 63) / 64;
+    constexpr int LUT_TABLES = BITS == 1 ? 1 : (LUT_PASSES * (64 / ENT) + RPL - 1) / RPL;   // tables per row group incl. padding
     constexpr int LUT_GROUPS = BITS == 1 ? 1 : NWK * NWR * RPL;
-    constexpr int TBL = ((LUT_TABLES > RS ? LUT_TABLES : RS) * 16 + 63) / 64 * 64;   // dwords per row group: bases stay 256-byte aligned
+    constexpr int TBL = ((LUT_TABLES > RS ? LUT_TABLES : RS) * ENT + 63) / 64 * 64;   // dwords per row group: bases stay 256-byte aligned
     constexpr int XCHUNKS = K / 8;
     constexpr int XPT = (XCHUNKS + NWK * NWR * 64 - 1) / (NWK * NWR * 64);   // 16-byte chunks of x staged per thread
     constexpr int XSLOTS = XPT * NWK * NWR * 64;
@@ -293,7 +354,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     };
 
     struct alignas(256) Smem {
-        // 2/4-bit: per wave and row group, RS tables of 16 x 4 B; 1-bit: lut[0] holds the 16 x 8 B mask table
+        // 2/3/4-bit: per wave and row group, RS tables of ENT x 4 B; 1-bit: lut[0] holds the 16 x 8 B mask table
         uint32_t lut[LUT_GROUPS][TBL];
         // staged activations, swizzled per lane slice; threads past the end of x (the
         // thread count need not divide the chunk count) write clamped data into the tail,
@@ -370,10 +431,10 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
-    uint32_t cbv[LUT_PASSES > 0 ? LUT_PASSES : 1][BITS == 4 ? 1 : 2];
+    uint32_t cbv[LUT_PASSES > 0 ? LUT_PASSES : 1][BITS == 4 ? 1 : BITS == 3 ? 4 : 2];
 #pragma unroll
     for (int p = 0; p < LUT_PASSES; ++p) {
-        int rw = (lane + p * 64) >> 4;                                 // row inside the wave: t * RPL + sub
+        int rw = (lane + p * 64) / ENT;                                // row inside the wave: t * RPL + sub
         rw = rw < ROWS_WAVE ? rw : ROWS_WAVE - 1;
         int64_t row = wave_row0 + rw;
         row = row < N ? row : N - 1;
@@ -382,6 +443,10 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
             const u32x2_t c = *reinterpret_cast<const u32x2_t*>(cbrow(row));
             cbv[p][0] = c[0];
             cbv[p][1] = c[1];
+        } else if constexpr (BITS == 3) {
+            const u32x4_t c = *reinterpret_cast<const u32x4_t*>(cbrow(row));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) cbv[p][j] = c[j];
         } else {
             cbv[p][0] = cbrow(row)[lane & 15];
         }
@@ -489,17 +554,25 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     if constexpr (BITS != 1) {
 #pragma unroll
         for (int p = 0; p < LUT_PASSES; ++p) {
-            const int rw = (lane + p * 64) >> 4, e = lane & 15;
+            const int rw = (lane + p * 64) / ENT, e = lane % ENT;
             const int t2 = rw / RPL, sub2 = rw % RPL;
             uint32_t entry;
             if constexpr (BITS == 2) {
                 const uint64_t c64 = static_cast<uint64_t>(cbv[p][0]) | (static_cast<uint64_t>(cbv[p][1]) << 32);
                 entry = (static_cast<uint32_t>(c64 >> (16 * (e & 3))) & 0xFFFFu) |
                         ((static_cast<uint32_t>(c64 >> (16 * (e >> 2))) & 0xFFFFu) << 16);
+            } else if constexpr (BITS == 3) {
+                // entry e: centroid e mod 8 for the even element, centroid e div 8 for the odd one
+                auto pick = [&](int i) -> uint32_t {
+                    const uint32_t lo2 = (i & 2) ? cbv[p][1] : cbv[p][0], hi2 = (i & 2) ? cbv[p][3] : cbv[p][2];
+                    const uint32_t d = (i & 4) ? hi2 : lo2;
+                    return (i & 1) ? d >> 16 : d & 0xFFFFu;
+                };
+                entry = pick(e & 7) | (pick(e >> 3) << 16);
             } else {
                 entry = cbv[p][0] << 16;
             }
-            sm.lut[wave * RPL + sub2][t2 * 16 + e] = entry;
+            sm.lut[wave * RPL + sub2][t2 * ENT + e] = entry;
         }
     }
 
@@ -519,7 +592,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     [[maybe_unused]] uint32_t cpair = 0;
     if constexpr (SC && BITS == 1) cpair = *reinterpret_cast<const uint32_t*>(codebook);
     asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(cpair) : : "memory");
-    const uint32_t mask = BITS == 1 ? 0x78u : 0x3Cu;
+    const uint32_t mask = BITS == 1 ? 0x78u : BITS == 3 ? 0xFCu : 0x3Cu;
     float acc[RS];
     [[maybe_unused]] float accb[RS];               // 1-bit with scales: the first block's sum
     float a0 = 0.f, a1 = 0.f;
@@ -544,19 +617,30 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     } else {
         uint32_t v[2][8];
         uint32_t re = 0, ro = 0;
-        issue4_b32<0, 0>(w[0][0], re, ro, ar, v[0], mask);
-        issue4_b32<0, 1>(w[0][0], re, ro, ar, v[0], mask);
+        // half H (0, 1) of unit uu of row slice tt into vd[4H..4H+3]
+        auto issue_half = [&](auto tc, auto uc, auto hc, uint32_t (&vd)[8]) {
+            constexpr int tt = decltype(tc)::value, uu = decltype(uc)::value, hh = decltype(hc)::value;
+            if constexpr (BITS == 3) {
+                constexpr int g3 = 3 * (uu / 2);
+                issue4_p6<tt * ENT * 4, 2 * (uu % 2) + hh>(w[tt][g3], w[tt][g3 + 1], w[tt][g3 + 2], ar, &vd[4 * hh], mask);
+            } else {
+                issue4_b32<tt * ENT * 4, hh>(w[tt][uu], re, ro, ar, vd, mask);
+            }
+        };
+        using std::integral_constant;
+        issue_half(integral_constant<int, 0>{}, integral_constant<int, 0>{}, integral_constant<int, 0>{}, v[0]);
+        issue_half(integral_constant<int, 0>{}, integral_constant<int, 0>{}, integral_constant<int, 1>{}, v[0]);
         static_for<0, NU>([&](auto ic) {
             constexpr int n = decltype(ic)::value;
             constexpr int t = n / U, u = n % U;
             if constexpr (n + 1 < NU) {
                 constexpr int t1 = (n + 1) / U, u1 = (n + 1) % U;
-                issue4_b32<t1 * 64, 0>(w[t1][u1], re, ro, ar, v[(n + 1) & 1], mask);
-                if constexpr (BITS == 2) consume8_dot2<4>(v[n & 1], &xr[u * 8], a0, a1);
+                issue_half(integral_constant<int, t1>{}, integral_constant<int, u1>{}, integral_constant<int, 0>{}, v[(n + 1) & 1]);
+                if constexpr (BITS != 4) consume8_dot2<4>(v[n & 1], &xr[u * 8], a0, a1);
                 else consume8_fma<4>(v[n & 1], &xr[u * 8], a0, a1);
-                issue4_b32<t1 * 64, 1>(w[t1][u1], re, ro, ar, v[(n + 1) & 1], mask);
+                issue_half(integral_constant<int, t1>{}, integral_constant<int, u1>{}, integral_constant<int, 1>{}, v[(n + 1) & 1]);
             } else {
-                if constexpr (BITS == 2) consume8_dot2<0>(v[n & 1], &xr[u * 8], a0, a1);
+                if constexpr (BITS != 4) consume8_dot2<0>(v[n & 1], &xr[u * 8], a0, a1);
                 else consume8_fma<0>(v[n & 1], &xr[u * 8], a0, a1);
             }
             if constexpr (u == U - 1) { settle_dot(a0, a1); acc[t] = a0 + a1; a0 = 0.f; a1 = 0.f; }
@@ -722,6 +806,12 @@ static const LutEntry kLut[] = {
     KMQ_LUT(2, 4, 64, 2, 2, 2, 7),   //            8
     KMQ_LUT(2, 4, 32, 7, 1, 4, 4),   // K = 14336: 16-byte loads, 8 rows per workgroup (6.6 us on 4096 rows; 7.1 with 3 or 8 rows per wave)
     KMQ_LUT(2, 2, 64, 7, 1, 4, 7),   //            8-byte loads, 4 rows per workgroup (7.05 us; taken for few rows)
+    // 3-bit (lane slices are whole groups of three words = 32 elements)
+    KMQ_LUT(3, 6, 32, 1, 4, 2, 6),   // K = 2048
+    KMQ_LUT(3, 6, 64, 1, 4, 2, 7),   // K = 4096 (14336 rows: 7.7 us; 8.0 with 4 rows per wave)
+    KMQ_LUT(3, 6, 64, 2, 2, 4, 4),   // K = 8192: 16 rows per workgroup
+    KMQ_LUT(3, 6, 64, 2, 2, 2, 6),   //            8
+    KMQ_LUT(3, 3, 64, 7, 1, 4, 6),   // K = 14336: 12-byte loads, 4 rows per workgroup (4096 rows: 8.7 us; 9.0-9.2 with 24-byte loads)
     // 4-bit
     KMQ_LUT(4, 4, 64, 1, 4, 2, 6),   // K = 2048
     KMQ_LUT(4, 4, 64, 2, 2, 2, 6),   // K = 4096
@@ -741,6 +831,11 @@ static const LutEntry kLut[] = {
     KMQ_LUT_SC(2, 4, 64, 2, 2, 2, 7),
     KMQ_LUT_SC(2, 4, 32, 7, 1, 4, 4),   // K = 14336
     KMQ_LUT_SC(2, 2, 64, 7, 1, 4, 7),
+    KMQ_LUT_SC(3, 6, 32, 1, 4, 2, 6),   // K = 2048
+    KMQ_LUT_SC(3, 6, 64, 1, 4, 2, 7),   // K = 4096
+    KMQ_LUT_SC(3, 6, 64, 2, 2, 4, 4),   // K = 8192
+    KMQ_LUT_SC(3, 6, 64, 2, 2, 2, 6),
+    KMQ_LUT_SC(3, 6, 32, 7, 1, 4, 4),   // K = 14336 (lane slices of 64 elements: one block)
     KMQ_LUT_SC(4, 4, 64, 1, 4, 2, 6),   // K = 2048
     KMQ_LUT_SC(4, 4, 64, 2, 2, 2, 6),   // K = 4096
     KMQ_LUT_SC(4, 4, 64, 4, 1, 4, 4),   // K = 8192

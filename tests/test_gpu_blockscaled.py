@@ -33,7 +33,7 @@ def test_generic_shapes_vs_oracle(gpu, bits, N, K, M):
 
 
 SC_SHAPES = [(1, 2048), (1, 4096), (1, 8192), (2, 2048), (2, 4096), (2, 8192), (2, 14336),
-             (4, 2048), (4, 4096), (4, 8192), (4, 14336)]
+             (3, 2048), (3, 4096), (3, 8192), (3, 14336), (4, 2048), (4, 4096), (4, 8192), (4, 14336)]
 
 
 @pytest.mark.parametrize("bits,K", SC_SHAPES)
