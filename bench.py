@@ -37,6 +37,9 @@ WORKLOADS = {
     "cfg3_b3_4096x4096_m16": (3, 4096, 4096, 16, 3, 0, False),
     "cfg3_b3_14336x4096_m8": (3, 14336, 4096, 8, 3, 1, False),
     "cfg3_b3_14336x4096_m16": (3, 14336, 4096, 16, 3, 1, False),
+    # the same two 3-bit matrices at batch 1 (canonical layout; not a contract row: token generation at 3 bits)
+    "b3_4096x4096_m1": (3, 4096, 4096, 1, 3, 0, False),
+    "b3_14336x4096_m1": (3, 14336, 4096, 1, 3, 1, False),
     "cfg4_qkv_b1_9216x3072_m1": (1, 9216, 3072, 1, 4, 0, True),
     "cfg4_o_b1_3072x3072_m1": (1, 3072, 3072, 1, 4, 1, True),
     "cfg4_gate_b1_8192x3072_m1": (1, 8192, 3072, 1, 4, 2, True),

@@ -808,6 +808,7 @@ static const LutEntry kLut[] = {
     KMQ_LUT(2, 2, 64, 7, 1, 4, 7),   //            8-byte loads, 4 rows per workgroup (7.05 us; taken for few rows)
     // 3-bit (lane slices are whole groups of three words = 32 elements)
     KMQ_LUT(3, 6, 32, 1, 4, 2, 6),   // K = 2048
+    KMQ_LUT(3, 3, 32, 3, 1, 4, 6),   // K = 3072: three slices of 12-byte loads (9216 rows: 5.2 us; 6.1 with one slice of 36-byte loads)
     KMQ_LUT(3, 6, 64, 1, 4, 2, 7),   // K = 4096 (14336 rows: 7.7 us; 8.0 with 4 rows per wave)
     KMQ_LUT(3, 6, 64, 2, 2, 4, 4),   // K = 8192: 16 rows per workgroup
     KMQ_LUT(3, 6, 64, 2, 2, 2, 6),   //            8

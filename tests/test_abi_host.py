@@ -168,7 +168,7 @@ def test_heuristic_names():
     assert kmq.kernel_name(4096, 14336, 2, 1).startswith("lut_b2")
     assert kmq.kernel_name(2048, 2048, 1, 1).startswith("lut_b1")
     assert kmq.kernel_name(4096, 4096, 3, 1).startswith("lut_b3")
-    assert kmq.kernel_name(4096, 3072, 3, 1) == "generic"
+    assert kmq.kernel_name(4096, 1024, 3, 1) == "generic"
     assert kmq.kernel_name(77, 515, 2, 1) == "generic"
     assert kmq.kernel_name(4096, 4096, 3, 16, kmq.LAYOUT_TILED) == "mfma_b3"
     assert kmq.kernel_name(4096, 4000, 3, 16, kmq.LAYOUT_TILED) == "invalid"

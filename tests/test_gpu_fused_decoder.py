@@ -52,8 +52,8 @@ MODES = [("norm", True, False), ("res", False, True), ("both", True, True), ("pl
          ("unit", "unit", False), ("unit+res", "unit", True)]
 LUT_SHAPES = [(1, 2048, 64), (1, 2048, 333), (1, 3072, 100), (1, 3072, 3072), (1, 4096, 50), (1, 8192, 96), (1, 8192, 3072),
               (2, 2048, 40), (2, 3072, 77), (2, 4096, 1000), (2, 8192, 64), (2, 14336, 130),
-              (3, 2048, 90), (3, 4096, 333), (3, 8192, 64), (3, 14336, 70),
-              (3, 2048, 90), (3, 4096, 333), (3, 8192, 64), (3, 14336, 70),
+              (3, 2048, 90), (3, 3072, 50), (3, 4096, 333), (3, 8192, 64), (3, 14336, 70),
+              (3, 2048, 90), (3, 3072, 50), (3, 4096, 333), (3, 8192, 64), (3, 14336, 70),
               (4, 2048, 40), (4, 4096, 333), (4, 8192, 64), (4, 14336, 70)]
 
 
@@ -71,7 +71,7 @@ def test_fused_on_the_table_kernels(gpu, bits, K, N, mode, use_g, use_r):
 
 
 @pytest.mark.parametrize("mode,use_g,use_r", MODES)
-@pytest.mark.parametrize("bits,N,K", [(3, 40, 3072), (3, 33, 515), (4, 100, 33), (1, 7, 1), (1, 9, 1000), (2, 64, 1024)])
+@pytest.mark.parametrize("bits,N,K", [(3, 40, 1024), (3, 33, 515), (4, 100, 33), (1, 7, 1), (1, 9, 1000), (2, 64, 1024)])
 def test_fused_any_shape(gpu, bits, N, K, mode, use_g, use_r):
     from paper_2602_15563_amd import kmq
     assert kmq.kernel_name_fused(N, K, bits) == "fused_generic"
@@ -143,7 +143,7 @@ def test_swiglu_rmsnorm_on_the_table_kernels(gpu, bits, K, N):
     _swiglu_norm(gpu, bits, N, K, 850 + N, unit=True)
 
 
-@pytest.mark.parametrize("bits,N,K", [(3, 40, 3072), (3, 33, 515), (4, 20, 33), (1, 9, 1000)])
+@pytest.mark.parametrize("bits,N,K", [(3, 40, 1024), (3, 33, 515), (4, 20, 33), (1, 9, 1000)])
 def test_swiglu_rmsnorm_any_shape(gpu, bits, N, K):
     from paper_2602_15563_amd import kmq
     assert kmq.kernel_name_fused(N, K, bits, pair=True) == "fused_generic"

@@ -106,7 +106,7 @@ def test_contract_configs_tiled(gpu, cfg):
 
 
 FAST_SHAPES = [(1, 2048), (1, 3072), (1, 4096), (1, 8192), (2, 2048), (2, 3072), (2, 4096), (2, 8192),
-               (2, 14336), (3, 2048), (3, 4096), (3, 8192), (3, 14336), (4, 2048), (4, 4096), (4, 8192), (4, 14336)]
+               (2, 14336), (3, 2048), (3, 3072), (3, 4096), (3, 8192), (3, 14336), (4, 2048), (4, 4096), (4, 8192), (4, 14336)]
 
 
 @pytest.mark.parametrize("bits,K", FAST_SHAPES)
