@@ -440,11 +440,14 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         row = row < N ? row : N - 1;
         if constexpr (SC) row = 0;                                     // one table for the whole tensor
         if constexpr (BITS == 2) {
-            const u32x2_t c = *reinterpret_cast<const u32x2_t*>(cbrow(row));
+            // (codebooks are 4-byte aligned by contract: the vector types say so)
+            typedef u32x2_t __attribute__((aligned(4))) u32x2_a4_t;
+            const u32x2_t c = *reinterpret_cast<const u32x2_a4_t*>(cbrow(row));
             cbv[p][0] = c[0];
             cbv[p][1] = c[1];
         } else if constexpr (BITS == 3) {
-            const u32x4_t c = *reinterpret_cast<const u32x4_t*>(cbrow(row));
+            typedef u32x4_t __attribute__((aligned(4))) u32x4_a4_t;
+            const u32x4_t c = *reinterpret_cast<const u32x4_a4_t*>(cbrow(row));
 #pragma unroll
             for (int j = 0; j < 4; ++j) cbv[p][j] = c[j];
         } else {

@@ -255,3 +255,37 @@ def test_small_batches_on_the_canonical_layout_per_column(gpu, bits, N, K, M):
     if name.startswith("lut_"):
         for m in range(M):
             assert np.array_equal(Yg[m], gpu.run_gemm(Wd, cbd, X[m], N, K, bits)[0])
+
+
+@pytest.mark.parametrize("bits,N,K,M,layout", [(1, 70, 3072, 1, 0), (2, 130, 4096, 1, 0), (3, 90, 4096, 1, 0), (3, 50, 3072, 1, 0),
+                                               (4, 64, 8192, 1, 0), (3, 33, 515, 1, 0), (2, 40, 1000, 3, 0),
+                                               (2, 100, 4096, 2, 0), (3, 64, 4096, 8, 1), (4, 48, 2048, 16, 1)])
+def test_operands_at_their_minimum_alignment(gpu, bits, N, K, M, layout):
+    """The contract asks 16 bytes of W and X but only 4 of the codebook and 2 of Y: the kernels' vector loads of
+    codebook rows and their paired output stores must cope with exactly that."""
+    import torch
+    from paper_2602_15563_amd import kmq
+    seed = 1300 + bits + M
+    idx = synth.make_indices(seed, 0, N, K, bits)
+    cb = synth.make_codebook(seed, 0, N, bits, symmetric=(bits == 1))
+    X = synth.make_x(seed, 0, M, K)
+    packed = oracle.pack(idx, bits)
+    Wd = gpu.dev(kmq.repack(packed, K, bits, kmq.LAYOUT_TILED) if layout else packed)
+    cbuf = torch.zeros(cb.size + 8, dtype=torch.int16, device="cuda")
+    ybuf = torch.full((M * N + 8,), 0x7FC1, dtype=torch.int16, device="cuda")
+    for c_off, y_off in ((2, 1), (6, 3), (4, 0)):             # int16 elements: 4, 12, 8 and 2, 6, 0 bytes
+        cbd = cbuf[c_off:c_off + cb.size].view(N, -1)
+        cbd.copy_(gpu.dev(cb))
+        ybuf.fill_(0x7FC1)
+        Y = ybuf[y_off:y_off + M * N].view(M, N)
+        assert cbd.data_ptr() % 16 == (2 * c_off) % 16 and Y.data_ptr() % 4 == (2 * y_off) % 4
+        ws_bytes = kmq.workspace_bytes(N, K, bits, M, layout)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda") if ws_bytes else None
+        if M == 1:
+            kmq.gemv(Wd, cbd, gpu.dev(X), Y, N, K, bits, layout, ws)
+        else:
+            kmq.gemm_smallbatch(Wd, cbd, gpu.dev(X), Y, N, K, M, bits, layout, ws)
+        torch.cuda.synchronize()
+        gpu.check_against_oracle(gpu.host_u16(Y), packed, cb, X, K, bits,
+                                 label=f"b{bits} {N}x{K} M{M} codebook+{2 * c_off}B y+{2 * y_off}B")
+        assert int(ybuf[y_off + M * N]) == 0x7FC1 and (y_off == 0 or int(ybuf[y_off - 1]) == 0x7FC1)   # nothing outside Y
