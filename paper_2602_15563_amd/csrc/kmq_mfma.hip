@@ -19,7 +19,9 @@
 //            fields spread so that one shift + AND yields four indices in the
 //            four bytes of a register, which is a v_perm_b32 selector: two byte
 //            gathers (low, high) and two interleaves per four weights, no LDS;
-//   4-bit    16 centroids do not fit a perm pool: bf16 table per row in LDS;
+//   4-bit    16 centroids do not fit a perm pool: tables in LDS, one column (= bank) per lane so that
+//            lookups never collide, the index dropped into byte 1 of the address by one instruction;
+//            with a tensor-wide codebook and long rows, a table of centroid pairs indexed by a whole byte;
 //   1-bit    no per-row table: the A operand is the {0,1} mask of the bits
 //            (row-independent nibble table in LDS), a second MFMA with an all-ones
 //            A operand accumulates sum_k x, and the epilogue applies the closed
@@ -28,6 +30,7 @@
 // A workgroup is NWK waves that split K (whole super-blocks each) for RBW blocks
 // of 16 rows; partial 16x16 tiles are summed through LDS in a fixed order.
 #include <cstdlib>
+#include <type_traits>
 
 #include "kmq_device.h"
 #include "kmq_launch.h"
@@ -76,8 +79,41 @@ __device__ __forceinline__ uint32_t group_bits(const uint32_t (&g)[GW], int j) {
 // scales of its four output rows.  The workgroup's scales are staged once, transposed, in LDS
 // (kMaxScaledBlocks blocks of K at most).
 constexpr int kMaxScaledBlocks = 256;          // K <= 16384 for the scaled matrix-core path
+// Staged scales: 16 rows of a K block take 20 entries, not 16.  Staging transposes (a lane reads eight
+// consecutive blocks of one row and writes them 8 x kSctRow entries apart); with 16 lanes on 16 rows and
+// the wave's four lane groups on four runs of eight blocks, a stride of 20 puts the groups 16 banks
+// apart, so the 64 two-byte writes of an instruction fall into 32 distinct dwords in 32 banks.  A stride
+// of 16 would put all of them into the same eight banks.  (Multiple of four: the reader's 8-byte loads.)
+constexpr int kSctRow = 20;
 
-template <int BITS, int NWK, int RBW, int SPW, bool SC>
+typedef __attribute__((address_space(3))) const uint32_t lds_cu32_t;
+
+// byte 1 of `a` <- (byte BYTE of src) & mask, other bytes of `a` kept: drops a table index into
+// bits 8.. of an LDS address with one instruction
+template <typename F>
+__device__ __forceinline__ void static_for_bytes(F&& f) {
+    f(std::integral_constant<int, 0>{});
+    f(std::integral_constant<int, 1>{});
+    f(std::integral_constant<int, 2>{});
+    f(std::integral_constant<int, 3>{});
+}
+
+template <int BYTE>
+__device__ __forceinline__ void index_to_byte1(uint32_t& a, uint32_t src, uint32_t mask) {
+    static_assert(BYTE >= 0 && BYTE < 4, "byte select");
+    if constexpr (BYTE == 0)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_0 src1_sel:DWORD" : "+v"(a) : "v"(src), "v"(mask));
+    else if constexpr (BYTE == 1)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_1 src1_sel:DWORD" : "+v"(a) : "v"(src), "v"(mask));
+    else if constexpr (BYTE == 2)
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_2 src1_sel:DWORD" : "+v"(a) : "v"(src), "v"(mask));
+    else
+        asm("v_and_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_3 src1_sel:DWORD" : "+v"(a) : "v"(src), "v"(mask));
+}
+
+//
+// PT (4-bit block-scaled only) selects the table of centroid PAIRS described at the table layout below.
+template <int BITS, int NWK, int RBW, int SPW, bool SC, bool PT = false>
 __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
     const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int64_t N, int64_t K, int M,
@@ -86,18 +122,30 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
     constexpr int GPG = T::GPG, GW = T::GW, SBE = T::SBE, C = 1 << BITS;
     constexpr int THREADS = NWK * 64;
 
+    // 4-bit: the centroid tables are laid out [entry][lane]: lane l keeps its row's 16 centroids (as
+    // bf16 in both halves of a dword) in column l, i.e. in LDS bank l, so a wave's 64 lookups never
+    // collide whatever the indices are, and the address is (entry << 8) | (lane << 2): the index
+    // goes into byte 1 of a register that holds lane * 4.
+    // With the tensor-wide codebook of the block-scaled format one table serves every row, and it can be
+    // a table of PAIRS (PT: 256 entries, 64 KB with a column per lane): a byte of the index stream is then
+    // the address of two weights, already packed as the matrix instruction wants them -- half the
+    // lookups and a third of the vector instructions, for a 64 KB fill per workgroup and one workgroup
+    // per CU: it pays on long rows (8192 x 8192, batch 16: 16.1 -> 13.5 us) and costs on short ones
+    // (4096 x 4096: 6.7 -> 7.5 us), so the launcher decides.
+    static_assert(!PT || (BITS == 4 && SC), "pair table: 4-bit, tensor-wide codebook");
+    constexpr int PT_RB = BITS == 4 ? (SC ? 1 : RBW) : 1, PT_ENT = BITS == 4 ? (PT ? 256 : 16) : 1;
     struct alignas(256) Smem {
-        uint16_t tbl[BITS == 4 ? RBW * 16 : 1][16];         // 4-bit: bf16 codebook rows
+        uint32_t ptab[PT_RB][PT_ENT][64];
         u32x2_t masks[16];                                  // 1-bit: nibble -> four bf16 {0,1}
         // per wave: 16 batch rows x (16 + 1 pad) 16-byte pieces of activations; when the wave is
-        // done with them the same memory holds its RBW partial 16x16 tiles ([n][m], 1 KB each)
+        // done with them the same memory holds its RBW partial 16x16 tiles ([m][n padded to 17] floats)
         u32x4_t xstage[NWK][16 * 17];
         float redx[BITS == 1 ? NWK : 1][16];                // 1-bit: partial sum_k x per batch column
         uint32_t cpair[BITS == 1 ? RBW * 16 : 1];           // 1-bit: the rows' centroid pairs, fetched at the start for the epilogue
-        // block-scaled: scales of the workgroup's rows, [row block][K block][row in block]
+        // block-scaled: scales of the workgroup's rows, [row block][K block][row in block, padded to kSctRow]
         // (kept as bf16: an fp32 table saves four conversions per tile and block but doubles the
         // staging writes and the footprint, and measured slower)
-        uint16_t sct[SC ? RBW * kMaxScaledBlocks * 16 : 1];
+        uint16_t sct[SC ? RBW * kMaxScaledBlocks * kSctRow : 1];
     };
     __shared__ Smem sm;
 
@@ -128,13 +176,23 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
                 sm.cpair[threadIdx.x] = *reinterpret_cast<const uint32_t*>(codebook + row * 2);
             }
         }
+    } else if constexpr (PT) {
+        const uint32_t cv = codebook[lane & 15];             // lane l holds centroid l mod 16; entries are wave-uniform
+        for (int e = wk; e < 256; e += NWK)
+            sm.ptab[0][e][lane] = static_cast<uint32_t>(__builtin_amdgcn_readlane(cv, e & 15)) |
+                                  (static_cast<uint32_t>(__builtin_amdgcn_readlane(cv, e >> 4)) << 16);
     } else if constexpr (BITS == 4) {
-        for (int i = threadIdx.x; i < RBW * 16 * C; i += THREADS) {
-            const int r = i / C, e = i % C;
-            int64_t row = (rb0 + r / 16) * 16 + (r % 16);
+#pragma unroll
+        for (int r = 0; r < PT_RB; ++r) {
+            int64_t row = (rb0 + r) * 16 + n;
             row = row < N ? row : N - 1;
             if constexpr (SC) row = 0;
-            sm.tbl[r][e] = codebook[row * C + e];
+            const uint32_t* cw = reinterpret_cast<const uint32_t*>(codebook + row * C);
+            for (int e2 = wk; e2 < C / 2; e2 += NWK) {       // the waves share the entries; every lane fills its own column
+                const uint32_t dw = cw[e2];
+                sm.ptab[r][2 * e2][lane] = __builtin_amdgcn_perm(dw, dw, 0x01000100u);
+                sm.ptab[r][2 * e2 + 1][lane] = __builtin_amdgcn_perm(dw, dw, 0x03020302u);
+            }
         }
     }
 
@@ -144,15 +202,16 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
             // eight scales (16 bytes) of one row per load: an eighth of the load instructions
             const int nb8 = nblk >> 3;
             for (int e = threadIdx.x; e < RBW * 16 * nb8; e += THREADS) {
-                const int rl = e / nb8, b8 = e % nb8;
-                int64_t row = rb0 * 16 + rl;
+                // 16 consecutive lanes: the 16 rows of a row block; the next 16 lanes: the next eight blocks
+                const int r16 = e & 15, b8 = (e >> 4) % nb8, rb = (e >> 4) / nb8;
+                int64_t row = (rb0 + rb) * 16 + r16;
                 row = row < N ? row : N - 1;
                 const u32x4_t v = *reinterpret_cast<const u32x4_t*>(scales + row * nblk + b8 * 8);
-                uint16_t* dst = &sm.sct[((rl >> 4) * nblk + b8 * 8) * 16 + (rl & 15)];
+                uint16_t* dst = &sm.sct[(rb * nblk + b8 * 8) * kSctRow + r16];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    dst[(2 * i) * 16] = static_cast<uint16_t>(v[i]);
-                    dst[(2 * i + 1) * 16] = static_cast<uint16_t>(v[i] >> 16);
+                    dst[(2 * i) * kSctRow] = static_cast<uint16_t>(v[i]);
+                    dst[(2 * i + 1) * kSctRow] = static_cast<uint16_t>(v[i] >> 16);
                 }
             }
         } else {
@@ -160,7 +219,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
                 const int rl = e / nblk, blk = e % nblk;        // consecutive threads: consecutive blocks of a row
                 int64_t row = rb0 * 16 + rl;
                 row = row < N ? row : N - 1;
-                sm.sct[((rl >> 4) * nblk + blk) * 16 + (rl & 15)] = scales[row * nblk + blk];
+                sm.sct[((rl >> 4) * nblk + blk) * kSctRow + (rl & 15)] = scales[row * nblk + blk];
             }
         }
     }
@@ -179,7 +238,9 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
         xoff[i] = (static_cast<uint32_t>(m) * static_cast<uint32_t>(K) + 8u * n) * 2u;
     }
     u32x4_t* xtile = &sm.xstage[wk][0];
-    static_assert(RBW * 256 * sizeof(float) <= 16 * 17 * sizeof(u32x4_t), "partial tiles reuse the activation tile");
+    // partial tiles: [row block][batch column][row, padded to 17] floats -- the threads that sum them read 16
+    // consecutive rows of two batch columns at once; unpadded (and row-major) that was a 16-way bank conflict
+    static_assert(RBW * 16 * 17 * sizeof(float) <= 16 * 17 * sizeof(u32x4_t), "partial tiles reuse the activation tile");
 
     f32x4_t acc[RBW];
 #pragma unroll
@@ -190,14 +251,11 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
 #pragma unroll
         for (int r = 0; r < RBW; ++r) accxs[r] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
-    [[maybe_unused]] const uint16_t* trow[RBW];
-    [[maybe_unused]] uint32_t lo0[RBW], lo1[RBW], hi0[RBW], hi1[RBW];   // perm pools: low / high bytes of the lane's centroids
-    if constexpr (BITS == 4) {
+    [[maybe_unused]] uint32_t areg[8];                      // 4-bit: lookup addresses, byte 0 = lane * 4, byte 1 = index
 #pragma unroll
-        // tensor-wide codebook: every lane reads the one table, 8 dwords in 8 banks, so a wave's
-        // lookups never collide; per-row tables of rows n and n + 8 share banks
-        for (int r = 0; r < RBW; ++r) trow[r] = &sm.tbl[SC ? 0 : r * 16 + n][0];
-    } else if constexpr (BITS == 2 || BITS == 3) {
+    for (int e = 0; e < 8; ++e) areg[e] = static_cast<uint32_t>(lane) * 4u;
+    [[maybe_unused]] uint32_t lo0[RBW], lo1[RBW], hi0[RBW], hi1[RBW];   // perm pools: low / high bytes of the lane's centroids
+    if constexpr (BITS == 2 || BITS == 3) {
 #pragma unroll
         for (int r = 0; r < RBW; ++r) {
             int64_t row = (rb0 + r) * 16 + n;
@@ -288,11 +346,27 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
                             a = u32x4_t{lo[0], lo[1], hi[0], hi[1]};
                         } else if constexpr (BITS == 4) {
                             const uint32_t gb = group_bits<BITS, GW>(gran[p][r], j);
+                            const uint32_t toff = static_cast<uint32_t>(reinterpret_cast<size_t>((lds_cu32_t*)(&sm.ptab[SC ? 0 : r][0][0])));
+                            if constexpr (PT) {                // a byte = two indices = one entry of the pair table
+                                static_for_bytes([&](auto bc) {
+                                    constexpr int b = decltype(bc)::value;
+                                    index_to_byte1<b>(areg[b], gb, 0xFFu);
+                                    a[b] = *reinterpret_cast<lds_cu32_t*>(static_cast<size_t>(areg[b] + toff));
+                                });
+                                return a;
+                            }
+                            // even nibbles sit in the low four bits of the bytes of gb, odd ones of gb >> 4
+                            const uint32_t go = gb >> 4;
                             uint32_t wv[8];
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) wv[e] = trow[r][(gb >> (4 * e)) & 15u];
-                            a = u32x4_t{wv[0] | (wv[1] << 16), wv[2] | (wv[3] << 16),
-                                        wv[4] | (wv[5] << 16), wv[6] | (wv[7] << 16)};
+                            static_for_bytes([&](auto bc) {
+                                constexpr int b = decltype(bc)::value;
+                                index_to_byte1<b>(areg[2 * b], gb, 0x0Fu);
+                                wv[2 * b] = *reinterpret_cast<lds_cu32_t*>(static_cast<size_t>(areg[2 * b] + toff));
+                                index_to_byte1<b>(areg[2 * b + 1], go, 0x0Fu);
+                                wv[2 * b + 1] = *reinterpret_cast<lds_cu32_t*>(static_cast<size_t>(areg[2 * b + 1] + toff));
+                            });
+                            a = u32x4_t{__builtin_amdgcn_perm(wv[1], wv[0], 0x07060100u), __builtin_amdgcn_perm(wv[3], wv[2], 0x07060100u),
+                                        __builtin_amdgcn_perm(wv[5], wv[4], 0x07060100u), __builtin_amdgcn_perm(wv[7], wv[6], 0x07060100u)};
                         } else {
 #pragma unroll
                             for (int h = 0; h < 2; ++h) {      // elements 4h..4h+3 of this step
@@ -343,7 +417,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
                                 f32x4_t t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, decode(r, j0)), b0, zero, 0, 0, 0);
                                 t = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, decode(r, j0 + 1)), b1, t, 0, 0, 0);
                                 // scales of output rows 4q..4q+3 of this row block, one 8-byte read
-                                const u32x2_t s4 = *reinterpret_cast<const u32x2_t*>(&sm.sct[((r * static_cast<int>(K / KMQ_BLOCK)) + blk) * 16 + 4 * q]);
+                                const u32x2_t s4 = *reinterpret_cast<const u32x2_t*>(&sm.sct[((r * static_cast<int>(K / KMQ_BLOCK)) + blk) * kSctRow + 4 * q]);
                                 const float sc[4] = {bf16_to_f32(s4[0] & 0xFFFFu), bf16_to_f32(s4[0] >> 16),
                                                      bf16_to_f32(s4[1] & 0xFFFFu), bf16_to_f32(s4[1] >> 16)};
 #pragma unroll
@@ -377,7 +451,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
 #pragma unroll
     for (int r = 0; r < RBW; ++r)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) reinterpret_cast<float*>(xtile)[r * 256 + (4 * q + i) * 16 + n] = acc[r][i];
+        for (int i = 0; i < 4; ++i) reinterpret_cast<float*>(xtile)[(r * 16 + n) * 17 + 4 * q + i] = acc[r][i];
     if constexpr (BITS == 1 && !SC) {
         if (q == 0) sm.redx[wk][n] = accx[0];               // every row of the all-ones tile is sum_k x[m][k]
     }
@@ -388,7 +462,7 @@ __global__ __launch_bounds__(NWK * 64) void gemm_mfma_kernel(
         const int r = nl >> 4, nn = nl & 15;
         float s = 0.f;
 #pragma unroll
-        for (int k = 0; k < NWK; ++k) s += reinterpret_cast<const float*>(&sm.xstage[k][0])[r * 256 + nn * 16 + m];
+        for (int k = 0; k < NWK; ++k) s += reinterpret_cast<const float*>(&sm.xstage[k][0])[(r * 16 + m) * 17 + nn];
         const int64_t row = (rb0 + r) * 16 + nn;
         if (m < M && row < N) {
             if constexpr (BITS == 1 && !SC) {
@@ -410,6 +484,14 @@ template <int BITS, int NWK, int RBW, int SPW>
 static void launch_mfma_one(const GemmArgs& a, hipStream_t s) {
     const int64_t nrb = (a.N + 15) / 16;
     const dim3 grid(static_cast<unsigned>((nrb + RBW - 1) / RBW)), block(NWK * 64);
+    if constexpr (BITS == 4) {
+        // pair table: long rows (the 64 KB fill is amortised) and a grid of one round (one workgroup per CU)
+        if (a.scales && a.K >= 8192 && grid.x <= 256) {
+            hipLaunchKernelGGL((gemm_mfma_kernel<BITS, NWK, RBW, SPW, true, true>), grid, block, 0, s,
+                               a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.scales);
+            return;
+        }
+    }
     if (a.scales)
         hipLaunchKernelGGL((gemm_mfma_kernel<BITS, NWK, RBW, SPW, true>), grid, block, 0, s,
                            a.W, a.codebook, a.X, a.Y, a.N, a.K, a.M, a.scales);
@@ -423,7 +505,7 @@ static void launch_mfma_one(const GemmArgs& a, hipStream_t s) {
 #define KMQ_MFMA_SHAPES(X) \
     X(8, 1, 1) X(8, 1, 2) X(8, 1, 4) X(4, 1, 3) X(4, 1, 4) X(2, 1, 3) \
     X(6, 1, 1) X(6, 1, 2) X(3, 1, 2) \
-    X(4, 2, 2) X(4, 2, 4) X(4, 2, 8) X(6, 2, 1) X(8, 2, 2) \
+    X(4, 2, 2) X(4, 2, 4) X(4, 2, 8) X(6, 2, 1) X(8, 2, 2) X(8, 2, 4) X(8, 2, 8) X(8, 1, 8) \
     X(6, 3, 1) X(8, 3, 2)
 #define KMQ_MFMA_RT_SHAPES(X) \
     X(8, 1) X(4, 1) X(2, 1) X(1, 1) X(8, 2) X(4, 2) X(2, 2) X(1, 2)
