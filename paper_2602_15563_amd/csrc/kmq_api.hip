@@ -9,22 +9,21 @@
 
 namespace kmq {
 
-// On the canonical layout batches above 1 have only the shape-agnostic kernel, and for batches of 2..4
-// running the batch-1 table kernel once per column of the batch can be faster (the tiled layout with its
-// matrix-core kernel is the intended route for batch > 1).  The choice is a two-line cost model fitted to
-// measurements (us): the shape-agnostic kernel costs about 5 + g * M * (N*K / 1e6) with g = 0.11 (0.20 for
-// the block-scaled format), a table-kernel launch about 2.6 + bytes / 3.3e6.  Checked against 9216x3072
-// 1-bit (per column wins at 2..4), 14336x4096 2-bit (wins), 4096x4096 4-bit (a tie at 2, loses at 3 and 4), 8192x8192
-// block-scaled 4-bit (wins).  KMQ_PER_COLUMN_MAX in the environment caps the batch (tuning, read once).
-static bool per_column_faster(int64_t N, int64_t K, int bits, int M, bool scaled) {
+// On the canonical layout a batch above 1 runs the batch-1 table kernel, where the shape has one, over a
+// grid of (row group, column) workgroups in ONE launch: the workgroups that share rows of W sit next to
+// each other on one XCD, so W still comes from memory once and the other columns find it in that L2 (the
+// tiled layout with its matrix-core kernel remains the fastest route for batch > 1: it also decodes each
+// weight once).  Measured (us), every further column costs N*K / r with r = 20, 19, 14, 9.5 million
+// weights per us at 1, 2, 3, 4 bits -- decode time, every column looks every weight up again -- against
+// N*K / 9 for every column of the shape-agnostic kernel, which also starts later (about 5 us against 2.6
+// + bytes / 3.3e6 for the first column): the table kernel wins at every batch.  Table / shape-agnostic:
+// 9216x3072 1-bit, batch 4: 8.9 / 21.7; 14336x4096 2-bit, batch 16: 50.6 / 121; 8192x8192 block-scaled
+// 4-bit, batch 16: 111 / 237; 4096x4096 4-bit, batch 4: 10.0 / 12.8.  KMQ_PER_COLUMN_MAX in the
+// environment caps the batch (tuning, read once).
+static bool per_column_faster(int M) {
     static const char* const v = std::getenv("KMQ_PER_COLUMN_MAX");
-    static const int cap = v ? std::atoi(v) : 4;
-    if (M < 2 || M > cap) return false;
-    const double mw = static_cast<double>(N) * static_cast<double>(K) * 1e-6;
-    const double generic_us = 5.0 + (scaled ? 0.20 : 0.11) * M * mw;
-    const double bytes = static_cast<double>(N) * static_cast<double>(words_per_row(bits, K)) * 4.0;
-    const double column_us = 2.6 + bytes / 3.3e6;
-    return M * column_us < generic_us;
+    static const int cap = v ? std::atoi(v) : KMQ_MAX_BATCH;
+    return M >= 2 && M <= cap;
 }
 
 // Launch-shape heuristic (the paper autotunes chunk shapes per problem, App. E
@@ -41,7 +40,7 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled) {
             static const char* const names[4] = {"mfma_sc_b1", "mfma_sc_b2", "mfma_sc_b3", "mfma_sc_b4"};
             return Plan{kVariantMfma, -1, 0, names[bits - 1]};
         }
-        if (M == 1 || per_column_faster(N, K, bits, M, true)) {
+        if (M == 1 || per_column_faster(M)) {
             const int l = lut_find(N, K, bits, layout, true);
             if (l >= 0) return Plan{M == 1 ? kVariantLut : kVariantPerColumn, l, 0, lut_name(l)};
         }
@@ -52,7 +51,7 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled) {
         static const char* const names[4] = {"mfma_b1", "mfma_b2", "mfma_b3", "mfma_b4"};
         return Plan{kVariantMfma, -1, 0, names[bits - 1]};
     }
-    if (M == 1 || per_column_faster(N, K, bits, M, false)) {
+    if (M == 1 || per_column_faster(M)) {
         const int l = lut_find(N, K, bits, layout);
         if (l >= 0) return Plan{M == 1 ? kVariantLut : kVariantPerColumn, l, 0, lut_name(l)};
     }
@@ -94,14 +93,8 @@ static kmq_status check_and_run(const GemmArgs& a, void* stream) {
     switch (plan.variant) {
         case kVariantMfma: e = launch_mfma(a, s); break;
         case kVariantLut: e = launch_lut_entry(plan.table_index, a, s); break;
-        case kVariantPerColumn:
-            for (int m = 0; m < a.M && e == hipSuccess; ++m) {
-                GemmArgs col = a;
-                col.M = 1;
-                col.X = a.X + static_cast<int64_t>(m) * a.K;     // K is a multiple of 8 for every table kernel: rows stay 16-byte aligned
-                col.Y = a.Y + static_cast<int64_t>(m) * a.N;
-                e = launch_lut_entry(plan.table_index, col, s);
-            }
+        case kVariantPerColumn:                               // one launch, a workgroup per (row group, column)
+            e = launch_lut_entry(plan.table_index, a, s);   // K is a multiple of 8 for every table kernel: rows of X stay 16-byte aligned
             break;
         case kVariantBlockGeneric: e = launch_blockscaled_generic(a, s); break;
         default: e = launch_generic(a, s); break;

@@ -34,7 +34,7 @@ enum Variant {
     kVariantLut,         // batch 1, K from a table: hand-scheduled LDS-table kernel
     kVariantMfma,        // tiled layout, batch 1..16: matrix-core kernel
     kVariantBlockGeneric,  // block-scaled format, any shape with K % 64 == 0
-    kVariantPerColumn,     // canonical layout, batch 2..4, shape with a batch-1 table kernel: that kernel once per batch column
+    kVariantPerColumn,     // canonical layout, batch > 1, shape with a batch-1 table kernel: that kernel over a (row group, column) grid
 };
 
 struct Plan {

@@ -309,7 +309,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
                      const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int64_t N,
                      const uint16_t* __restrict__ scales,
                      const uint32_t* __restrict__ W2, const uint16_t* __restrict__ codebook2,
-                     const uint16_t* __restrict__ norm_w, float eps, const uint16_t* __restrict__ residual) {
+                     const uint16_t* __restrict__ norm_w, float eps, const uint16_t* __restrict__ residual, int mcols) {
     static_assert(!(SC && PAIR), "the fused pair is offered for the per-row-codebook format");
     static_assert(FUSE == 0 || !SC, "decoder fusions are offered for the per-row-codebook format");
     static_assert(!(PAIR && (FUSE & 2)), "the fused pair has no residual input");
@@ -370,7 +370,20 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int wk = wave % NWK, wr = wave / NWK;
     const int sub = lane / LPR, pos = lane % LPR;
-    const int64_t wg_row0 = static_cast<int64_t>(blockIdx.x) * ROWS_WG;
+    // mcols > 1: a batch of mcols activation rows in one launch, every workgroup still one column (x and y are
+    // K and N elements apart per column).  Workgroup ids go round-robin over the 8 XCDs, each with its own L2;
+    // the id is cut so that the mcols workgroups that read the same rows of W sit on one XCD, one after the
+    // other: the first fetches those rows from memory, the others find them in that L2.
+    int64_t wg = blockIdx.x;
+    if (mcols > 1) {
+        const int64_t t = wg >> 3;
+        const int64_t col = t % mcols;
+        wg = (t / mcols) * 8 + (wg & 7);
+        if (wg * ROWS_WG >= N) return;                       // the grid is padded to a multiple of 8 row groups
+        x += col * K;
+        y += col * (PAIR ? N / 2 : N);
+    }
+    const int64_t wg_row0 = wg * ROWS_WG;
     const int64_t wave_row0 = wg_row0 + wr * ROWS_WAVE;
     // start of a row's packed words / codebook (PAIR: even virtual rows first matrix, odd rows second)
     // PAIR: even virtual rows come from the first matrix, odd rows from the second.  The choice
@@ -749,16 +762,16 @@ static void launch_lut(const GemmArgs& a, hipStream_t s) {
             const dim3 grid(static_cast<unsigned>((nv + rows_wg - 1) / rows_wg));
             if (a.norm && a.norm_w) {
                 hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, true, 1>), grid, block, 0, s,
-                                   a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, a.norm_w, a.eps, nullptr);
+                                   a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, a.norm_w, a.eps, nullptr, 1);
                 return;
             }
             if (a.norm) {
                 hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, true, 4>), grid, block, 0, s,
-                                   a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, nullptr, a.eps, nullptr);
+                                   a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, nullptr, a.eps, nullptr, 1);
                 return;
             }
             hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, true, 0>), grid, block, 0, s,
-                               a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, nullptr, 0.f, nullptr);
+                               a.W, a.codebook, a.X, a.Y, nv, a.scales, a.W2, a.codebook2, nullptr, 0.f, nullptr, 1);
             return;
         }
     }
@@ -766,7 +779,7 @@ static void launch_lut(const GemmArgs& a, hipStream_t s) {
     if constexpr (!SC) {                                      // decoder fusions (per-row-codebook format)
 #define KMQ_LUT_FUSED(F) \
         hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, false, false, F>), grid, block, 0, s, \
-                           a.W, a.codebook, a.X, a.Y, a.N, a.scales, nullptr, nullptr, a.norm_w, a.eps, a.residual)
+                           a.W, a.codebook, a.X, a.Y, a.N, a.scales, nullptr, nullptr, a.norm_w, a.eps, a.residual, 1)
         const int fuse = (a.norm ? (a.norm_w ? 1 : 4) : 0) | (a.residual ? 2 : 0);
         switch (fuse) {
             case 1: KMQ_LUT_FUSED(1); return;
@@ -778,8 +791,15 @@ static void launch_lut(const GemmArgs& a, hipStream_t s) {
         }
 #undef KMQ_LUT_FUSED
     }
+    if (a.M > 1) {                                            // batch: one workgroup per (row group, column)
+        const int64_t groups = (a.N + rows_wg - 1) / rows_wg;
+        const dim3 grid_m(static_cast<unsigned>((groups + 7) / 8 * 8 * a.M));
+        hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, SC, false, 0>), grid_m, block, 0, s,
+                           a.W, a.codebook, a.X, a.Y, a.N, a.scales, nullptr, nullptr, nullptr, 0.f, nullptr, a.M);
+        return;
+    }
     hipLaunchKernelGGL((gemv_lut_kernel<BITS, G, LPR, NWK, NWR, RS, WPE, SC, false, 0>), grid, block, 0, s,
-                       a.W, a.codebook, a.X, a.Y, a.N, a.scales, nullptr, nullptr, nullptr, 0.f, nullptr);
+                       a.W, a.codebook, a.X, a.Y, a.N, a.scales, nullptr, nullptr, nullptr, 0.f, nullptr, 1);
 }
 
 #define KMQ_LUT(BITS, G, LPR, NWK, NWR, RS, WPE) \

@@ -155,7 +155,8 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.kmq_gemv_blockscaled(W, cb, None, x, y, 4, 64, 2, 0, None, 0, None) == 1
     assert kmq.kernel_name_blockscaled(4, 96, 2, 1) == "invalid"
     assert kmq.kernel_name_blockscaled(8192, 8192, 4, 1).startswith("lut_sc_b4")
-    assert kmq.kernel_name_blockscaled(8192, 8192, 4, 16) == "blockscaled_generic"
+    assert kmq.kernel_name_blockscaled(8192, 8192, 4, 16).startswith("lut_sc_b4")    # canonical batch: table kernel over (row group, column)
+    assert kmq.kernel_name_blockscaled(100, 8192 + 64, 4, 16) == "blockscaled_generic"
     assert lib.kmq_gemv_bf16(None, x, y, 4, 64, None) == 1 and lib.kmq_gemv_bf16(W, x, y, 4, 40000, None) == 3
     assert lib.kmq_gemv_bf16(W + 2, x, y, 4, 64, None) == 4 and lib.kmq_gemv_bf16(W, x, y, 0, 64, None) == 3
     for s in range(9):
@@ -230,11 +231,11 @@ def test_argument_errors_of_the_later_calls_and_the_size_limits():
     assert kmq.workspace_bytes(1, top, 2, 16) == 64 * 16 * 1 * 4
 
 
-def test_per_column_choice_follows_the_cost_model():
-    assert kmq.kernel_name(9216, 3072, 1, 4).startswith("lut_b1")          # table kernel per column
-    assert kmq.kernel_name(14336, 4096, 2, 4).startswith("lut_b2")
-    assert kmq.kernel_name(4096, 4096, 4, 4) == "generic"                   # small 4-bit matrix: one pass of the generic kernel is cheaper
-    assert kmq.kernel_name(9216, 3072, 1, 5) == "generic" and kmq.kernel_name(9216, 3072, 1, 16) == "generic"
+def test_batches_on_the_canonical_layout_take_the_table_kernels():
+    assert kmq.kernel_name(9216, 3072, 1, 4).startswith("lut_b1")          # table kernel, one workgroup per (row group, column)
+    assert kmq.kernel_name(14336, 4096, 2, 4).startswith("lut_b2") and kmq.kernel_name(14336, 4096, 2, 16).startswith("lut_b2")
+    assert kmq.kernel_name(4096, 4096, 4, 2).startswith("lut_b4")
+    assert kmq.kernel_name(4096, 4096, 4, 16).startswith("lut_b4") and kmq.kernel_name(2048, 2048, 1, 8).startswith("lut_b1")
     assert kmq.kernel_name(100, 515, 2, 2) == "generic"                     # no table kernel for this K
     assert kmq.kernel_name_blockscaled(8192, 8192, 4, 4).startswith("lut_sc_b4")
-    assert kmq.kernel_name_blockscaled(8192, 8192, 4, 8) == "blockscaled_generic"
+    assert kmq.kernel_name_blockscaled(8192, 8192, 4, 16).startswith("lut_sc_b4")

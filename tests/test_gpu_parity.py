@@ -236,11 +236,14 @@ def test_degenerate_inputs(gpu):
 
 @pytest.mark.parametrize("bits,N,K,M", [(1, 9216, 3072, 4), (1, 300, 3072, 2), (2, 1000, 4096, 3), (2, 333, 14336, 4),
                                         (4, 4096, 4096, 2), (4, 77, 8192, 4), (1, 64, 8192, 3),
-                                        (3, 1000, 4096, 2), (3, 4096, 14336, 4), (3, 130, 2048, 3)])
-def test_small_batches_on_the_canonical_layout_per_column(gpu, bits, N, K, M):
-    """Batches 2..4 on the canonical layout may run the batch-1 table kernel once per column (a cost model in
-    the heuristic decides): whatever is chosen must match the oracle, and a per-column result is the batch-1
-    result of each column bit for bit."""
+                                        (3, 1000, 4096, 2), (3, 4096, 14336, 4), (3, 130, 2048, 3),
+                                        (2, 14336, 4096, 16), (1, 9216, 3072, 7), (3, 17, 4096, 16), (4, 64, 8192, 9),
+                                        (2, 7, 2048, 5), (1, 4090, 2048, 16), (3, 1500, 3072, 8)])
+def test_batches_on_the_canonical_layout_per_column(gpu, bits, N, K, M):
+    """Batches on the canonical layout may run the batch-1 table kernel over a (row group, column) grid in one
+    launch (a cost model in the heuristic decides): whatever is chosen must match the oracle, and a per-column
+    result is the batch-1 result of each column bit for bit.  Row counts that leave the padded grid (a multiple
+    of 8 row groups per column) partly empty are part of the list."""
     from paper_2602_15563_amd import kmq
     seed = 900 + bits + M
     idx = synth.make_indices(seed, 0, N, K, bits)
