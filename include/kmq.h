@@ -136,7 +136,10 @@ kmq_status kmq_gemv(const uint32_t* W, const uint16_t* codebook, const uint16_t*
 /* Y = X W^T for 1 <= M <= KMQ_MAX_BATCH (paper App. D/E: the small-batch,
  * memory-bound regime; larger batches are better served by kmq_dequant plus a
  * dense GEMM, App. E "Model benchmarks").  X is M x K bf16 row-major (16-byte
- * aligned), Y is M x N bf16 row-major, overwritten.  Other arguments as kmq_gemv. */
+ * aligned), Y is M x N bf16 row-major, overwritten.  Other arguments as kmq_gemv.
+ * Both layouts are accepted at every M.  KMQ_LAYOUT_TILED is the fast one for M > 1
+ * (matrix-core kernel: a weight is dequantised once for the whole batch); on the
+ * canonical layout every batch column looks the weights up again, in one launch. */
 kmq_status kmq_gemm_smallbatch(const uint32_t* W, const uint16_t* codebook, const uint16_t* X,
                                uint16_t* Y, int64_t N, int64_t K, int M, int bits, int layout,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
