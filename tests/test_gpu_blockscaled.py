@@ -91,10 +91,13 @@ def test_papers_benchmark_shape_full_size(gpu, bits):
 
 
 @pytest.mark.parametrize("bits", (1, 2, 3, 4))
-@pytest.mark.parametrize("N,K,M", [(16, 512, 16), (40, 1024, 4), (97, 4096, 8), (333, 3072, 1), (64, 8192, 16), (130, 2048, 2)])
+@pytest.mark.parametrize("N,K,M", [(16, 512, 16), (40, 1024, 4), (97, 4096, 8), (333, 3072, 1), (64, 8192, 16), (130, 2048, 2),
+                                   (20, 384, 5), (70, 640, 16), (5000, 8192, 3), (33, 16384, 16), (50, 1536, 7)])
 def test_tiled_layout_matrix_core_vs_oracle(gpu, bits, N, K, M):
     """The block-scaled product on the tiled layout (matrix-core kernel), ragged row counts, every
-    batch kind, K with 1..16 super-blocks per wave."""
+    batch kind, K with 1..16 super-blocks per wave; numbers of blocks that are and are not multiples of
+    eight (two ways of staging the scales); long rows with few and with many row blocks (4-bit: with and
+    without the table of centroid pairs)."""
     from paper_2602_15563_amd import kmq
     if kmq.tiled_words(N, K, bits, 1) < 0:
         pytest.skip("K is not a whole number of super-blocks at this bit-width")
