@@ -344,22 +344,18 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     static_assert(!SC || EL % KMQ_BLOCK == 0 || KMQ_BLOCK % EL == 0, "lane slices must not straddle blocks");
     static_assert(!SC || NSC == 1 || (BITS == 1 && NSC == 2), "block sums kept by the pipeline");
 
-    // Staged x is swizzled per lane slice so that a wave's 16-byte reads spread over the banks: chunk q of
-    // slice sl sits at position q ^ (sl mod C16) when C16 is a power of two (one XOR per read address),
-    // else at (q + sl) mod C16.
-    constexpr bool C16_POW2 = (C16 & (C16 - 1)) == 0;
-    auto swz = [](int q, int sl) -> int {
-        if constexpr (C16_POW2) return q ^ (sl & (C16 - 1));
-        else return (q + sl) % C16;
-    };
+    // Staged x is padded per lane slice so that a wave's 16-byte reads spread over the banks: a slice of C16
+    // chunks takes XSTR chunks (an odd number), chunk q of slice sl sits at sl * XSTR + q -- one base
+    // register per lane, the chunk number goes into the instruction's offset field.
+    constexpr int XSTR = C16 | 1;
 
     struct alignas(256) Smem {
         // 2/3/4-bit: per wave and row group, RS tables of ENT x 4 B; 1-bit: lut[0] holds the 16 x 8 B mask table
         uint32_t lut[LUT_GROUPS][TBL];
-        // staged activations, swizzled per lane slice; threads past the end of x (the
+        // staged activations, padded per lane slice; threads past the end of x (the
         // thread count need not divide the chunk count) write clamped data into the tail,
         // so that staging has no branch for the loads to be sunk into
-        u32x4_t xs[(XSLOTS + C16 - 1) / C16 * C16];
+        u32x4_t xs[(XSLOTS + C16 - 1) / C16 * XSTR];
         float part[NWK][ROWS_WG];                  // per-slice partial sums
         float sxp[NWK];                            // 1-bit: per-slice sum of x
         float ssq[NWK * NWR];                      // RMSNorm: per-wave sum of x^2 over the chunks the wave staged
@@ -497,15 +493,8 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     }
     // where this lane will read its slice of x from: computed now, while the loads are in flight,
     // and pinned here so that it is not scheduled behind the wait for x
-    int xidx[C16];
-    {
-        const int sl = wk * LPR + pos;
-#pragma unroll
-        for (int q = 0; q < C16; ++q) {
-            xidx[q] = sl * C16 + swz(q, sl);
-            asm volatile("" : "+v"(xidx[q]));
-        }
-    }
+    int xbase = (wk * LPR + pos) * XSTR;
+    asm volatile("" : "+v"(xbase));
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
 
@@ -533,7 +522,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     for (int h = 0; h < XPT; ++h) {
         const int c = threadIdx.x * XPT + h;
         const int sl = c / C16, q = c % C16;
-        sm.xs[sl * C16 + swz(q, sl)] = u32x4_t{xt[4 * h], xt[4 * h + 1], xt[4 * h + 2], xt[4 * h + 3]};
+        sm.xs[sl * XSTR + q] = u32x4_t{xt[4 * h], xt[4 * h + 1], xt[4 * h + 2], xt[4 * h + 3]};
     }
     if constexpr (BITS == 1) {
         if (threadIdx.x < 16) {
@@ -551,7 +540,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     {
 #pragma unroll
         for (int q = 0; q < C16; ++q) {
-            const u32x4_t v = sm.xs[xidx[q]];
+            const u32x4_t v = sm.xs[xbase + q];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if constexpr (BITS == 4) {
