@@ -66,6 +66,7 @@ for _h in (2048, 4096, 8192):
 # Triton kernels on an NVIDIA L40S, 864 GB/s): effective GB/s, us per call.
 PAPER_NUMBERS = {"paper_b4s_8192x8192_m1": (721.0, 49.5), "paper_b1s_8192x8192_m1": (438.0, 24.0)}
 HEADLINE = "cfg2_gateup_b2_14336x4096_m1"
+LAYOUT_NAMES = {0: "canonical", 1: "tiled", 2: "rowlane"}
 TRAFFIC_SUMMARIES = {HEADLINE: "gemv_b2_14336x4096_m1_pmc_traffic.txt"}
 
 
@@ -110,11 +111,11 @@ class Instances:
         self.repack_ms = None
         wpr = self.packed.shape[1]
         stored = self.packed
-        if self.layout == 1:
+        if self.layout != 0:
             t0 = time.perf_counter()
-            stored = kmq.repack(self.packed, K, bits, 1).reshape(-1, wpr)
+            stored = kmq.repack(self.packed, K, bits, self.layout).reshape(-1, wpr)
             self.repack_ms = (time.perf_counter() - t0) * 1e3
-            assert np.array_equal(kmq.unrepack(stored, N, K, bits, 1), self.packed)
+            assert np.array_equal(kmq.unrepack(stored, N, K, bits, self.layout), self.packed)
         nrows_stored = stored.shape[0]
         g = torch.Generator(device="cuda")
         g.manual_seed(1234 + seed)
@@ -381,7 +382,7 @@ def run_sweep(M: int, replays: int, fuse: str = ""):
             "passes_per_s": round(1e6 / us, 1),
             "calls": calls, "GBps": round(nbytes / us * 1e-3, 1), "pct_peak": round(100 * nbytes / us * 1e-3 / HBM_PEAK_GBS, 2),
             "bytes": nbytes, "kernels": sorted({it.kernel for it in insts}),
-            "layout": "tiled" if insts[0].layout else "canonical", "max_err_over_A": float(f"{worst:.3e}")}
+            "layout": LAYOUT_NAMES[insts[0].layout], "max_err_over_A": float(f"{worst:.3e}")}
 
 
 def time_bf16_baseline(N: int, K: int, steps: int):
@@ -633,8 +634,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-cache-resident", action="store_true",
                     help="skip the secondary same-matrix-every-call timing (keeps a kernel trace to the cold calls)")
-    ap.add_argument("--layout", type=int, default=None, choices=(0, 1),
-                    help="0 canonical, 1 tiled (default: canonical for batch 1, tiled for batch > 1)")
+    ap.add_argument("--layout", type=int, default=None, choices=(0, 1, 2),
+                    help="0 canonical, 1 tiled (matrix-core order), 2 row-lane (default: canonical for batch 1, tiled for batch > 1)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the timed region, launch a plain 64 MiB device copy 10 times: a kernel of known "
                          "traffic against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -682,7 +683,7 @@ def main():
         "vs_baseline": round(gbs / PAPER_NUMBERS[args.workload][0], 3) if args.workload in PAPER_NUMBERS else None,
         "dtype": "bf16", "accumulate_dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "bits": inst.bits, "N": inst.N, "K": inst.K, "batch": inst.M,
-                   "kernel": inst.kernel, "layout": "tiled" if inst.layout else "canonical",
+                   "kernel": inst.kernel, "layout": LAYOUT_NAMES[inst.layout],
                    "rotating_instances": inst.R, "hip_graph": not args.no_graph,
                    "algorithmic_bytes_per_call": inst.bytes, "max_err_over_A_vs_oracle": float(f"{worst:.3e}"),
                    "clocks_before_run": clocks,
@@ -721,7 +722,7 @@ def main():
             it = Instances(name)
             w = it.check()
             s, n = time_workload(it, 5000, 100)
-            rows.append({"workload": name, "kernel": it.kernel, "layout": "tiled" if it.layout else "canonical",
+            rows.append({"workload": name, "kernel": it.kernel, "layout": LAYOUT_NAMES[it.layout],
                          "us_per_call": round(s / n * 1e6, 3),
                          "GBps": round(it.bytes / (s / n) / 1e9, 1),
                          "pct_peak": round(100 * it.bytes / (s / n) / 1e9 / HBM_PEAK_GBS, 2),

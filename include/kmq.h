@@ -58,7 +58,8 @@ enum {
 
 enum {
     KMQ_LAYOUT_CANONICAL = 0, /* the format above */
-    KMQ_LAYOUT_TILED = 1      /* GPU tile order, see kmq_repack */
+    KMQ_LAYOUT_TILED = 1,     /* matrix-core operand order, see kmq_repack */
+    KMQ_LAYOUT_ROWLANE = 2    /* lane-per-row order of the batch 1..4 kernels, see kmq_repack */
 };
 
 #define KMQ_MAX_BATCH 16

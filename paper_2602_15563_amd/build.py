@@ -16,13 +16,17 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libkmq.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
 
-SOURCES = ["kmq_host.cpp", "kmq_generic.hip", "kmq_lut.hip", "kmq_mfma.hip", "kmq_blockscaled.hip", "kmq_dense.hip", "kmq_quantize.hip", "kmq_fused.hip", "kmq_api.hip"]
+SOURCES = ["kmq_host.cpp", "kmq_generic.hip", "kmq_lut.hip", "kmq_rowlane.hip", "kmq_mfma.hip", "kmq_blockscaled.hip", "kmq_dense.hip", "kmq_quantize.hip", "kmq_fused.hip", "kmq_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed-fp32 code generation is switched off on purpose: some packed forms have given
          # wrong results on this hardware; ordinary float code loses nothing measurable here
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+if os.environ.get("KMQ_TUNING"):      # launch-shape overrides from the environment, for sweeps; never in a normal build
+    FLAGS.append("-DKMQ_TUNING")
+if os.environ.get("KMQ_TIMESTAMPS"):  # per-wave time stamps in the row-lane kernel (slower; for taking a kernel apart)
+    FLAGS.append("-DKMQ_TIMESTAMPS")
 
 
 def _compile(src: str) -> str:

@@ -31,7 +31,12 @@ static bool per_column_faster(int M) {
 Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled) {
     Plan p{kVariantInvalid, -1, 0, "invalid"};
     if (!bits_valid(bits) || !dims_valid(N, K) || M < 1 || M > KMQ_MAX_BATCH) return p;
-    if (layout != KMQ_LAYOUT_CANONICAL && layout != KMQ_LAYOUT_TILED) return p;
+    if (layout != KMQ_LAYOUT_CANONICAL && layout != KMQ_LAYOUT_TILED && layout != KMQ_LAYOUT_ROWLANE) return p;
+    if (layout == KMQ_LAYOUT_ROWLANE) {
+        if (scaled || !rowlane_valid(bits, K) || !rowlane_has_kernel(K, bits, M)) return p;
+        static const char* const names[2] = {"rowlane_b1", "rowlane_b2"};
+        return Plan{kVariantRowlane, -1, 0, names[bits - 1]};
+    }
     if (scaled) {
         if (K % KMQ_BLOCK != 0) return p;
         if (layout == KMQ_LAYOUT_TILED) {
@@ -76,8 +81,9 @@ static kmq_status check_and_run(const GemmArgs& a, void* stream) {
     if (!a.W || !a.codebook || !a.X || !a.Y) return KMQ_ERR_NULL;
     if (!bits_valid(a.bits)) return KMQ_ERR_BITS;
     if (!dims_valid(a.N, a.K) || a.M < 1 || a.M > KMQ_MAX_BATCH) return KMQ_ERR_SHAPE;
-    if (a.layout != KMQ_LAYOUT_CANONICAL && a.layout != KMQ_LAYOUT_TILED) return KMQ_ERR_LAYOUT;
+    if (a.layout != KMQ_LAYOUT_CANONICAL && a.layout != KMQ_LAYOUT_TILED && a.layout != KMQ_LAYOUT_ROWLANE) return KMQ_ERR_LAYOUT;
     if (a.layout == KMQ_LAYOUT_TILED && !tiled_valid(a.bits, a.K)) return KMQ_ERR_LAYOUT;
+    if (a.layout == KMQ_LAYOUT_ROWLANE && (!rowlane_valid(a.bits, a.K) || a.scales)) return KMQ_ERR_LAYOUT;
     if (!aligned(a.W, 16) || !aligned(a.X, 16) || !aligned(a.codebook, 4) || !aligned(a.Y, 2)) return KMQ_ERR_ALIGN;
     const bool scaled = a.scales != nullptr;
     if (scaled) {
@@ -86,12 +92,13 @@ static kmq_status check_and_run(const GemmArgs& a, void* stream) {
         if (!aligned(a.scales, 2)) return KMQ_ERR_ALIGN;
     }
     const Plan plan = make_plan(a.N, a.K, a.bits, a.M, a.layout, scaled);
-    if (plan.variant == kVariantInvalid) return KMQ_ERR_SHAPE;
+    if (plan.variant == kVariantInvalid) return a.layout == KMQ_LAYOUT_ROWLANE ? KMQ_ERR_LAYOUT : KMQ_ERR_SHAPE;
     if (plan.workspace_bytes > 0 && (!a.workspace || a.workspace_bytes < plan.workspace_bytes)) return KMQ_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
     switch (plan.variant) {
         case kVariantMfma: e = launch_mfma(a, s); break;
+        case kVariantRowlane: e = launch_rowlane(a, s); break;
         case kVariantLut: e = launch_lut_entry(plan.table_index, a, s); break;
         case kVariantPerColumn:                               // one launch, a workgroup per (row group, column)
             e = launch_lut_entry(plan.table_index, a, s);   // K is a multiple of 8 for every table kernel: rows of X stay 16-byte aligned

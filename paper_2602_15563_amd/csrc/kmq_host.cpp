@@ -77,6 +77,10 @@ int64_t kmq_tiled_words(int64_t N, int64_t K, int bits, int layout) {
         if (!kmq::tiled_valid(bits, K)) return -1;
         return kmq::round_up(N, kmq::kTileRows) * wpr;
     }
+    if (layout == KMQ_LAYOUT_ROWLANE) {
+        if (!kmq::rowlane_valid(bits, K)) return -1;
+        return kmq::round_up(N, kmq::kTileRows) * wpr;
+    }
     return -1;
 }
 
@@ -90,7 +94,11 @@ static kmq_status repack_impl(const uint32_t* src, int64_t N, int64_t K, int bit
         std::memcpy(dst, src, static_cast<size_t>(N * wpr) * sizeof(uint32_t));
         return KMQ_OK;
     }
-    if (layout != KMQ_LAYOUT_TILED || !kmq::tiled_valid(bits, K)) return KMQ_ERR_LAYOUT;
+    if (layout == KMQ_LAYOUT_ROWLANE) {
+        if (!kmq::rowlane_valid(bits, K)) return KMQ_ERR_LAYOUT;
+    } else if (layout != KMQ_LAYOUT_TILED || !kmq::tiled_valid(bits, K)) {
+        return KMQ_ERR_LAYOUT;
+    }
     const int64_t nrows_padded = kmq::round_up(N, kmq::kTileRows);
     if (forward) std::memset(dst, 0, static_cast<size_t>(nrows_padded * wpr) * sizeof(uint32_t));
     else         std::memset(dst, 0, static_cast<size_t>(N * wpr) * sizeof(uint32_t));
@@ -98,15 +106,18 @@ static kmq_status repack_impl(const uint32_t* src, int64_t N, int64_t K, int bit
     uint32_t* canon_out = forward ? nullptr : dst;
     const uint32_t* tiled_in = forward ? nullptr : src;
     uint32_t* tiled_out = forward ? dst : nullptr;
-    const int gpg = kmq::tiled_groups_per_granule(bits);
+    const bool rowlane = layout == KMQ_LAYOUT_ROWLANE;
+    const int gpg = rowlane ? 1 : kmq::tiled_groups_per_granule(bits);
+    const int64_t ce = rowlane ? kmq::rowlane_chunk_elems(bits) : 1;
     for (int64_t n = 0; n < N; ++n) {
         for (int64_t k = 0; k < K; ++k) {
             const int64_t g = (k % (32 * gpg)) / 8;
             const int j = static_cast<int>(g / 4), e = static_cast<int>(k % 8);
-            const int64_t gd = kmq::tiled_granule_dword(bits, K, n, k);
+            const int64_t gd = rowlane ? kmq::rowlane_chunk_dword(bits, K, n, k) : kmq::tiled_granule_dword(bits, K, n, k);
             for (int t = 0; t < bits; ++t) {
                 const int64_t cp = k * bits + t;                       // canonical stream bit of this row
-                const int tp = kmq::tiled_bit_position(bits, j, e, t);
+                const int tp = rowlane ? kmq::rowlane_bit_position(bits, static_cast<int>(k % ce), t)
+                                       : kmq::tiled_bit_position(bits, j, e, t);
                 if (forward) {
                     const uint32_t bit = (canon[n * wpr + (cp >> 5)] >> (cp & 31)) & 1u;
                     tiled_out[gd + (tp >> 5)] |= bit << (tp & 31);

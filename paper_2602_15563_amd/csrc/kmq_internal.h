@@ -63,6 +63,40 @@ KMQ_HD inline int tiled_bit_position(int bits, int j, int e, int t) {
     }
 }
 
+// KMQ_LAYOUT_ROWLANE (see include/kmq.h).  A chunk is 16 bytes of one row (128 / bits elements);
+// a tile is 16 rows x 4 consecutive chunks, stored lane-major: lane kp*16 + r holds chunk kp of
+// row r.  Tiles of a 16-row block follow each other along K.
+KMQ_HD inline bool rowlane_bits(int bits) { return bits == 1 || bits == 2; }
+KMQ_HD inline int64_t rowlane_chunk_elems(int bits) { return 128 / bits; }
+KMQ_HD inline bool rowlane_valid(int bits, int64_t K) { return rowlane_bits(bits) && K % (4 * rowlane_chunk_elems(bits)) == 0; }
+
+// Dword offset in the row-lane stream of the chunk that holds element k of row n.
+KMQ_HD inline int64_t rowlane_chunk_dword(int bits, int64_t K, int64_t n, int64_t k) {
+    const int64_t ce = rowlane_chunk_elems(bits), te = 4 * ce;
+    const int64_t tiles = K / te;
+    const int64_t t = k / te, kp = (k % te) / ce;
+    const int64_t rb = n / kTileRows, r = n % kTileRows;
+    return ((rb * tiles + t) * 64 + kp * 16 + r) * 4;
+}
+
+// Inside a chunk: bit position (0..127, dword-major) of bit t of the index of element c of the chunk.
+// 2-bit: pairs of elements travel as nibbles; nibble slot s = 8*word + position is consumed against
+//        the activation pair that lane s % 16 holds in register s / 16 after an 8-byte load per lane,
+//        i.e. pair 2*(s % 16) + s / 16 of the chunk.
+// 1-bit: four elements travel as a nibble; slot s = 8*word + 2*byte + view holds elements 4s..4s+3.
+//        View 0 nibbles sit at bits 3..6 of each byte; view 1 nibbles at bits 7, 8, 9, 10 (mod 32)
+//        above the byte's start, which a rotation of the word by 4 brings to bits 3..6 as well.
+KMQ_HD inline int rowlane_bit_position(int bits, int c, int t) {
+    if (bits == 2) {
+        const int p = c >> 1, e = c & 1;
+        const int s = (p >> 1) + 16 * (p & 1);
+        return 4 * s + 2 * e + t;
+    }
+    const int s = c >> 2, i = c & 3;
+    const int q = s >> 3, b = (s & 7) >> 1, view = s & 1;
+    return 32 * q + (view ? (8 * b + 7 + i) % 32 : 8 * b + 3 + i);
+}
+
 }  // namespace kmq
 
 #endif

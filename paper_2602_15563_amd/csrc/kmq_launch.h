@@ -35,6 +35,7 @@ enum Variant {
     kVariantMfma,        // tiled layout, batch 1..16: matrix-core kernel
     kVariantBlockGeneric,  // block-scaled format, any shape with K % 64 == 0
     kVariantPerColumn,     // canonical layout, batch > 1, shape with a batch-1 table kernel: that kernel over a (row group, column) grid
+    kVariantRowlane,       // row-lane layout, batch 1..4: lane-per-row table kernel, activations through DPP broadcasts
 };
 
 struct Plan {
@@ -74,6 +75,10 @@ hipError_t launch_stream_read(const void* p, size_t bytes, void* sink, hipStream
 hipError_t launch_mfma(const GemmArgs& a, hipStream_t s);
 int mfma_waves_along_k(int64_t N, int64_t K, int bits);
 int mfma_row_blocks(int64_t N, int64_t K, int bits);
+
+// Row-lane layout kernels (batch 1..4).
+bool rowlane_has_kernel(int64_t K, int bits, int M);
+hipError_t launch_rowlane(const GemmArgs& a, hipStream_t s);
 
 // Hand-scheduled table kernels (1/2/4-bit): -1 if (bits, K, layout) has none.
 int lut_find(int64_t N, int64_t K, int bits, int layout, bool scaled = false);

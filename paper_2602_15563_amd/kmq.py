@@ -34,7 +34,7 @@ _preload_torch_hip_runtime()
 _lib = ctypes.CDLL(LIB_PATH)
 
 OK = 0
-LAYOUT_CANONICAL, LAYOUT_TILED = 0, 1
+LAYOUT_CANONICAL, LAYOUT_TILED, LAYOUT_ROWLANE = 0, 1, 2
 MAX_BATCH = 16
 
 _i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
