@@ -67,7 +67,7 @@ for _h in (2048, 4096, 8192):
 PAPER_NUMBERS = {"paper_b4s_8192x8192_m1": (721.0, 49.5), "paper_b1s_8192x8192_m1": (438.0, 24.0)}
 HEADLINE = "cfg2_gateup_b2_14336x4096_m1"
 LAYOUT_NAMES = {0: "canonical", 1: "tiled", 2: "rowlane"}
-TRAFFIC_SUMMARIES = {HEADLINE: "gemv_b2_14336x4096_m1_pmc_traffic.txt"}
+PROFILE_SUMMARIES = {HEADLINE: "gemv_b2_14336x4096_m1_rowlane.txt"}
 
 
 def _dev(a):
@@ -94,9 +94,12 @@ class Instances:
         if M is not None:
             self.M = M
         bits, N, K, M = self.bits, self.N, self.K, self.M
-        # batch > 1 runs on the tiled (matrix-core) layout by default: the offline,
-        # reversible repack is outside the timed region
-        self.layout = (1 if M > 1 else 0) if layout is None else layout
+        # Default layouts (the offline, reversible repack is outside the timed region): 2-bit products at
+        # batch <= 4 run on the row-lane layout (lane-per-row kernels on the vector units), every other
+        # batch > 1 on the tiled (matrix-core) layout, the rest on the canonical one.
+        if layout is None:
+            layout = 2 if (bits == 2 and M <= 4 and not self.scaled) else (1 if M > 1 else 0)
+        self.layout = layout
         self.bytes = (synth.algorithmic_bytes_blockscaled if self.scaled else synth.algorithmic_bytes)(N, K, bits, M)
         self.R = max(2, -(-2 * LLC_BYTES // self.bytes)) if rotate else 1
         self.R = min(self.R, 2048) if R is None else R
@@ -191,7 +194,7 @@ def time_workload(inst: Instances, steps: int, warmup: int, use_graph: bool = Tr
         stream.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         if use_graph:
-            n_replays = max(1, steps // CALLS_PER_GRAPH)
+            n_replays = max(10, steps // CALLS_PER_GRAPH)    # never fewer than ten replays: the spread is part of the result
             steps = n_replays * CALLS_PER_GRAPH
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=stream):
@@ -432,45 +435,86 @@ def time_bf16_baseline(N: int, K: int, steps: int):
     return {"us_per_call": round(us, 3), "GB/s": round(nbytes / us * 1e-3, 1), "bytes": nbytes, "rotating_instances": R}
 
 
-def time_read_ceiling(inst: Instances, steps: int):
-    """Pure read of the same packed index streams (same rotation, same graph replay)."""
+def _graph_us_per_call(launch, replays: int):
+    """us per call of launch(i), i = 0..99, captured into one HIP graph and replayed."""
     import torch
-
-    from paper_2602_15563_amd import kmq
     stream = torch.cuda.Stream()
-    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     with torch.cuda.stream(stream):
         for i in range(20):
-            kmq.stream_read(inst.W[i % inst.R], sink)
+            launch(i)
         stream.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=stream):
             for i in range(CALLS_PER_GRAPH):
-                kmq.stream_read(inst.W[i % inst.R], sink)
+                launch(i)
         graph.replay()
         stream.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        n = max(1, steps // CALLS_PER_GRAPH)
         e0.record(stream)
-        for _ in range(n):
+        for _ in range(replays):
             graph.replay()
         e1.record(stream)
         stream.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / (n * CALLS_PER_GRAPH)
-    nbytes = inst.W[0].numel() * 4
-    return {"us_per_call": round(us, 3), "GB/s": round(nbytes / us * 1e-3, 1), "bytes": nbytes,
-            "what": "kmq_stream_read over the same rotating index streams (reads only, no decode)"}
+    return e0.elapsed_time(e1) * 1e3 / (replays * CALLS_PER_GRAPH)
 
 
-def measured_traffic(workload: str):
-    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", TRAFFIC_SUMMARIES.get(workload, "_none_"))
+def time_launch_floor(replays: int = 20):
+    """What a call costs when the kernel does nothing: empty kernels (kmq_probe_empty) through the same
+    100-call graph protocol, at the launch shapes the product kernels use."""
+    import torch
+
+    from paper_2602_15563_amd import probe
+    sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
+    shapes = {"1x64": (1, 64), "896x512": (896, 512), "1792x256": (1792, 256), "256x1024": (256, 1024), "3584x256": (3584, 256)}
+    return {k: round(_graph_us_per_call(lambda i, g=g, b=b: probe.empty(g, b, sink), replays), 3) for k, (g, b) in shapes.items()}
+
+
+def time_read_ceiling(inst: Instances, replays: int = 20):
+    """Pure reads (kmq_probe_read: no decode, no store) of the same rotating index streams, and of a
+    134 MB buffer, through the same graph protocol: every probe variant, the best one reported."""
+    import torch
+
+    from paper_2602_15563_amd import probe
+    names = probe.read_variants()
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = {}
+    big = [torch.empty(134217728 // 4, dtype=torch.int32, device="cuda").random_() for _ in range(5)]
+    for label, bufs, rep in (("same_bytes", inst.W, replays), ("134MB", big, 3)):
+        nbytes = bufs[0].numel() * 4
+        rows = {}
+        for v, name in enumerate(names):
+            rows[name] = round(_graph_us_per_call(lambda i, v=v: probe.read(bufs[i % len(bufs)], v, sink), rep), 3)
+        best = min(rows, key=rows.get)
+        out[label] = {"bytes": nbytes, "best_variant": best, "us_per_call": rows[best],
+                      "GB/s": round(nbytes / rows[best] * 1e-3, 1), "all_variants_us": rows}
+    del big
+    torch.cuda.empty_cache()
+    out["us_per_call"] = out["same_bytes"]["us_per_call"]
+    out["GB/s"] = out["same_bytes"]["GB/s"]
+    out["what"] = "kmq_probe_read (libkmq_probe.so): reads only, no decode, no store; best of the listed variants"
+    return out
+
+
+def committed_profile(workload: str, kernel: str):
+    """Figures of the committed rocprofv3 summaries for this workload, or None where there is no summary or
+    it was taken with another kernel than the one this run times (then the figures do not describe it).
+    The summaries state: kernel = <name>, traffic_bytes_per_launch = <HBM bytes from FETCH_SIZE + WRITE_SIZE,
+    scaled by a copy of known size>, kernel_us_avg / kernel_us_median = <kernel-trace durations>."""
+    path = os.path.join(ROOT, "profiles", PROFILE_SUMMARIES.get(workload, "_none_"))
     if not os.path.exists(path):
         return None
+    vals = {}
     for line in open(path):
-        if line.startswith("traffic_bytes_per_launch"):
-            return int(line.split("=")[1])
-    return None
+        if "=" in line and not line.startswith(("#", " ")):
+            k, v = line.split("=", 1)
+            vals[k.strip()] = v.strip()
+    if vals.get("kernel") != kernel:
+        return None
+    out = {"file": "profiles/" + PROFILE_SUMMARIES[workload]}
+    for k in ("traffic_bytes_per_launch", "kernel_us_avg", "kernel_us_median"):
+        if k in vals:
+            out[k] = float(vals[k]) if "us" in k else int(vals[k])
+    return out
 
 
 def run_large_batch(h: int = 8192, batches=(16, 64, 256), replays: int = 5):
@@ -632,6 +676,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch directly instead of replaying a HIP graph")
     ap.add_argument("--no-rotate", action="store_true", help="reuse one instance (cache-resident, NOT the headline)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-probes", action="store_true", help="skip the launch-floor and read-ceiling probes")
     ap.add_argument("--no-cache-resident", action="store_true",
                     help="skip the secondary same-matrix-every-call timing (keeps a kernel trace to the cold calls)")
     ap.add_argument("--layout", type=int, default=None, choices=(0, 1, 2),
@@ -690,10 +735,18 @@ def main():
                    "offline_host_ms": {"kmq_pack": round(inst.pack_ms, 2),
                                        "kmq_repack": None if inst.repack_ms is None else round(inst.repack_ms, 2)}},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.workload),
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
                      "note": "achieved = algorithmic bytes per launch / average launch-to-launch time "
-                             "(HIP events on the launch stream around the timed region)"},
+                             "(HIP events on the launch stream around the timed region); traffic and kernel_us_* come "
+                             "from the committed rocprofv3 summary named in profile_file, and are null when that summary "
+                             "was taken with another kernel than this run's"},
     }
+    prof = committed_profile(args.workload, inst.kernel)
+    if prof:
+        out["roofline"]["traffic"] = prof.get("traffic_bytes_per_launch")
+        out["roofline"]["kernel_us_avg"] = prof.get("kernel_us_avg")
+        out["roofline"]["kernel_us_median"] = prof.get("kernel_us_median")
+        out["roofline"]["profile_file"] = prof["file"]
     if args.workload in PAPER_NUMBERS:
         out["config"]["paper"] = {"GB/s": PAPER_NUMBERS[args.workload][0], "us_per_call": PAPER_NUMBERS[args.workload][1],
                                   "hardware": "NVIDIA L40S (864 GB/s), Triton kernel, paper App. E; another machine: context only"}
@@ -706,7 +759,9 @@ def main():
         out["config"]["bf16_baseline"] = base
         out["config"]["speedup_vs_bf16"] = round(base["us_per_call"] / us, 2)
         out["config"]["model_max_speedup"] = round(model.speedup(16.0, inst.bits + 0.25, inst.M, nu), 2)
-    out["roofline"]["read_ceiling"] = time_read_ceiling(inst, min(steps, 5000))
+    if not args.no_probes:
+        out["roofline"]["floor_us"] = time_launch_floor()
+        out["roofline"]["read_ceiling"] = time_read_ceiling(inst)
     if not args.no_rotate and not args.no_graph and not args.no_cache_resident:
         # secondary figure, NOT the headline: the same matrix every call, so it is served from the caches
         one = Instances(args.workload, rotate=False, layout=args.layout)

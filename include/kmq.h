@@ -105,7 +105,26 @@ kmq_status kmq_unpack(const uint32_t* packed, int64_t N, int64_t K, int bits, ui
  * The 2- and 3-bit orders spread the fields so that at most one shift and one
  * AND leave four indices in the four bytes of a register (3-bit, step 3: two of each).  Requires K % (32*gpg) == 0
  * (else KMQ_ERR_LAYOUT).  Same size as the canonical stream with rows padded
- * to 16: size `tiled` with kmq_tiled_words(). */
+ * to 16: size `tiled` with kmq_tiled_words().
+ *
+ * KMQ_LAYOUT_ROWLANE (bits = 1 or 2, K % 256 == 0, else KMQ_ERR_LAYOUT) is the order of the
+ * lane-per-row kernels that serve batches 1..4 without the matrix cores (a weight is decoded
+ * once per launch of up to four batch columns; wider batches take several launches).  A CHUNK is
+ * 64 consecutive elements of a row (2*bits dwords); a TILE is 16 rows x 4 consecutive chunks,
+ * 64 chunks stored one after the other, chunk kp of row 16*rb + r at dword offset
+ *     ((rb * (K/256) + t) * 64 + kp*16 + r) * 2*bits          (t = tile number along K),
+ * so a wave's load of one tile is contiguous, the 16 lanes that share a chunk number hold 16
+ * different rows, and the activations of chunk kp are 32 bf16 pairs, two per lane.  Inside a chunk
+ * (bit positions count through its dwords, LSB first), bit u of the index of element c (0..63):
+ *     bits = 2:  p = c/2 (pair), s = p/2 + 16*(p%2):    4*s + 2*(c%2) + u
+ *                (nibble slot s, 8 per dword, holds the pair whose activations sit in lane s%16,
+ *                register s/16, after one 8-byte load per lane)
+ *     bits = 1:  s = c/4, q = s/8, b = (s%8)/2, view = s%2, i = c%4:
+ *                view 0:  32*q + 8*b + 3 + i
+ *                view 1:  32*q + (8*b + 7 + i) % 32
+ *                (a nibble sits at bits 3..6 of a byte, either of the dword itself or of the dword
+ *                rotated right by 4: one byte-select AND yields its 8-byte table offset)
+ * Rows are padded to a multiple of 16 with zeros, as for KMQ_LAYOUT_TILED; same size. */
 kmq_status kmq_repack(const uint32_t* canonical, int64_t N, int64_t K, int bits, int layout,
                       uint32_t* tiled);
 kmq_status kmq_unrepack(const uint32_t* tiled, int64_t N, int64_t K, int bits, int layout,
@@ -138,9 +157,11 @@ kmq_status kmq_gemv(const uint32_t* W, const uint16_t* codebook, const uint16_t*
  * memory-bound regime; larger batches are better served by kmq_dequant plus a
  * dense GEMM, App. E "Model benchmarks").  X is M x K bf16 row-major (16-byte
  * aligned), Y is M x N bf16 row-major, overwritten.  Other arguments as kmq_gemv.
- * Both layouts are accepted at every M.  KMQ_LAYOUT_TILED is the fast one for M > 1
- * (matrix-core kernel: a weight is dequantised once for the whole batch); on the
- * canonical layout every batch column looks the weights up again, in one launch. */
+ * Every layout is accepted at every M.  KMQ_LAYOUT_TILED is the fast one for M >= 8
+ * (matrix-core kernel: a weight is dequantised once for the whole batch);
+ * KMQ_LAYOUT_ROWLANE serves M = 1..4 on the vector units, each weight dequantised once
+ * (M > 4: one launch per four columns); on the canonical layout every batch column
+ * looks the weights up again, in one launch. */
 kmq_status kmq_gemm_smallbatch(const uint32_t* W, const uint16_t* codebook, const uint16_t* X,
                                uint16_t* Y, int64_t N, int64_t K, int M, int bits, int layout,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -276,14 +297,6 @@ kmq_status kmq_quantize_blockscaled(const uint16_t* Wdense, int64_t N, int64_t K
 /* Name of the kernel variant the launch heuristic picks for this problem
  * (static string, never NULL; "invalid" on bad arguments).  For reports. */
 const char* kmq_kernel_name(int64_t N, int64_t K, int bits, int M, int layout);
-
-/* Measurement aid (paper App. E: effective bandwidth is judged against what the
- * memory system can deliver): reads `bytes` (>= 16, rounded down to 16) of DEVICE
- * memory at `data` (16-byte aligned) once, with the access shape of the GEMV
- * kernels, and discards them.  Gives the time a pure read of the same size
- * takes on this machine.  `sink` (device, 4 bytes, may be NULL) is never written
- * in practice; it only keeps the loads alive. */
-kmq_status kmq_stream_read(const void* data, size_t bytes, void* sink, void* hip_stream);
 
 const char* kmq_status_string(kmq_status s);
 

@@ -18,11 +18,15 @@ namespace kmq {
 // N*K / 9 for every column of the shape-agnostic kernel, which also starts later (about 5 us against 2.6
 // + bytes / 3.3e6 for the first column): the table kernel wins at every batch.  Table / shape-agnostic:
 // 9216x3072 1-bit, batch 4: 8.9 / 21.7; 14336x4096 2-bit, batch 16: 50.6 / 121; 8192x8192 block-scaled
-// 4-bit, batch 16: 111 / 237; 4096x4096 4-bit, batch 4: 10.0 / 12.8.  KMQ_PER_COLUMN_MAX in the
-// environment caps the batch (tuning, read once).
+// 4-bit, batch 16: 111 / 237; 4096x4096 4-bit, batch 4: 10.0 / 12.8.  (Builds with -DKMQ_TUNING
+// read a cap on the batch from KMQ_PER_COLUMN_MAX in the environment, for sweeps.)
 static bool per_column_faster(int M) {
+#ifdef KMQ_TUNING
     static const char* const v = std::getenv("KMQ_PER_COLUMN_MAX");
     static const int cap = v ? std::atoi(v) : KMQ_MAX_BATCH;
+#else
+    constexpr int cap = KMQ_MAX_BATCH;
+#endif
     return M >= 2 && M <= cap;
 }
 
@@ -289,13 +293,6 @@ kmq_status kmq_dequant_blockscaled(const uint32_t* W, const uint16_t* codebook, 
         (reinterpret_cast<uintptr_t>(scales) & 1) || (reinterpret_cast<uintptr_t>(Wdense) & 15)) return KMQ_ERR_ALIGN;
     return kmq::hip_status(kmq::launch_dequant_blockscaled(W, codebook, scales, Wdense, N, K, bits,
                                                            static_cast<hipStream_t>(hip_stream)));
-}
-
-kmq_status kmq_stream_read(const void* data, size_t bytes, void* sink, void* hip_stream) {
-    if (!data) return KMQ_ERR_NULL;
-    if (bytes < 16 || bytes > (size_t(1) << 40)) return KMQ_ERR_SHAPE;
-    if (reinterpret_cast<uintptr_t>(data) & 15) return KMQ_ERR_ALIGN;
-    return kmq::hip_status(kmq::launch_stream_read(data, bytes, sink, static_cast<hipStream_t>(hip_stream)));
 }
 
 const char* kmq_last_hip_error(void) { return kmq::g_last_hip_error; }

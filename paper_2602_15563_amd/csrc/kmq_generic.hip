@@ -242,35 +242,6 @@ __global__ __launch_bounds__(256) void dequant_rows8_kernel(const uint32_t* __re
     __builtin_nontemporal_store(u32x4_t{out[0], out[1], out[2], out[3]}, reinterpret_cast<u32x4_t*>(Wd + n * K + (c8 << 3)));
 }
 
-// Measurement aid: reads `nvec` 16-byte vectors once with the same access shape
-// as the GEMV kernels (four 1 KB wave-loads in flight per wave) and keeps
-// nothing; `sink` is written only if the xor of all data equals a magic value.
-__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4_t* __restrict__ p, int64_t nvec,
-                                                          uint32_t* __restrict__ sink) {
-    const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    u32x4_t v[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int64_t idx = (wave * 4 + i) * 64 + lane;
-        idx = idx < nvec ? idx : nvec - 1;
-        v[i] = __builtin_nontemporal_load(p + idx);
-    }
-    uint32_t a = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a ^= v[i][0] ^ v[i][1] ^ v[i][2] ^ v[i][3];
-    if (a == 0x9E3779B9u && sink) sink[0] = a;
-}
-
-hipError_t launch_stream_read(const void* p, size_t bytes, void* sink, hipStream_t s) {
-    const int64_t nvec = static_cast<int64_t>(bytes / 16);
-    const int64_t waves = (nvec + 255) / 256;
-    const dim3 grid(static_cast<unsigned>((waves + 3) / 4)), block(256);
-    hipLaunchKernelGGL(stream_read_kernel, grid, block, 0, s, static_cast<const u32x4_t*>(p), nvec,
-                       static_cast<uint32_t*>(sink));
-    return hipGetLastError();
-}
-
 template <int BITS>
 static hipError_t launch_generic_bits(const GemmArgs& a, int slices, hipStream_t s) {
     const dim3 grid(static_cast<unsigned>((a.N + 3) / 4), static_cast<unsigned>(slices)), block(256);

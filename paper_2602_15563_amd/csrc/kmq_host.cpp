@@ -108,7 +108,7 @@ static kmq_status repack_impl(const uint32_t* src, int64_t N, int64_t K, int bit
     uint32_t* tiled_out = forward ? dst : nullptr;
     const bool rowlane = layout == KMQ_LAYOUT_ROWLANE;
     const int gpg = rowlane ? 1 : kmq::tiled_groups_per_granule(bits);
-    const int64_t ce = rowlane ? kmq::rowlane_chunk_elems(bits) : 1;
+    const int64_t ce = rowlane ? kmq::kRowlaneChunk : 1;
     for (int64_t n = 0; n < N; ++n) {
         for (int64_t k = 0; k < K; ++k) {
             const int64_t g = (k % (32 * gpg)) / 8;

@@ -63,23 +63,22 @@ KMQ_HD inline int tiled_bit_position(int bits, int j, int e, int t) {
     }
 }
 
-// KMQ_LAYOUT_ROWLANE (see include/kmq.h).  A chunk is 16 bytes of one row (128 / bits elements);
-// a tile is 16 rows x 4 consecutive chunks, stored lane-major: lane kp*16 + r holds chunk kp of
-// row r.  Tiles of a 16-row block follow each other along K.
+// KMQ_LAYOUT_ROWLANE (see include/kmq.h).  A chunk is 64 consecutive elements of one row (2*bits
+// dwords); a tile is 16 rows x 4 consecutive chunks, stored lane-major: lane kp*16 + r holds chunk
+// kp of row r.  The tiles of a 16-row block follow each other along K.
 KMQ_HD inline bool rowlane_bits(int bits) { return bits == 1 || bits == 2; }
-KMQ_HD inline int64_t rowlane_chunk_elems(int bits) { return 128 / bits; }
-KMQ_HD inline bool rowlane_valid(int bits, int64_t K) { return rowlane_bits(bits) && K % (4 * rowlane_chunk_elems(bits)) == 0; }
+constexpr int64_t kRowlaneChunk = 64, kRowlaneTile = 4 * kRowlaneChunk;
+KMQ_HD inline bool rowlane_valid(int bits, int64_t K) { return rowlane_bits(bits) && K % kRowlaneTile == 0; }
 
 // Dword offset in the row-lane stream of the chunk that holds element k of row n.
 KMQ_HD inline int64_t rowlane_chunk_dword(int bits, int64_t K, int64_t n, int64_t k) {
-    const int64_t ce = rowlane_chunk_elems(bits), te = 4 * ce;
-    const int64_t tiles = K / te;
-    const int64_t t = k / te, kp = (k % te) / ce;
+    const int64_t tiles = K / kRowlaneTile;
+    const int64_t t = k / kRowlaneTile, kp = (k % kRowlaneTile) / kRowlaneChunk;
     const int64_t rb = n / kTileRows, r = n % kTileRows;
-    return ((rb * tiles + t) * 64 + kp * 16 + r) * 4;
+    return ((rb * tiles + t) * 64 + kp * 16 + r) * (2 * bits);
 }
 
-// Inside a chunk: bit position (0..127, dword-major) of bit t of the index of element c of the chunk.
+// Inside a chunk: bit position (dword-major) of bit t of the index of element c (0..63) of the chunk.
 // 2-bit: pairs of elements travel as nibbles; nibble slot s = 8*word + position is consumed against
 //        the activation pair that lane s % 16 holds in register s / 16 after an 8-byte load per lane,
 //        i.e. pair 2*(s % 16) + s / 16 of the chunk.

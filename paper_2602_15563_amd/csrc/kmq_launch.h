@@ -69,8 +69,6 @@ size_t quantize_blockscaled_workspace_bytes();
 hipError_t launch_quantize_blockscaled(const uint16_t* W, int64_t N, int64_t K, int bits, int iters, uint32_t* packed,
                                        uint16_t* codebook, uint16_t* scales, void* workspace, hipStream_t s);
 
-hipError_t launch_stream_read(const void* p, size_t bytes, void* sink, hipStream_t s);
-
 // Matrix-core kernel (tiled layout only).
 hipError_t launch_mfma(const GemmArgs& a, hipStream_t s);
 int mfma_waves_along_k(int64_t N, int64_t K, int bits);

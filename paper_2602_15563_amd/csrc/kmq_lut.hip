@@ -862,9 +862,12 @@ constexpr int kLutCount = sizeof(kLut) / sizeof(kLut[0]);
 // round-robin over 256 CUs.
 int lut_find(int64_t N, int64_t K, int bits, int layout, bool scaled) {
     if (layout != KMQ_LAYOUT_CANONICAL) return -1;
-    // tuning override for sweeps: KMQ_LUT_PICK=n takes the n-th shape listed for (bits, K)
+    int pick = -1;
+#ifdef KMQ_TUNING
+    // sweeps only (builds with -DKMQ_TUNING): KMQ_LUT_PICK=n takes the n-th shape listed for (bits, K)
     static const char* const pick_env = std::getenv("KMQ_LUT_PICK");
-    int pick = pick_env ? std::atoi(pick_env) : -1;
+    if (pick_env) pick = std::atoi(pick_env);
+#endif
     int best = -1;
     int64_t best_cost = 0;
     for (int i = 0; i < kLutCount; ++i) {

@@ -533,10 +533,16 @@ static bool mfma_has_shape(int nwk, int rbw, int spw) {
     return false;
 }
 
-// Tuning override for sweeps: KMQ_MFMA_NWK / KMQ_MFMA_RBW in the environment (read once).
+// Tuning override for sweeps, in builds with -DKMQ_TUNING only: KMQ_MFMA_NWK / KMQ_MFMA_RBW in the
+// environment (read once).  An ordinary build never looks at the environment.
 static int env_int(const char* name) {
+#ifdef KMQ_TUNING
     const char* v = std::getenv(name);
     return v ? std::atoi(v) : 0;
+#else
+    (void)name;
+    return 0;
+#endif
 }
 
 // Waves along K for `rbw` row blocks per wave: the largest of 8, 6, 4, 3, 2, 1 that divides

@@ -86,8 +86,6 @@ _lib.kmq_quantize_blockscaled_workspace_bytes.restype = _sz
 _lib.kmq_quantize_blockscaled_workspace_bytes.argtypes = []
 _lib.kmq_quantize_blockscaled.restype = ctypes.c_int32
 _lib.kmq_quantize_blockscaled.argtypes = [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _sz, _vp]
-_lib.kmq_stream_read.restype = ctypes.c_int32
-_lib.kmq_stream_read.argtypes = [_vp, _sz, _vp, _vp]
 _lib.kmq_last_hip_error.restype = ctypes.c_char_p
 _lib.kmq_last_hip_error.argtypes = []
 _lib.kmq_status_string.restype = ctypes.c_char_p
@@ -280,8 +278,3 @@ def dequant(W, codebook, Wdense, N: int, K: int, bits: int, layout: int = 0):
 def dequant_blockscaled(W, codebook, scales, Wdense, N: int, K: int, bits: int):
     """Wdense[N][K] (bf16 storage) = bf16(codebook[idx] * scale) of the block-scaled format, on torch's current stream."""
     _check(_lib.kmq_dequant_blockscaled(_ptr(W), _ptr(codebook), _ptr(scales), _ptr(Wdense), N, K, bits, _stream()))
-
-
-def stream_read(t, sink=None):
-    """Read a device tensor once and discard it (read-ceiling probe) on torch's current stream."""
-    _check(_lib.kmq_stream_read(_ptr(t), t.numel() * t.element_size(), _ptr(sink), _stream()))

@@ -26,6 +26,23 @@ def test_every_declared_symbol_is_exported():
         assert hasattr(lib, n), f"{n} declared in kmq.h but not exported"
 
 
+def test_the_probe_library_is_apart_from_the_product():
+    """The measurement probes live in their own library: every symbol its header declares is exported
+    there, and the product library exports none of them."""
+    from paper_2602_15563_amd import probe
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "kmq_probe.h")).read(), flags=re.S)
+    names = set(re.findall(r"\b(kmq_probe_[a-z0-9_]+)\s*\(", text))
+    assert names == {"kmq_probe_empty", "kmq_probe_read_variants", "kmq_probe_read_name", "kmq_probe_read"}
+    for n in sorted(names):
+        assert hasattr(probe._lib, n), f"{n} declared in kmq_probe.h but not exported"
+        assert not hasattr(kmq.raw(), n)
+    assert not hasattr(kmq.raw(), "kmq_stream_read")
+    v = probe.read_variants()
+    assert len(v) == len(set(v)) >= 8 and all(n.startswith(("oneshot_", "persist_")) for n in v)
+    assert probe._lib.kmq_probe_read(None, 4096, 0, None, None) == -1        # argument errors before any launch
+    assert probe._lib.kmq_probe_empty(0, 256, None, None) == -1 and probe._lib.kmq_probe_empty(4, 100, None, None) == -1
+
+
 @pytest.mark.parametrize("bits", BITS)
 @pytest.mark.parametrize("K", (1, 2, 7, 10, 11, 21, 22, 31, 32, 33, 63, 64, 65, 100, 515, 4096))
 def test_host_pack_matches_oracle_and_round_trips(bits, K):
@@ -103,6 +120,60 @@ def test_repack_is_a_reversible_permutation(bits, N):
     assert np.array_equal(kmq.repack(p, K, bits, kmq.LAYOUT_CANONICAL).reshape(N, wpr), p)
 
 
+@pytest.mark.parametrize("bits", (1, 2))
+@pytest.mark.parametrize("N", (1, 15, 16, 17, 40))
+def test_rowlane_repack_is_a_reversible_permutation(bits, N):
+    """KMQ_LAYOUT_ROWLANE: the position formula of kmq.h, element by element, and the inverse."""
+    K = 1024
+    g = np.random.default_rng(100 * N + bits)
+    idx = g.integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
+    p = kmq.pack(idx, bits)
+    t = kmq.repack(p, K, bits, kmq.LAYOUT_ROWLANE)
+    wpr = kmq.words_per_row(bits, K)
+    assert t.size == -(-N // 16) * 16 * wpr == kmq.tiled_words(N, K, bits, kmq.LAYOUT_ROWLANE)
+    assert np.array_equal(kmq.unrepack(t, N, K, bits, kmq.LAYOUT_ROWLANE), p)
+
+    def position(c, u):
+        if bits == 2:
+            pr = c // 2
+            s = pr // 2 + 16 * (pr % 2)
+            return 4 * s + 2 * (c % 2) + u
+        s, i = c // 4, c % 4
+        q, b, view = s // 8, (s % 8) // 2, s % 2
+        return 32 * q + ((8 * b + 7 + i) % 32 if view else 8 * b + 3 + i)
+
+    seen = set()
+    for _ in range(400):
+        n, k = int(g.integers(0, N)), int(g.integers(0, K))
+        tile, kp, c = k // 256, (k % 256) // 64, k % 64
+        rb, r = divmod(n, 16)
+        base = ((rb * (K // 256) + tile) * 64 + kp * 16 + r) * 2 * bits
+        v = 0
+        for u in range(bits):
+            pos = position(c, u)
+            assert 0 <= pos < 64 * bits
+            seen.add((c, u, pos))
+            v |= ((int(t[base + pos // 32]) >> (pos % 32)) & 1) << u
+        assert v == idx[n, k]
+    # the formula is a bijection of the chunk's bits
+    assert len({position(c, u) for c in range(64) for u in range(bits)}) == 64 * bits
+    if N % 16:                                            # rows of a short last block are zero
+        rb, r = divmod(N, 16)
+        off = ((rb * (K // 256)) * 64 + r) * 2 * bits
+        assert not t[off:off + 2 * bits].any()
+
+
+@pytest.mark.parametrize("bits,K", [(1, 128), (2, 320), (3, 1024), (4, 1024), (8, 1024)])
+def test_rowlane_repack_rejects_other_bit_widths_and_ragged_k(bits, K):
+    idx = np.zeros((4, K), dtype=np.uint8)
+    p = kmq.pack(idx, bits)
+    assert kmq.tiled_words(4, K, bits, kmq.LAYOUT_ROWLANE) == -1
+    with pytest.raises(kmq.KmqError) as e:
+        kmq.repack(p, K, bits, kmq.LAYOUT_ROWLANE)
+    assert e.value.status == 7
+    assert kmq.kernel_name(4, K, bits, 1, kmq.LAYOUT_ROWLANE) == "invalid"
+
+
 @pytest.mark.parametrize("bits,K", [(1, 256), (2, 128), (3, 64), (4, 96), (2, 33)])
 def test_repack_rejects_k_that_is_not_whole_superblocks(bits, K):
     idx = np.zeros((4, K), dtype=np.uint8)
@@ -133,7 +204,9 @@ def test_argument_errors_are_reported_before_any_launch():
     assert gemv(bits=0) == 2 and gemv(bits=5) == 2
     assert gemv(N=0) == 3 and gemv(K=0) == 3 and gemv(N=-1) == 3 and gemv(K=1 << 30) == 3
     assert gemm(0) == 3 and gemm(17) == 3
-    assert gemv(layout=2) == 7 and gemv(layout=-1) == 7
+    assert gemv(layout=3) == 7 and gemv(layout=-1) == 7
+    assert gemv(layout=2) == 7                        # row-lane layout: K = 64 is not a whole number of 256-element tiles
+    assert gemv(layout=2, K=1024, bits=3) == 7 and gemv(layout=2, K=1024, W=W + 4) == 4
     assert gemv(K=40, layout=1) == 7                  # 2-bit K=40 is not a whole number of 256-element super-blocks
     assert gemv(W=W + 4) == 4 and gemv(x=x + 2) == 4 and gemv(cb=cb + 2) == 4 and gemv(y=y + 1) == 4
     assert lib.kmq_dequant(None, cb, y, 4, 64, 2, 0, None) == 1
@@ -173,6 +246,11 @@ def test_heuristic_names():
     assert kmq.kernel_name(77, 515, 2, 1) == "generic"
     assert kmq.kernel_name(4096, 4096, 3, 16, kmq.LAYOUT_TILED) == "mfma_b3"
     assert kmq.kernel_name(4096, 4000, 3, 16, kmq.LAYOUT_TILED) == "invalid"
+    assert kmq.kernel_name(14336, 4096, 2, 1, kmq.LAYOUT_ROWLANE) == "rowlane_b2"
+    assert kmq.kernel_name(9216, 3072, 1, 4, kmq.LAYOUT_ROWLANE) == "rowlane_b1"
+    assert kmq.kernel_name(9216, 3072, 1, 16, kmq.LAYOUT_ROWLANE) == "rowlane_b1"     # four launches of four columns
+    assert kmq.kernel_name(64, 256 * 17, 2, 1, kmq.LAYOUT_ROWLANE) == "invalid"      # 17 tiles: no even split over <= 16 waves
+    assert kmq.workspace_bytes(14336, 4096, 2, 4, kmq.LAYOUT_ROWLANE) == 0
 
 
 def test_workspace_bytes_split_k():

@@ -1,0 +1,153 @@
+"""GPU parity of the lane-per-row kernels (KMQ_LAYOUT_ROWLANE), through the C ABI against the
+CPU oracle: ragged row counts, every tile split the launcher can pick, batches 1..16, one-hot
+probes (bit-exact for the 2-bit table kernel), determinism, minimum alignments."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_15563_amd import kmq, synth
+
+pytestmark = pytest.mark.gpu
+
+RL = kmq.LAYOUT_ROWLANE
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    from tests import gpu_util
+    assert torch.cuda.is_available()
+    return gpu_util
+
+
+def _case(seed, N, K, bits, M, symmetric=False):
+    g = np.random.default_rng(seed)
+    idx = g.integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
+    cb = synth.f32_to_bf16(g.normal(0, 0.02, size=(N, 1 << bits)).astype(np.float32))
+    if symmetric:
+        t = synth.f32_to_bf16(np.abs(g.normal(0, 0.02, size=N)).astype(np.float32))
+        cb = np.stack([t ^ np.uint16(0x8000), t], axis=1)
+    X = synth.f32_to_bf16(g.standard_normal(size=(M, K)).astype(np.float32))
+    return idx, cb, X
+
+
+# K / 256 tiles: 1, 2 (1 wave x 2), 3, 4, 6, 7 (1 x 7), 8, 12, 14 (2 x 7), 16, 24, 32, 56 (14 waves x 4)
+@pytest.mark.parametrize("bits", (1, 2))
+@pytest.mark.parametrize("K", (256, 512, 768, 1024, 1536, 1792, 2048, 3072, 3584, 4096, 6144, 8192, 14336))
+@pytest.mark.parametrize("N", (1, 15, 16, 17, 33, 130))
+def test_rowlane_gemv_vs_oracle(gpu, bits, K, N):
+    idx, cb, X = _case(1000 * bits + K + N, N, K, bits, 1, symmetric=(bits == 1 and N % 2 == 1))
+    p = kmq.pack(idx, bits)
+    assert kmq.kernel_name(N, K, bits, 1, RL) == f"rowlane_b{bits}"
+    Yg = gpu.run_gemm(gpu.dev(kmq.repack(p, K, bits, RL)), gpu.dev(cb), X, N, K, bits, layout=RL)
+    gpu.check_against_oracle(Yg, oracle.pack(idx, bits), cb, X, K, bits, label=f"rowlane b{bits} {N}x{K}")
+
+
+@pytest.mark.parametrize("bits", (1, 2))
+@pytest.mark.parametrize("M", (2, 3, 4, 5, 7, 8, 13, 16))
+@pytest.mark.parametrize("N,K", [(17, 512), (48, 3072), (100, 4096), (31, 8192)])
+def test_rowlane_batches_vs_oracle(gpu, bits, M, N, K):
+    """Up to four columns per launch share every lookup; wider batches take several launches."""
+    idx, cb, X = _case(77 * bits + M + N + K, N, K, bits, M)
+    p = kmq.pack(idx, bits)
+    Yg = gpu.run_gemm(gpu.dev(kmq.repack(p, K, bits, RL)), gpu.dev(cb), X, N, K, bits, layout=RL)
+    gpu.check_against_oracle(Yg, oracle.pack(idx, bits), cb, X, K, bits, label=f"rowlane b{bits} {N}x{K} M{M}")
+
+
+def test_rowlane_one_hot_probe_is_bit_exact(gpu):
+    """x = e_k: a sum with one non-zero term, so y[n] must equal the dequantised weight W[n][k] bit for
+    bit -- unpack, table build and lookup inside the production kernel, every position of a tile."""
+    bits, N, K = 2, 40, 1024
+    idx, cb, _ = _case(5, N, K, bits, 1)
+    p = kmq.pack(idx, bits)
+    Wd = oracle.dequant(oracle.pack(idx, bits), cb, K, bits)
+    Wdev, cbd = gpu.dev(kmq.repack(p, K, bits, RL)), gpu.dev(cb)
+    ks = list(range(0, 256)) + [256, 511, 777, 1023]
+    for k0 in range(0, len(ks), 4):
+        kk = ks[k0:k0 + 4]
+        X = np.zeros((len(kk), K), dtype=np.uint16)
+        for m, k in enumerate(kk):
+            X[m, k] = 0x3F80
+        Yg = gpu.run_gemm(Wdev, cbd, X, N, K, bits, layout=RL)
+        for m, k in enumerate(kk):
+            assert np.array_equal(Yg[m], Wd[:, k]), f"column {k}"
+
+
+def test_rowlane_one_hot_probe_one_bit(gpu):
+    """The 1-bit kernel computes c0*sum(x) + (c1 - c0)*S1: with x = e_k that is c0 + (c1 - c0) or c0,
+    exact for the symmetric codebooks of the contract's 1-bit configurations."""
+    bits, N, K = 1, 40, 512
+    idx, cb, _ = _case(6, N, K, bits, 1, symmetric=True)
+    p = kmq.pack(idx, bits)
+    Wd = oracle.dequant(oracle.pack(idx, bits), cb, K, bits)
+    Wdev, cbd = gpu.dev(kmq.repack(p, K, bits, RL)), gpu.dev(cb)
+    for k0 in range(0, K, 4):
+        X = np.zeros((4, K), dtype=np.uint16)
+        for m in range(4):
+            X[m, k0 + m] = 0x3F80
+        Yg = gpu.run_gemm(Wdev, cbd, X, N, K, bits, layout=RL)
+        for m in range(4):
+            assert np.array_equal(Yg[m], Wd[:, k0 + m]), f"column {k0 + m}"
+
+
+@pytest.mark.parametrize("bits,N,K,M", [(2, 14336, 4096, 1), (2, 4096, 14336, 1), (1, 9216, 3072, 1), (1, 9216, 3072, 4),
+                                        (1, 3072, 8192, 1), (1, 2048, 2048, 1), (2, 14336, 4096, 4)])
+def test_rowlane_contract_shapes(gpu, bits, N, K, M):
+    """Full-size shapes of the benchmark configurations that have a row-lane kernel, sampled row blocks
+    (first, last and random ones), held to the contract's 2e-3 * sum |w x|."""
+    idx = synth.make_indices(bits, 3, N, K, bits)
+    cb = synth.make_codebook(bits, 3, N, bits, symmetric=(bits == 1))
+    X = synth.make_x(bits, 3, M, K)
+    p = kmq.pack(idx, bits)
+    Yg = gpu.run_gemm(gpu.dev(kmq.repack(p, K, bits, RL)), gpu.dev(cb), X, N, K, bits, layout=RL)
+    w = gpu.check_against_oracle(Yg, p, cb, X, K, bits, row_ranges=gpu.sample_ranges(N, 9), label=f"rowlane b{bits} {N}x{K} M{M}",
+                                 strict=True)
+    assert w < 1e-3
+
+
+def test_rowlane_all_rows_headline_shape(gpu):
+    """Every one of the 14336 outputs of the headline product (the oracle takes a few seconds)."""
+    bits, N, K = 2, 14336, 4096
+    idx = synth.make_indices(2, 0, N, K, bits)
+    cb = synth.make_codebook(2, 0, N, bits)
+    X = synth.make_x(2, 0, 1, K)
+    p = kmq.pack(idx, bits)
+    Yg = gpu.run_gemm(gpu.dev(kmq.repack(p, K, bits, RL)), gpu.dev(cb), X, N, K, bits, layout=RL)
+    gpu.check_against_oracle(Yg, p, cb, X, K, bits, label="rowlane headline", strict=True)
+
+
+@pytest.mark.parametrize("bits", (1, 2))
+def test_rowlane_is_deterministic_and_writes_nothing_else(gpu, bits):
+    """Same bits run to run; y at its minimum alignment (2 bytes) inside a guard pattern; rows past N untouched."""
+    N, K, M = 37, 2048, 3
+    idx, cb, X = _case(9 + bits, N, K, bits, M)
+    Wdev, cbd, Xd = gpu.dev(kmq.repack(kmq.pack(idx, bits), K, bits, RL)), gpu.dev(cb), gpu.dev(X)
+    outs = []
+    for trial in range(3):
+        buf = torch.full((M * N + 9,), 0x7A7A, dtype=torch.int16, device="cuda")
+        Y = buf[1:1 + M * N].view(M, N)                                       # 2-byte aligned, not 4
+        kmq.gemm_smallbatch(Wdev, cbd, Xd, Y, N, K, M, bits, RL)
+        torch.cuda.synchronize()
+        h = gpu.host_u16(buf)
+        assert h[0] == 0x7A7A and (h[1 + M * N:] == 0x7A7A).all()
+        outs.append(h[1:1 + M * N].reshape(M, N).copy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    gpu.check_against_oracle(outs[0], oracle.pack(idx, bits), cb, X, K, bits, label=f"rowlane guard b{bits}")
+
+
+def test_rowlane_degenerate_inputs(gpu):
+    """x = 0 gives 0; a constant codebook row gives c * sum(x); unsorted and duplicate centroids are fine."""
+    bits, N, K = 2, 20, 768
+    g = np.random.default_rng(3)
+    idx = g.integers(0, 4, size=(N, K), dtype=np.uint8)
+    cb = synth.f32_to_bf16(g.normal(0, 0.02, size=(N, 4)).astype(np.float32))
+    cb[3, :] = cb[3, 0]                      # constant row
+    cb[5, :] = cb[5, ::-1].copy()            # unsorted
+    cb[7, 1] = cb[7, 2]                      # duplicates
+    p = kmq.pack(idx, bits)
+    Wdev, cbd = gpu.dev(kmq.repack(p, K, bits, RL)), gpu.dev(cb)
+    X0 = np.zeros((1, K), dtype=np.uint16)
+    assert not (gpu.run_gemm(Wdev, cbd, X0, N, K, bits, layout=RL) & 0x7FFF).any()
+    X = synth.f32_to_bf16(g.standard_normal(size=(1, K)).astype(np.float32))
+    Yg = gpu.run_gemm(Wdev, cbd, X, N, K, bits, layout=RL)
+    gpu.check_against_oracle(Yg, p, cb, X, K, bits, label="rowlane degenerate")
