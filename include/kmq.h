@@ -213,13 +213,15 @@ const char* kmq_kernel_name_swiglu(int64_t N, int64_t K, int bits, int layout);
 /* Decoder-layer fusions at batch 1 (paper App. E "Model benchmarks": token generation runs a
  * layer's projections back to back; Sec. 3.3 "Software formats" attributes part of the 1-bit
  * model's lost speed to the elementwise work on the activations, RMSNorm and the activation
- * function).  One launch computes
- *     xn[k] = bf16( x[k] * norm_weight[k] )                  (rmsnorm with gains; else xn = x)
+ * function).  One launch computes RMSNorm in front of the product and a residual sum behind it:
  *     r     = 1 / sqrt( (1/K) sum_k x[k]^2 + eps )           (rmsnorm; else 1)
- *     y[n]  = bf16( residual[n] + r * sum_k w[n][k] xn[k] )  (residual optional)
- * i.e. RMSNorm in front of the product -- its scalar factor commutes with the sum, so the
- * activations enter the product as bf16(x * g) and r multiplies the fp32 result -- and a
- * residual sum behind it.
+ *     xn[k] = bf16( x[k] * r * norm_weight[k] )              (the normalised bf16 activations; else xn = x)
+ *     y[n]  = bf16( residual[n] + sum_k w[n][k] xn[k] )      (residual optional)
+ * The kernels let the scalar r commute with the sum: they round x[k] * norm_weight[k] to bf16
+ * and multiply the fp32 sum by r.  Each activation then differs from xn[k] by at most 2^-7 of
+ * itself (two roundings to 8 significant bits of the same exact value), so the result is within
+ * 2^-7 * sum_k |w xn| of the definition above in the worst case and, the roundings being
+ * independent, far inside 2e-3 * sum_k |w xn| for rows of hundreds of elements.
  *   rmsnorm      0: no normalisation (norm_weight and eps ignored); 1: RMSNorm
  *   norm_weight  K bf16 gains, 16-byte aligned, or NULL for unit gains -- the cheaper form: gains
  *                are per input channel and can be multiplied into the dense weights before they are

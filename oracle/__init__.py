@@ -235,8 +235,8 @@ def dequant_blockscaled(packed, codebook, scales, K: int, bits: int, block: int 
 
 
 def rmsnorm(x, g, eps: float):
-    """(xn, r): xn = bf16(x * g) as uint16 patterns, r = 1 / sqrt(mean(x^2) + eps) in fp64; the
-    normalised activations are xn * r (the fused call applies r after the product)."""
+    """(xn, r): r = 1 / sqrt(mean(x^2) + eps) in fp64 and the normalised activations
+    xn = bf16(x * r * g) as uint16 patterns (one rounding of the fp64 value)."""
     x = _arr(x, np.uint16).reshape(-1)
     g = np.full(x.shape, 0x3F80, np.uint16) if g is None else _arr(g, np.uint16, x.shape)   # None: unit gains
     xn = np.empty_like(x)
@@ -252,17 +252,17 @@ _rmsnorm = rmsnorm     # gemv_fused has a parameter of that name
 def gemv_fused(packed, codebook, x, K: int, bits: int, norm_weight=None, eps: float = 0.0, residual=None, rows=None,
                rmsnorm=None):
     """The fused decoder call's definition, composed from the pieces above:
-    Y[n] = residual[n] + r * sum_k w[n][k] xn[k]; returns (Y, A) with A = |residual| + r * sum |w xn|.
+    Y[n] = residual[n] + sum_k w[n][k] xn[k] with xn = rmsnorm(x) (bf16); returns (Y, A) with
+    A = |residual| + sum |w xn|.
     rmsnorm defaults to "gains were given"; rmsnorm=True without gains normalises with unit gains."""
     x = _arr(x, np.uint16).reshape(1, -1)
-    r = 1.0
     if rmsnorm is None:
         rmsnorm = norm_weight is not None
     if rmsnorm:
-        xn, r = _rmsnorm(x[0], norm_weight, eps)
+        xn, _ = _rmsnorm(x[0], norm_weight, eps)
         x = xn.reshape(1, -1)
     Y, A, _ = gemm(packed, codebook, x, K, bits, rows=rows)
-    Y, A = Y[0] * r, A[0] * r
+    Y, A = Y[0], A[0]
     if residual is not None:
         res = (np.ascontiguousarray(residual, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
         Y, A = Y + res, A + np.abs(res)

@@ -242,20 +242,22 @@ int oracle_swiglu(const double* gate, const double* up, int64_t n, double* y) {
 }
 
 // RMSNorm in front of a product (the normalisation of the Llama-3 decoder layers the paper
-// benchmarks, App. E "Model benchmarks"): rmsnorm(x)[k] = x[k] * g[k] / sqrt(mean(x^2) + eps).
-// The scalar factor r = 1 / sqrt(mean(x^2) + eps) commutes with the product that follows, and
-// the activations the product sees are bf16 (the method's activation type), so the fused call
-// is DEFINED as: xn[k] = bf16( x[k] * g[k] ) (a bf16 x bf16 product is exact in fp64: one
-// rounding), and r returned separately, in fp64, to multiply the product's result.
+// benchmarks, App. E "Model benchmarks"; the paper fixes none of its arithmetic).  The plain
+// definition, written out: r = 1 / sqrt(mean(x^2) + eps) and
+//     xn[k] = bf16( x[k] * r * g[k] )
+// evaluated in fp64 and rounded ONCE to the method's activation type; the product that follows
+// sees xn.  r is returned as well, for the pins.  (A kernel may let the scalar r commute with the
+// sum and apply it to the fp32 result instead; that is an approximation of this definition, and
+// the parity tests bound it.)
 int oracle_rmsnorm(const uint16_t* x, const uint16_t* g, int64_t K, double eps, uint16_t* xn, double* r) {
     if (!x || !g || !xn || !r || K < 1 || !(eps >= 0.0)) return 1;
     double ss = 0.0;
     for (int64_t k = 0; k < K; ++k) {
         const double v = bf16_to_double(x[k]);
         ss += v * v;
-        xn[k] = oracle_round_bf16(v * bf16_to_double(g[k]));
     }
     *r = 1.0 / std::sqrt(ss / static_cast<double>(K) + eps);
+    for (int64_t k = 0; k < K; ++k) xn[k] = oracle_round_bf16(bf16_to_double(x[k]) * *r * bf16_to_double(g[k]));
     return 0;
 }
 

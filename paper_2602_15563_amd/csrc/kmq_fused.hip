@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void gemv_fused_generic_kernel(
     const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
     const uint32_t* __restrict__ W2, const uint16_t* __restrict__ codebook2,
     const uint16_t* __restrict__ x, bool norm, const uint16_t* __restrict__ norm_w, float eps,
-    const uint16_t* __restrict__ residual, uint16_t* __restrict__ y, int64_t N, int64_t K) {
+    const uint16_t* residual, uint16_t* y, int64_t N, int64_t K) {   // (may be one buffer: no __restrict__)
     constexpr int C = 1 << BITS;
     __shared__ float lut[4][2][C];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;

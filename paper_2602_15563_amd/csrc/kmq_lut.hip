@@ -306,10 +306,11 @@ __device__ __forceinline__ void load_words(const uint32_t* p, uint32_t (&w)[G]) 
 template <int BITS, int G, int LPR, int NWK, int NWR, int RS, int WPE, bool SC, bool PAIR, int FUSE>
 __global__ __launch_bounds__(NWK * NWR * 64) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
-                     const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int64_t N,
+                     const uint16_t* __restrict__ x, uint16_t* y, int64_t N,
                      const uint16_t* __restrict__ scales,
                      const uint32_t* __restrict__ W2, const uint16_t* __restrict__ codebook2,
-                     const uint16_t* __restrict__ norm_w, float eps, const uint16_t* __restrict__ residual, int mcols) {
+                     const uint16_t* __restrict__ norm_w, float eps, const uint16_t* residual, int mcols) {
+    // (y and residual carry no __restrict__: the fused call documents that they may be the same buffer)
     static_assert(!(SC && PAIR), "the fused pair is offered for the per-row-codebook format");
     static_assert(FUSE == 0 || !SC, "decoder fusions are offered for the per-row-codebook format");
     static_assert(!(PAIR && (FUSE & 2)), "the fused pair has no residual input");

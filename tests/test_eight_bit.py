@@ -120,7 +120,10 @@ def test_gpu_fusions(gpu):
     torch.cuda.synchronize()
     Y, A = oracle.gemv_fused(p, cb, x, K, BITS, norm_weight=g, eps=1e-5, residual=res)
     yg = synth.bf16_to_f64(gpu.host_u16(y))
-    assert np.all(np.abs(yg - Y) <= gpu.arithmetic_bound(A, Y, K + 16))
+    # (+ 2^-7 of the product's magnitude: the oracle rounds x*r*g, the kernel rounds x*g and scales the sum)
+    Ap = A - np.abs(synth.bf16_to_f64(res))
+    assert np.all(np.abs(yg - Y) <= gpu.arithmetic_bound(A, Y, K + 16) + 2.0 ** -7 * Ap)
+    assert np.all(np.abs(yg - Y) <= gpu.TOL * A + 2.0 ** -8 * np.abs(Y))
     kmq.gemv_swiglu(gpu.dev(p), gpu.dev(cb), gpu.dev(p), gpu.dev(cb), gpu.dev(x), y, N, K, BITS)
     torch.cuda.synchronize()
     G, Ag, _ = oracle.gemm(p, cb, x.reshape(1, -1), K, BITS)

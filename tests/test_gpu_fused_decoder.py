@@ -42,6 +42,14 @@ def _check(gpu, yg, idx, cb, x, bits, g, res, label, unit=False):
     err = np.abs(yg - Y)
     # fp32 sums in any order, the scalar in fp32 (a few roundings), one bf16 rounding of the result
     bound = gpu.arithmetic_bound(A, Y, K + 16)
+    if g is not None or unit:
+        # The oracle rounds x*r*g to bf16; the kernels round x*g and apply the scalar r to the fp32 sum (it
+        # commutes with the sum).  Both roundings are within half an ulp (2^-8, relative) of the same exact
+        # value, so an activation differs by at most 2^-7 of itself and the sum by at most 2^-7 * sum |w xn|.
+        # That is the guarantee; independent rounding errors add in quadrature, so for long rows the
+        # difference stays far inside the contract's 2e-3 * A, which is asserted below as well.
+        Ap = A - (np.abs(synth.bf16_to_f64(res)) if res is not None else 0.0)
+        bound = bound + 2.0 ** -7 * Ap
     bad = err > bound
     if K >= 512:
         bad |= err > gpu.TOL * A + 2.0 ** -8 * np.abs(Y)
@@ -106,7 +114,7 @@ def test_unit_weights_reduce_to_a_scaled_product(gpu):
     yg = _run(gpu, idx, cb, x, 1, one, None)
     Y0, A0, _ = oracle.gemm(oracle.pack(idx, 1), cb, x.reshape(1, -1), K, 1)
     xd = synth.bf16_to_f64(x)
-    r = 1.0 / np.sqrt(np.mean(xd * xd) + EPS)
+    r = 1.0 / np.sqrt(np.mean(xd * xd) + EPS)       # (the kernels apply the scalar to the sum: with unit gains that is exactly this)
     assert np.all(np.abs(yg - Y0[0] * r) <= gpu.arithmetic_bound(A0[0] * r, Y0[0] * r, K + 16))
 
 
@@ -126,12 +134,15 @@ def _swiglu_norm(gpu, bits, N, K, seed, unit=False):
     G, Ag = oracle.gemv_fused(oracle.pack(ig, bits), cg, x, K, bits, norm_weight=g, eps=EPS, rmsnorm=True)
     U, Au = oracle.gemv_fused(oracle.pack(iu, bits), cu, x, K, bits, norm_weight=g, eps=EPS, rmsnorm=True)
     want = oracle.swiglu(G, U)
-    dg, du = (K + 24) * 2.0 ** -23 * Ag, (K + 24) * 2.0 ** -23 * Au
     silu = oracle.swiglu(G, np.ones_like(G))
-    inner = 1.1 * np.abs(U) * dg + np.abs(silu) * du + 1.1 * dg * du + 8 * 2.0 ** -23 * np.abs(want)
-    bound = inner + 2.0 ** -8 * (np.abs(want) + inner)
     err = np.abs(yg - want)
-    assert np.all(err <= bound), f"b{bits} {N}x{K}: max err/bound {np.max(err / np.maximum(bound, 1e-300)):.2f}"
+    # guarantee: fp32 sums plus the rounding-point difference of the normalised activations (2^-7 of
+    # sum |w xn|: the oracle rounds x*r*g, the kernels round x*g and scale the sum), through silu' in [-0.1, 1.1]
+    for dg, du, what in (((K + 24) * 2.0 ** -23 * Ag + 2.0 ** -7 * Ag, (K + 24) * 2.0 ** -23 * Au + 2.0 ** -7 * Au, "guaranteed"),
+                         (2e-3 * Ag, 2e-3 * Au, "contract (independent roundings add in quadrature)")):
+        inner = 1.1 * np.abs(U) * dg + np.abs(silu) * du + 1.1 * dg * du + 8 * 2.0 ** -23 * np.abs(want)
+        bound = inner + 2.0 ** -8 * (np.abs(want) + inner)
+        assert np.all(err <= bound), f"b{bits} {N}x{K}, {what}: max err/bound {np.max(err / np.maximum(bound, 1e-300)):.2f}"
 
 
 @pytest.mark.parametrize("bits,K,N", [(1, 2048, 40), (1, 3072, 64), (1, 3072, 8192), (1, 4096, 333), (1, 8192, 17),

@@ -70,23 +70,33 @@ def test_unit_scales_and_replicated_codebook_reduce_to_the_per_row_product(bits)
 
 
 @pytest.mark.parametrize("bits", (1, 2, 4))
-def test_equals_the_papers_byte_table_routine(bits):
-    """App. E "Kernel implementations": a 256-entry table maps each packed byte to its
-    8/bits elements, the result is scaled block-wise, then multiplied by x.  Written here
-    with numpy in fp64 from that description (LSB-first elements in a byte)."""
+def test_byte_view_of_the_stream_with_partial_sums_per_byte(bits):
+    """The special case that meets the paper's uint8 element stream (App. E "Kernel implementations"): for
+    1, 2 and 4 bits the little-endian bytes of the packed words hold 8/bits whole elements each, first
+    element in the low bits.  Checked with a formulation of its own: for every byte POSITION of a row and
+    every byte VALUE, the partial product of the 8/bits centroids that value selects with the activations
+    at that position is tabulated once (an activation-side table); an output is then the sum, over the byte
+    positions, of the tabulated entry its row's byte selects, times the scale of the block the byte lies in."""
     N, K, M = 12, 256, 2
     idx, cb, sc, X = _case(23 + bits, N, K, bits, M)
     p = oracle.pack(idx, bits)
-    epb = 8 // bits
-    c = synth.bf16_to_f64(cb)
-    lut8 = np.array([[c[(v >> (e * bits)) & ((1 << bits) - 1)] for e in range(epb)] for v in range(256)])
-    Wq = p.view(np.uint8).reshape(N, -1)[:, :K // epb]          # little-endian bytes of the words
-    Wu = lut8[Wq].reshape(N, K)
-    W = (Wu.reshape(N, K // 64, 64) * synth.bf16_to_f64(sc)[:, :, None]).reshape(N, K)
-    want = synth.bf16_to_f64(X) @ W.T
+    per_byte = 8 // bits
+    field = (1 << bits) - 1
+    centroid = synth.bf16_to_f64(cb)
+    act = synth.bf16_to_f64(X)
+    scale = synth.bf16_to_f64(sc)
+    stream = p.view(np.uint8).reshape(N, -1)[:, :K // per_byte]          # byte j of row n
+    # partial[m, j, v] = sum over the elements e of byte position j of centroid[field e of v] * act[m, j*per_byte + e]
+    selected = np.array([[centroid[(v >> (e * bits)) & field] for e in range(per_byte)] for v in range(256)])    # [v][e]
+    partial = np.einsum("mje,ve->mjv", act.reshape(M, K // per_byte, per_byte), selected)
+    block_of_byte = (np.arange(K // per_byte) * per_byte) // 64
+    want = np.zeros((M, N))
+    for m in range(M):
+        for n in range(N):
+            picked = partial[m, np.arange(K // per_byte), stream[n]]                                              # one entry per byte
+            want[m, n] = np.sum(picked * scale[n, block_of_byte])
     Y, A, _ = oracle.gemm_blockscaled(p, cb, sc, X, K, bits)
     assert np.all(np.abs(Y - want) <= 1e-13 * A)
-    assert np.allclose(A, np.abs(synth.bf16_to_f64(X))[:, None, :].__mul__(np.abs(W)[None]).sum(-1), rtol=1e-12)
 
 
 @pytest.mark.parametrize("bits", (1, 2, 3, 4))
