@@ -166,6 +166,22 @@ kmq_status kmq_gemm_smallbatch(const uint32_t* W, const uint16_t* codebook, cons
                                uint16_t* Y, int64_t N, int64_t K, int M, int bits, int layout,
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* kmq_gemm_smallbatch for callers that cannot allocate device memory and so cannot bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * (without the workspace pair), same kernels, same results bit for bit.  Where the problem needs a
+ * workspace (kmq_workspace_bytes > 0: K split over workgroups), the partial sums go to an array of
+ * KMQ_NOALLOC_SCRATCH_BYTES that the library holds on every GPU it runs on, until the process ends;
+ * a problem that needs more returns KMQ_ERR_WORKSPACE (64 KiB covers every shape the split currently
+ * serves).  The call itself allocates and frees nothing.  The first call on a device looks the
+ * array's address up (make that call outside stream capture).  All calls on one GPU share that
+ * GPU's array: it keeps the last call's contents (nothing in it has to start at zero: every partial
+ * sum is written before it is read), and calls that overlap on one GPU -- different streams, or graphs
+ * replayed concurrently -- race on it; calls on one stream are ordered and safe. */
+#define KMQ_NOALLOC_SCRATCH_BYTES 65536
+kmq_status kmq_gemm_smallbatch_noalloc(const uint32_t* W, const uint16_t* codebook, const uint16_t* X,
+                                       uint16_t* Y, int64_t N, int64_t K, int M, int bits, int layout,
+                                       void* hip_stream);
+
 /* Wdense[n][k] = codebook[n][idx[n][k]] as bf16 bit patterns, N x K row-major,
  * bit-exact (device pointers).  The separate-dequantise route the paper
  * suggests for large batches (App. E "Model benchmarks"), and the bit-exactness probe. */

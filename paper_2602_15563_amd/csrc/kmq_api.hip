@@ -81,7 +81,10 @@ static kmq_status hip_status(hipError_t e) {
 
 static bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
-static kmq_status check_and_run(const GemmArgs& a, void* stream) {
+// library_scratch: the caller brings no workspace; a plan that needs one takes this GPU's share of the
+// library's own scratch array (kmq_gemm_smallbatch_noalloc), up to its fixed size.
+static kmq_status check_and_run(const GemmArgs& a_in, void* stream, bool library_scratch = false) {
+    GemmArgs a = a_in;
     if (!a.W || !a.codebook || !a.X || !a.Y) return KMQ_ERR_NULL;
     if (!bits_valid(a.bits)) return KMQ_ERR_BITS;
     if (!dims_valid(a.N, a.K) || a.M < 1 || a.M > KMQ_MAX_BATCH) return KMQ_ERR_SHAPE;
@@ -97,6 +100,12 @@ static kmq_status check_and_run(const GemmArgs& a, void* stream) {
     }
     const Plan plan = make_plan(a.N, a.K, a.bits, a.M, a.layout, scaled);
     if (plan.variant == kVariantInvalid) return a.layout == KMQ_LAYOUT_ROWLANE ? KMQ_ERR_LAYOUT : KMQ_ERR_SHAPE;
+    if (plan.workspace_bytes > 0 && library_scratch) {
+        if (plan.workspace_bytes > KMQ_NOALLOC_SCRATCH_BYTES) return KMQ_ERR_WORKSPACE;
+        const hipError_t es = noalloc_scratch(&a.workspace);
+        if (es != hipSuccess) return hip_status(es);
+        a.workspace_bytes = KMQ_NOALLOC_SCRATCH_BYTES;
+    }
     if (plan.workspace_bytes > 0 && (!a.workspace || a.workspace_bytes < plan.workspace_bytes)) return KMQ_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
@@ -130,6 +139,13 @@ kmq_status kmq_gemm_smallbatch(const uint32_t* W, const uint16_t* codebook, cons
                                void* workspace, size_t workspace_bytes, void* hip_stream) {
     const kmq::GemmArgs a{W, codebook, X, Y, N, K, M, bits, layout, workspace, workspace_bytes};
     return kmq::check_and_run(a, hip_stream);
+}
+
+kmq_status kmq_gemm_smallbatch_noalloc(const uint32_t* W, const uint16_t* codebook, const uint16_t* X,
+                                       uint16_t* Y, int64_t N, int64_t K, int M, int bits, int layout,
+                                       void* hip_stream) {
+    const kmq::GemmArgs a{W, codebook, X, Y, N, K, M, bits, layout, nullptr, 0};
+    return kmq::check_and_run(a, hip_stream, /*library_scratch=*/true);
 }
 
 kmq_status kmq_gemv(const uint32_t* W, const uint16_t* codebook, const uint16_t* x, uint16_t* y,

@@ -2,10 +2,38 @@
 // They are the fallback behind the shape-specialised kernels and the
 // bit-exact dequantiser.  Operation: paper App. E, "Kernel implementations"
 // (lookup, then multiply-accumulate), per-row codebooks, fp32 accumulation.
+#include <mutex>
+
 #include "kmq_device.h"
 #include "kmq_launch.h"
 
+// Scratch of kmq_gemm_smallbatch_noalloc: the split-K partial sums of callers that cannot allocate.
+// Every GPU the library runs on holds its own copy at its own address until the process ends.  In host
+// code this name is a stand-in, not a device address: the address comes from hipGetSymbolAddress below.
+static __device__ __align__(256) unsigned char scratch[KMQ_NOALLOC_SCRATCH_BYTES];
+
 namespace kmq {
+
+// Device address of this GPU's scratch array (looked up once per device, with that device current).
+hipError_t noalloc_scratch(void** ptr) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* per_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    return hipSuccess;
+}
 
 // b-bit field `e` (0..31) of a 32-element group held in BITS consecutive words.
 template <int BITS>

@@ -49,6 +49,7 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled = 
 
 hipError_t launch_generic(const GemmArgs& a, hipStream_t s);   // split-K when a.workspace is given and the shape asks for it
 int generic_splitk_slices(int64_t N, int64_t K, int layout);
+hipError_t noalloc_scratch(void** ptr);   // this GPU's KMQ_NOALLOC_SCRATCH_BYTES of library-owned scratch (kmq_gemm_smallbatch_noalloc)
 hipError_t launch_dequant(const uint32_t* W, const uint16_t* codebook, uint16_t* Wd, int64_t N,
                           int64_t K, int bits, int layout, hipStream_t s);
 

@@ -56,6 +56,8 @@ _lib.kmq_gemv.restype = ctypes.c_int32
 _lib.kmq_gemv.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _vp, _sz, _vp]
 _lib.kmq_gemm_smallbatch.restype = ctypes.c_int32
 _lib.kmq_gemm_smallbatch.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp, _sz, _vp]
+_lib.kmq_gemm_smallbatch_noalloc.restype = ctypes.c_int32
+_lib.kmq_gemm_smallbatch_noalloc.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _int, _int, _int, _vp]
 _lib.kmq_dequant.restype = ctypes.c_int32
 _lib.kmq_dequant.argtypes = [_vp, _vp, _vp, _i64, _i64, _int, _int, _vp]
 _lib.kmq_kernel_name.restype = ctypes.c_char_p
@@ -196,6 +198,14 @@ def gemm_smallbatch(W, codebook, X, Y, N: int, K: int, M: int, bits: int, layout
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(_lib.kmq_gemm_smallbatch(_ptr(W), _ptr(codebook), _ptr(X), _ptr(Y), N, K, M, bits, layout,
                                     _ptr(workspace), ws_bytes, _stream()))
+
+
+NOALLOC_SCRATCH_BYTES = 65536
+
+
+def gemm_smallbatch_noalloc(W, codebook, X, Y, N: int, K: int, M: int, bits: int, layout: int = 0):
+    """gemm_smallbatch without a workspace argument: split-K partial sums go to the library's own per-GPU array."""
+    _check(_lib.kmq_gemm_smallbatch_noalloc(_ptr(W), _ptr(codebook), _ptr(X), _ptr(Y), N, K, M, bits, layout, _stream()))
 
 
 def kernel_name_blockscaled(N: int, K: int, bits: int, M: int, layout: int = 0) -> str:
