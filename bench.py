@@ -94,11 +94,22 @@ class Instances:
         if M is not None:
             self.M = M
         bits, N, K, M = self.bits, self.N, self.K, self.M
-        # Default layouts (the offline, reversible repack is outside the timed region): 2-bit products at
-        # batch <= 4 run on the row-lane layout (lane-per-row kernels on the vector units), every other
-        # batch > 1 on the tiled (matrix-core) layout, the rest on the canonical one.
+        # Default layouts (the offline, reversible repack is outside the timed region), by what was measured
+        # fastest within the contract's rule that the matrix cores serve batches of 8 and more:
+        #   batch 1: the row-lane layout for 2-bit matrices with many rows (14336 x 4096: 5.4 us against 6.0 us
+        #            canonical; 4096 x 14336, 256 row blocks: 6.7 against 6.5, stays canonical), else canonical;
+        #   batch 2..7: the row-lane layout where it exists (1 and 2 bits: every weight decoded once, on the
+        #            vector units), else tiled;
+        #   batch >= 8: tiled (matrix-core kernel).
         if layout is None:
-            layout = 2 if (bits == 2 and M <= 4 and not self.scaled) else (1 if M > 1 else 0)
+            from paper_2602_15563_amd import kmq as _k
+            has_rowlane = not self.scaled and _k.kernel_name(N, K, bits, M, 2) != "invalid"
+            if M == 1:
+                layout = 2 if (has_rowlane and bits == 2 and N >= 8192) else 0
+            elif M < 8:
+                layout = 2 if has_rowlane else 1
+            else:
+                layout = 1
         self.layout = layout
         self.bytes = (synth.algorithmic_bytes_blockscaled if self.scaled else synth.algorithmic_bytes)(N, K, bits, M)
         self.R = max(2, -(-2 * LLC_BYTES // self.bytes)) if rotate else 1
@@ -249,7 +260,7 @@ SWEEP_SHAPES = ["cfg4_qkv_b1_9216x3072_m1", "cfg4_o_b1_3072x3072_m1", "cfg4_gate
                 "cfg4_up_b1_8192x3072_m1", "cfg4_down_b1_3072x8192_m1"]         # gate and up are two matrices
 
 
-def run_sweep(M: int, replays: int, fuse: str = ""):
+def run_sweep(M: int, replays: int, fuse: str = "", layout=None):
     """The 1-bit decoder-layer sweep of the fifth contract configuration: 28 layers x
     (fused QKV, O, gate, up, down), every matrix with its own weights (396 MB of indices, so
     each pass streams from HBM), captured as one HIP graph of 140 calls on one stream."""
@@ -258,7 +269,7 @@ def run_sweep(M: int, replays: int, fuse: str = ""):
 
     import oracle
     from paper_2602_15563_amd import synth
-    insts = [Instances(n, R=SWEEP_LAYERS, M=M) for n in SWEEP_SHAPES]
+    insts = [Instances(n, R=SWEEP_LAYERS, M=M, layout=layout) for n in SWEEP_SHAPES]
     worst = max(it.check() for it in insts)
     gate, up = insts[2], insts[3]
     fuse_gate_up = fuse == "gate_up"
@@ -335,9 +346,9 @@ def run_sweep(M: int, replays: int, fuse: str = ""):
         it.call(layer)
     torch.cuda.synchronize()
     for it in insts[:1] + insts[4:]:
-        if it.layout:                     # tiled: bring the words back to canonical order on the host
+        if it.layout:                     # repacked: bring the words back to canonical order on the host
             from paper_2602_15563_amd import kmq
-            packed = kmq.unrepack(it.W[layer].cpu().numpy().view(np.uint32).reshape(-1), it.N, it.K, it.bits, 1)
+            packed = kmq.unrepack(it.W[layer].cpu().numpy().view(np.uint32).reshape(-1), it.N, it.K, it.bits, it.layout)
         else:
             packed = it.W[layer].cpu().numpy().view(np.uint32)
         cb = it.C[layer].cpu().numpy().view(np.uint16)
@@ -791,8 +802,9 @@ def main():
 
     if args.sweep:
         rows = []
-        for M, fused in ((1, ""), (1, "gate_up"), (1, "decoder"), (1, "decoder_unit_gains"), (4, ""), (16, "")):
-            rows.append(run_sweep(M, 200, fuse=fused))
+        for M, fused, lay in ((1, "", None), (1, "gate_up", None), (1, "decoder", None), (1, "decoder_unit_gains", None),
+                              (4, "", 2), (4, "", 1), (16, "", None)):
+            rows.append(run_sweep(M, 200, fuse=fused, layout=lay))
             print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
             torch.cuda.empty_cache()
         os.makedirs(args.out, exist_ok=True)
