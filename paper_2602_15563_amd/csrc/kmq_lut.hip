@@ -803,32 +803,40 @@ static const LutEntry kLut[] = {
     // Several shapes may serve one (bits, K): lut_find takes the one whose grid comes out
     // most even over the CUs for the given N; the first listed wins ties.
     // 1-bit
+    KMQ_LUT(1, 3, 16, 1, 4, 1, 4),   // K = 1536, 16 rows per workgroup
     KMQ_LUT(1, 4, 16, 1, 4, 1, 4),   // K = 2048, 16 rows per workgroup
     KMQ_LUT(1, 4, 16, 1, 2, 1, 4),   //            8
     KMQ_LUT(1, 3, 32, 1, 4, 2, 4),   // K = 3072, 16
     KMQ_LUT(1, 3, 32, 1, 3, 3, 4),   //           18
     KMQ_LUT(1, 3, 32, 1, 3, 2, 4),   //           12
     KMQ_LUT(1, 4, 32, 1, 4, 2, 4),   // K = 4096
+    KMQ_LUT(1, 3, 64, 1, 6, 2, 4),   // K = 6144, 12
     KMQ_LUT(1, 4, 64, 1, 4, 2, 4),   // K = 8192,  8
     KMQ_LUT(1, 4, 64, 1, 4, 3, 4),   //           12
     // 2-bit
+    KMQ_LUT(2, 3, 32, 1, 4, 2, 6),   // K = 1536
     KMQ_LUT(2, 4, 32, 1, 4, 2, 6),   // K = 2048
     KMQ_LUT(2, 3, 64, 1, 4, 2, 6),   // K = 3072
     KMQ_LUT(2, 4, 64, 1, 4, 2, 7),   // K = 4096
+    KMQ_LUT(2, 3, 64, 2, 3, 2, 6),   // K = 6144: two slices of 12-byte loads, 6 rows per workgroup
     KMQ_LUT(2, 4, 64, 2, 2, 4, 4),   // K = 8192: 16 rows per workgroup (x, staged once per workgroup, is 16 KB here)
     KMQ_LUT(2, 4, 64, 2, 2, 2, 7),   //            8
     KMQ_LUT(2, 4, 32, 7, 1, 4, 4),   // K = 14336: 16-byte loads, 8 rows per workgroup (6.6 us on 4096 rows; 7.1 with 3 or 8 rows per wave)
     KMQ_LUT(2, 2, 64, 7, 1, 4, 7),   //            8-byte loads, 4 rows per workgroup (7.05 us; taken for few rows)
     // 3-bit (lane slices are whole groups of three words = 32 elements)
+    KMQ_LUT(3, 3, 16, 3, 1, 2, 6),   // K = 1536: three slices of 12-byte loads, 8 rows per workgroup
     KMQ_LUT(3, 6, 32, 1, 4, 2, 6),   // K = 2048
     KMQ_LUT(3, 3, 32, 3, 1, 4, 6),   // K = 3072: three slices of 12-byte loads (9216 rows: 5.2 us; 6.1 with one slice of 36-byte loads)
     KMQ_LUT(3, 6, 64, 1, 4, 2, 7),   // K = 4096 (14336 rows: 7.7 us; 8.0 with 4 rows per wave)
+    KMQ_LUT(3, 3, 64, 3, 2, 4, 6),   // K = 6144: three slices of 12-byte loads, 8 rows per workgroup
     KMQ_LUT(3, 6, 64, 2, 2, 4, 4),   // K = 8192: 16 rows per workgroup
     KMQ_LUT(3, 6, 64, 2, 2, 2, 6),   //            8
     KMQ_LUT(3, 3, 64, 7, 1, 4, 6),   // K = 14336: 12-byte loads, 4 rows per workgroup (4096 rows: 8.7 us; 9.0-9.2 with 24-byte loads)
     // 4-bit
+    KMQ_LUT(4, 3, 64, 1, 4, 2, 6),   // K = 1536: 12-byte loads
     KMQ_LUT(4, 4, 64, 1, 4, 2, 6),   // K = 2048
     KMQ_LUT(4, 4, 64, 2, 2, 2, 6),   // K = 4096
+    KMQ_LUT(4, 4, 64, 3, 2, 2, 6),   // K = 6144
     KMQ_LUT(4, 4, 64, 4, 1, 4, 4),   // K = 8192: 4 rows per workgroup (4096 rows: 6.6 us; 7.0 with 2 or 6)
     KMQ_LUT(4, 4, 64, 4, 1, 2, 6),   //           2
     KMQ_LUT(4, 4, 64, 7, 1, 4, 4),   // K = 14336: 4 rows per workgroup (4096 rows: 10.5 us; 12.2 with 2, 10.9 with 6)

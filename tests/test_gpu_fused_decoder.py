@@ -61,8 +61,8 @@ MODES = [("norm", True, False), ("res", False, True), ("both", True, True), ("pl
 LUT_SHAPES = [(1, 2048, 64), (1, 2048, 333), (1, 3072, 100), (1, 3072, 3072), (1, 4096, 50), (1, 8192, 96), (1, 8192, 3072),
               (2, 2048, 40), (2, 3072, 77), (2, 4096, 1000), (2, 8192, 64), (2, 14336, 130),
               (3, 2048, 90), (3, 3072, 50), (3, 4096, 333), (3, 8192, 64), (3, 14336, 70),
-              (3, 2048, 90), (3, 3072, 50), (3, 4096, 333), (3, 8192, 64), (3, 14336, 70),
-              (4, 2048, 40), (4, 4096, 333), (4, 8192, 64), (4, 14336, 70)]
+              (4, 2048, 40), (4, 4096, 333), (4, 8192, 64), (4, 14336, 70),
+              (1, 1536, 70), (1, 6144, 50), (2, 1536, 33), (2, 6144, 40), (3, 1536, 50), (3, 6144, 30), (4, 1536, 20), (4, 6144, 45)]
 
 
 @pytest.mark.parametrize("mode,use_g,use_r", MODES)

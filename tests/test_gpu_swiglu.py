@@ -42,8 +42,9 @@ def _check(gpu, bits, N, K, seed):
         assert np.abs(G).max() > 0.5       # the test does exercise the non-linear part
 
 
-LUT_SHAPES = [(1, 2048), (1, 3072), (1, 4096), (1, 8192), (2, 2048), (2, 3072), (2, 4096), (2, 8192), (2, 14336),
-              (3, 2048), (3, 3072), (3, 4096), (3, 8192), (3, 14336), (4, 2048), (4, 4096), (4, 8192), (4, 14336)]
+LUT_SHAPES = [(1, 1536), (1, 2048), (1, 3072), (1, 4096), (1, 6144), (1, 8192), (2, 1536), (2, 2048), (2, 3072), (2, 4096), (2, 6144),
+              (2, 8192), (2, 14336), (3, 1536), (3, 2048), (3, 3072), (3, 4096), (3, 6144), (3, 8192), (3, 14336),
+              (4, 1536), (4, 2048), (4, 4096), (4, 6144), (4, 8192), (4, 14336)]
 
 
 @pytest.mark.parametrize("bits,K", LUT_SHAPES)
