@@ -109,7 +109,10 @@ kmq_status kmq_unpack(const uint32_t* packed, int64_t N, int64_t K, int bits, ui
  *
  * KMQ_LAYOUT_ROWLANE (bits = 1 or 2, K % 256 == 0, else KMQ_ERR_LAYOUT) is the order of the
  * lane-per-row kernels that serve batches 1..4 without the matrix cores (a weight is decoded
- * once per launch of up to four batch columns; wider batches take several launches).  A CHUNK is
+ * once per launch of up to four batch columns; wider batches take several launches).  Every such K
+ * has a kernel: K / 256 = c * w with c in {1,2,3,4,6,7,8} tiles per wave and w <= 16 waves is served
+ * with every load in flight at once, any other tile count (17, 19, 43, ... or beyond 128) by a kernel
+ * that walks K in rounds (kmq_kernel_name says "rowlane_loop_...").  A CHUNK is
  * 64 consecutive elements of a row (2*bits dwords); a TILE is 16 rows x 4 consecutive chunks,
  * 64 chunks stored one after the other, chunk kp of row 16*rb + r at dword offset
  *     ((rb * (K/256) + t) * 64 + kp*16 + r) * 2*bits          (t = tile number along K),

@@ -77,6 +77,7 @@ int mfma_row_blocks(int64_t N, int64_t K, int bits);
 
 // Row-lane layout kernels (batch 1..4).
 bool rowlane_has_kernel(int64_t K, int bits, int M);
+bool rowlane_loops(int64_t K);              // K served by the kernel that walks K in rounds
 hipError_t launch_rowlane(const GemmArgs& a, hipStream_t s);
 
 // Hand-scheduled table kernels (1/2/4-bit): -1 if (bits, K, layout) has none.

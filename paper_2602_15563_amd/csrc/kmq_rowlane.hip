@@ -158,9 +158,13 @@ __device__ unsigned long long kmq_rowlane_ts[1024 * 16 * 8];
 
 // BITS 1 or 2; CPW tiles per wave; MB batch columns; WPE waves per SIMD the register budget is
 // sized for.  K = 256 * CPW * (waves per workgroup); the grid is one workgroup per 16-row block.
+// LOOP: any K that is a multiple of 256: the workgroup walks K in rounds of CPW * (waves) tiles;
+// a tile past the end of the last round is read from a valid address and meets activations
+// forced to zero.  (The loads of a round are issued when the round starts, nothing is in flight
+// across rounds: the shapes with a kernel of their own do not take this path.)
 // DBG (instrumented builds only) takes parts of the kernel out, to time the rest: 1 no loads of
 // x, 2 no loads of the codebook, 16 no lookups, 32 no loads of the index words, 64 no store.
-template <int BITS, int CPW, int MB, int WPE, int DBG = 0>
+template <int BITS, int CPW, int MB, int WPE, bool LOOP = false, int DBG = 0>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
                          const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int64_t N, int64_t K) {
@@ -217,12 +221,39 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);      // (left alone, the compiler sinks this load below the index loads)
     u32x2_t xv[MB][CPW];
+    using wvec_t = typename WordVec<G>::type;
+    wvec_t wv[CPW];
+    float acc[MB][2];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) acc[m][0] = acc[m][1] = 0.f;
+    [[maybe_unused]] float sxl[MB];                                            // LOOP, 1-bit: this lane's share of the sum of x
+#pragma unroll
+    for (int m = 0; m < MB; ++m) sxl[m] = 0.f;
+    uint32_t lut_base = static_cast<uint32_t>(reinterpret_cast<size_t>((lds_cu32_t*)(&sm.lut[0])));
+    if constexpr (BITS == 1) lut_base += static_cast<uint32_t>(wave) * 256;
+    uint32_t t0 = 0;                                                           // first tile of the round
+    do {
+    // tile of slot j in this round: t0 + j * nwk + wave (LOOP: clamped, and x masked, past the end)
+    uint32_t tile_of[CPW];
+    [[maybe_unused]] uint32_t live[CPW];
+#pragma unroll
+    for (int j = 0; j < CPW; ++j) {
+        const uint32_t t = t0 + static_cast<uint32_t>(j) * nwk + static_cast<uint32_t>(wave);
+        if constexpr (LOOP) {
+            const bool in = t < tiles;
+            tile_of[j] = __builtin_amdgcn_readfirstlane(in ? t : tiles - 1);
+            live[j] = __builtin_amdgcn_readfirstlane(in ? 0xFFFFFFFFu : 0u);
+        } else {
+            tile_of[j] = t;
+        }
+    }
 #pragma unroll
     for (int j = 0; j < CPW; ++j) {
 #pragma unroll
         for (int m = 0; m < MB; ++m) {
             // (the tile's base stays on the scalar side: pinned, or the sum is re-associated into vector adds)
-            uint64_t xb = reinterpret_cast<uint64_t>(x_base) + static_cast<uint64_t>(m) * K * 2 + static_cast<uint64_t>(j) * nwk * 512;
+            uint64_t xb = LOOP ? reinterpret_cast<uint64_t>(X) + static_cast<uint64_t>(m) * K * 2 + static_cast<uint64_t>(tile_of[j]) * 512
+                               : reinterpret_cast<uint64_t>(x_base) + static_cast<uint64_t>(m) * K * 2 + static_cast<uint64_t>(j) * nwk * 512;
             asm volatile("" : "+s"(xb));
             if constexpr (DBG & 1) xv[m][j] = u32x2_t{0x3F803F80u + off_x, 0x3F803F80u};
             else xv[m][j] = *reinterpret_cast<const __attribute__((address_space(1))) u32x2_t*>(reinterpret_cast<global_cchar_t*>(xb) + off_x);
@@ -230,11 +261,10 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
     }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
-    using wvec_t = typename WordVec<G>::type;
-    wvec_t wv[CPW];
 #pragma unroll
     for (int j = 0; j < CPW; ++j) {
-        uint64_t wb = reinterpret_cast<uint64_t>(w_base) + static_cast<uint64_t>(j) * nwk * TILE_BYTES;
+        uint64_t wb = LOOP ? reinterpret_cast<uint64_t>(W) + (static_cast<uint64_t>(rb) * tiles + tile_of[j]) * TILE_BYTES
+                           : reinterpret_cast<uint64_t>(w_base) + static_cast<uint64_t>(j) * nwk * TILE_BYTES;
         asm volatile("" : "+s"(wb));
         if constexpr (DBG & 32) {
 #pragma unroll
@@ -243,47 +273,59 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
             wv[j] = __builtin_nontemporal_load(reinterpret_cast<const __attribute__((address_space(1))) wvec_t*>(reinterpret_cast<global_cchar_t*>(wb) + off_w));
         }
     }
+    if constexpr (LOOP) {
+#pragma unroll
+        for (int j = 0; j < CPW; ++j)
+#pragma unroll
+            for (int m = 0; m < MB; ++m) { xv[m][j][0] &= live[j]; xv[m][j][1] &= live[j]; }
+    }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
     KMQ_TS(1);
 
-    // ---- tables ----------------------------------------------------------------------------------------
-    uint32_t lut_base = static_cast<uint32_t>(reinterpret_cast<size_t>((lds_cu32_t*)(&sm.lut[0])));
-    if constexpr (BITS == 2) {
-        // the workgroup's pair table: wave w writes entries w, w + nwk, ...
-        // (a loop that always runs once: a load whose only use sits behind a branch gets sunk into it)
-        int e = wave;
-        do {
-            const uint32_t a = (e & 3) * 2, b = (e >> 2) * 2;
-            const uint32_t sel = a | ((a + 1) << 8) | (b << 16) | ((b + 1) << 24);
-            sm.lut[e * 64 + lane] = __builtin_amdgcn_perm(cb[1], cb[0], sel);
-            e += nwk;
-        } while (e < 16);
-        KMQ_TS(2);
-        __syncthreads();
-    } else {
-        // this wave's copy of the mask table; a wave reads back only what it wrote itself (LDS serves a
-        // wave's instructions in order), so no barrier
-        lut_base += static_cast<uint32_t>(wave) * 256;
-        if (lane < 16) {
-            u32x2_t m;
-            m[0] = ((lane & 1u) ? 0x3F80u : 0u) | ((lane & 2u) ? 0x3F800000u : 0u);
-            m[1] = ((lane & 4u) ? 0x3F80u : 0u) | ((lane & 8u) ? 0x3F800000u : 0u);
-            *reinterpret_cast<u32x2_t*>(&sm.lut[wave * 64 + lane * 2]) = m;
+    // ---- tables (first round) ---------------------------------------------------------------------------
+    if (!LOOP || t0 == 0) {
+        if constexpr (BITS == 2) {
+            // the workgroup's pair table: wave w writes entries w, w + nwk, ...
+            // (a loop that always runs once: a load whose only use sits behind a branch gets sunk into it)
+            int e = wave;
+            do {
+                const uint32_t a = (e & 3) * 2, b = (e >> 2) * 2;
+                const uint32_t sel = a | ((a + 1) << 8) | (b << 16) | ((b + 1) << 24);
+                sm.lut[e * 64 + lane] = __builtin_amdgcn_perm(cb[1], cb[0], sel);
+                e += nwk;
+            } while (e < 16);
+            KMQ_TS(2);
+            __syncthreads();
+        } else {
+            // this wave's copy of the mask table; a wave reads back only what it wrote itself (LDS serves a
+            // wave's instructions in order), so no barrier
+            if (lane < 16) {
+                u32x2_t m;
+                m[0] = ((lane & 1u) ? 0x3F80u : 0u) | ((lane & 2u) ? 0x3F800000u : 0u);
+                m[1] = ((lane & 4u) ? 0x3F80u : 0u) | ((lane & 8u) ? 0x3F800000u : 0u);
+                *reinterpret_cast<u32x2_t*>(&sm.lut[wave * 64 + lane * 2]) = m;
+            }
+            KMQ_TS(2);
         }
-        KMQ_TS(2);
+    }
+    if constexpr (BITS == 1) {
         // the closed form's sum of x, taken while the index words are still on their way: every pair of
         // the wave's tiles sits in exactly one lane
 #pragma unroll
         for (int m = 0; m < MB; ++m) {
-            float s = 0.f;
+            float s = LOOP ? sxl[m] : 0.f;
 #pragma unroll
             for (int j = 0; j < CPW; ++j) {
                 s = dot2_bf16(0x3F803F80u, xv[m][j][0], s);
                 s = dot2_bf16(0x3F803F80u, xv[m][j][1], s);
             }
-            s = group_sum<64>(s);
-            if (lane == 63) sm.sx[m][wave] = s;
+            if constexpr (LOOP) {
+                sxl[m] = s;
+            } else {
+                s = group_sum<64>(s);
+                if (lane == 63) sm.sx[m][wave] = s;
+            }
         }
     }
     KMQ_TS(3);
@@ -295,9 +337,6 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
     // what the compiler itself has in flight on the LGKM counter must have landed before the
     // hand-counted pipeline starts
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    float acc[MB][2];
-#pragma unroll
-    for (int m = 0; m < MB; ++m) acc[m][0] = acc[m][1] = 0.f;
     constexpr int NW = CPW * G;
     if constexpr (DBG & 16) {
         uint32_t t = 0;
@@ -359,6 +398,15 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
             for (int m = 1; m < MB; ++m) dot8_mask<-1, 8 * q + 4 * h>(vv[g & 1], xv[m][j][0], xv[m][j][1], acc[m][0], acc[m][1]);
         });
     }
+    t0 += CPW * nwk;
+    } while (LOOP && t0 < tiles);
+    if constexpr (LOOP && BITS == 1) {
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+            const float s = group_sum<64>(sxl[m]);
+            if (lane == 63) sm.sx[m][wave] = s;
+        }
+    }
     __builtin_amdgcn_sched_barrier(0);
     KMQ_TS(5);
 
@@ -417,10 +465,12 @@ extern "C" int kmq_debug_rowlane_timestamps(unsigned long long* host, size_t cou
 
 // ---- launch ----------------------------------------------------------------------------------------
 
-struct RowlaneShape { int cpw, nwk; };
+struct RowlaneShape { int cpw, nwk; bool loop; };
 
 // K / 256 tiles = cpw * nwk with nwk <= 16 waves; many thin waves first (occupancy hides the LDS latency
-// of the lookups better than a deeper per-wave queue, which the 4-bit LGKM counter caps anyway)
+// of the lookups better than a deeper per-wave queue, which the 4-bit LGKM counter caps anyway).
+// A tile count with no such factorisation (17, 19, 34, 43, ... or beyond 128) takes the kernel that
+// walks K in rounds of 2 * nwk tiles.
 static bool rowlane_shape(int64_t K, RowlaneShape& s) {
     const int64_t tiles = K / 256;
     static const int cpws[] = {2, 1, 3, 4, 6, 7, 8};
@@ -428,18 +478,28 @@ static bool rowlane_shape(int64_t K, RowlaneShape& s) {
     static const char* const force = std::getenv("KMQ_RL_CPW");     // sweeps only: builds with -DKMQ_TUNING
     if (force) {
         const int c = std::atoi(force);
-        if (c >= 1 && tiles % c == 0 && tiles / c <= 16) { s = {c, static_cast<int>(tiles / c)}; return true; }
+        if (c >= 1 && tiles % c == 0 && tiles / c <= 16) { s = {c, static_cast<int>(tiles / c), false}; return true; }
+        if (c == 0 && tiles >= 1) { const int64_t r = (tiles + 31) / 32; s = {2, static_cast<int>((tiles + 2 * r - 1) / (2 * r)), true}; return true; }    // KMQ_RL_CPW=0: the round loop
     }
 #endif
     for (int c : cpws) {
-        if (tiles % c == 0 && tiles / c <= 16 && tiles / c >= 1) { s = {c, static_cast<int>(tiles / c)}; return true; }
+        if (tiles % c == 0 && tiles / c <= 16 && tiles / c >= 1) { s = {c, static_cast<int>(tiles / c), false}; return true; }
     }
-    return false;
+    if (tiles < 1) return false;
+    // rounds of at most 32 tiles (16 waves x 2), the waves spread evenly over the rounds
+    const int64_t rounds = (tiles + 31) / 32;
+    s = {2, static_cast<int>((tiles + 2 * rounds - 1) / (2 * rounds)), true};
+    return true;
 }
 
 bool rowlane_has_kernel(int64_t K, int bits, int M) {
     RowlaneShape s;
     return rowlane_valid(bits, K) && M >= 1 && M <= KMQ_MAX_BATCH && rowlane_shape(K, s);
+}
+
+bool rowlane_loops(int64_t K) {
+    RowlaneShape s;
+    return rowlane_shape(K, s) && s.loop;
 }
 
 template <int BITS>
@@ -454,7 +514,7 @@ static hipError_t launch_rowlane_bits(const GemmArgs& a, const RowlaneShape& s, 
     static const char* const dbg_env = std::getenv("KMQ_RL_DBG");
     const int dbg = dbg_env ? std::atoi(dbg_env) : 0;
     if (dbg && s.cpw == 2 && a.M == 1) {
-#define KMQ_RL_DBG_CASE(D) case D: hipLaunchKernelGGL((gemv_rowlane_kernel<BITS, 2, 1, 8, D>), grid, block, 0, st, a.W, a.codebook, a.X, a.Y, a.N, a.K); return hipGetLastError();
+#define KMQ_RL_DBG_CASE(D) case D: hipLaunchKernelGGL((gemv_rowlane_kernel<BITS, 2, 1, 8, false, D>), grid, block, 0, st, a.W, a.codebook, a.X, a.Y, a.N, a.K); return hipGetLastError();
         switch (dbg) {
             KMQ_RL_DBG_CASE(1) KMQ_RL_DBG_CASE(2) KMQ_RL_DBG_CASE(3) KMQ_RL_DBG_CASE(16) KMQ_RL_DBG_CASE(32) KMQ_RL_DBG_CASE(19)
             KMQ_RL_DBG_CASE(35) KMQ_RL_DBG_CASE(64) KMQ_RL_DBG_CASE(80)
@@ -463,6 +523,12 @@ static hipError_t launch_rowlane_bits(const GemmArgs& a, const RowlaneShape& s, 
 #undef KMQ_RL_DBG_CASE
     }
 #endif
+    if (s.loop) {
+#define KMQ_RL_LOOP(MB) hipLaunchKernelGGL((gemv_rowlane_kernel<BITS, 2, MB, 8, true>), grid, block, 0, st, a.W, a.codebook, a.X, a.Y, a.N, a.K)
+        switch (a.M) { case 1: KMQ_RL_LOOP(1); break; case 2: KMQ_RL_LOOP(2); break; case 3: KMQ_RL_LOOP(3); break; default: KMQ_RL_LOOP(4); break; }
+#undef KMQ_RL_LOOP
+        return hipGetLastError();
+    }
     switch (s.cpw) {
         case 1: KMQ_RL_CPW(1, 8); break;
         case 2: KMQ_RL_CPW(2, 8); break;

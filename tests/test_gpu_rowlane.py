@@ -43,6 +43,34 @@ def test_rowlane_gemv_vs_oracle(gpu, bits, K, N):
     gpu.check_against_oracle(Yg, oracle.pack(idx, bits), cb, X, K, bits, label=f"rowlane b{bits} {N}x{K}")
 
 
+# tile counts with no split into cpw x (at most 16 waves): 17 and 19 (one round, one masked tile), 34 (two rounds of 18),
+# 43 (K = 11008: two rounds of 22, one masked), 74 (K = 18944: three rounds of 26), 129 (five rounds of 26, one masked)
+@pytest.mark.parametrize("bits", (1, 2))
+@pytest.mark.parametrize("tiles", (17, 19, 34, 43, 74, 129))
+@pytest.mark.parametrize("N,M", [(1, 1), (17, 1), (40, 1), (33, 2), (16, 3), (50, 4), (21, 6)])
+def test_rowlane_round_loop_vs_oracle(gpu, bits, tiles, N, M):
+    """Any K that is a multiple of 256: the kernel that walks K in rounds, tiles past the end masked."""
+    K = 256 * tiles
+    idx, cb, X = _case(31 * bits + tiles + N + M, N, K, bits, M, symmetric=(bits == 1 and N % 2 == 1))
+    p = kmq.pack(idx, bits)
+    assert kmq.kernel_name(N, K, bits, M, RL) == f"rowlane_loop_b{bits}"
+    Yg = gpu.run_gemm(gpu.dev(kmq.repack(p, K, bits, RL)), gpu.dev(cb), X, N, K, bits, layout=RL)
+    gpu.check_against_oracle(Yg, oracle.pack(idx, bits), cb, X, K, bits, label=f"rowlane loop b{bits} {N}x{K} M{M}")
+
+
+def test_rowlane_round_loop_one_hot_is_bit_exact(gpu):
+    """x = e_k at positions in the first, a middle and the last tile of a K whose last round is partly masked."""
+    bits, N, K = 2, 20, 256 * 43
+    idx, cb, _ = _case(4343, N, K, bits, 1)
+    Wd = oracle.dequant(oracle.pack(idx, bits), cb, K, bits)
+    Wt, cbd = gpu.dev(kmq.repack(kmq.pack(idx, bits), K, bits, RL)), gpu.dev(cb)
+    for k in (0, 255, 256 * 21 + 7, 256 * 22, 256 * 42 + 100, K - 1):
+        X = np.zeros((1, K), dtype=np.uint16)
+        X[0, k] = 0x3F80
+        Yg = gpu.run_gemm(Wt, cbd, X, N, K, bits, layout=RL)
+        assert np.array_equal(Yg[0], Wd[:, k]), f"column {k}"
+
+
 @pytest.mark.parametrize("bits", (1, 2))
 @pytest.mark.parametrize("M", (2, 3, 4, 5, 7, 8, 13, 16))
 @pytest.mark.parametrize("N,K", [(17, 512), (48, 3072), (100, 4096), (31, 8192)])
