@@ -691,7 +691,7 @@ def main():
     ap.add_argument("--no-cache-resident", action="store_true",
                     help="skip the secondary same-matrix-every-call timing (keeps a kernel trace to the cold calls)")
     ap.add_argument("--layout", type=int, default=None, choices=(0, 1, 2),
-                    help="0 canonical, 1 tiled (matrix-core order), 2 row-lane (default: canonical for batch 1, tiled for batch > 1)")
+                    help="0 canonical, 1 tiled (matrix-core order), 2 row-lane (default: per workload, see Instances)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the timed region, launch a plain 64 MiB device copy 10 times: a kernel of known "
                          "traffic against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled")
@@ -701,7 +701,9 @@ def main():
                     help="also run the paper's micro-benchmark grid (h x bits x batch 1 / 16) -> <out>/bench_micro_sweep.json")
     ap.add_argument("--large-batch", action="store_true",
                     help="also time batches 16 / 64 / 256 at h = 8192 by dequantise + dense GEMM -> <out>/bench_large_batch.json")
-    ap.add_argument("--table", action="store_true", help="also time every contract shape -> <out>/bench_table.json")
+    ap.add_argument("--table", action="store_true", help="also time every contract shape and the paper's h = 8192 rows -> <out>/bench_table.json")
+    ap.add_argument("--no-contract-shapes", action="store_true",
+                    help="skip the short timing of the contract's other shapes and of the batch-1 decoder sweep (config.contract_shapes)")
     ap.add_argument("--out", default=os.path.join(ROOT, "bench_out"), help="folder for the json files of --table, --sweep, --micro-sweep and --large-batch")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -781,6 +783,28 @@ def main():
         del one
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(inst)
+
+    if not args.no_contract_shapes and args.workload == HEADLINE and not args.table:
+        # the contract's other configurations, briefly (the headline above is the metric; --table and --sweep
+        # time these at length): same protocol, 2000 calls each, instance 0 checked against the oracle
+        rows = []
+        for name in WORKLOADS:
+            if not name.startswith("cfg") or name == HEADLINE:
+                continue
+            it = Instances(name)
+            w = it.check()
+            s, n = time_workload(it, 2000, 100)
+            rows.append({"workload": name, "kernel": it.kernel, "layout": LAYOUT_NAMES[it.layout],
+                         "us_per_call": round(s / n * 1e6, 3),
+                         "pct_peak": round(100 * it.bytes / (s / n) / 1e9 / HBM_PEAK_GBS, 2),
+                         "max_err_over_A": float(f"{w:.3e}")})
+            del it
+            torch.cuda.empty_cache()
+        out["config"]["contract_shapes"] = rows
+        if not args.sweep:
+            sw = run_sweep(1, 50)
+            out["config"]["decoder_sweep_batch1"] = {k: sw[k] for k in ("us_per_sweep", "us_per_call", "passes_per_s", "calls", "pct_peak", "layout", "max_err_over_A")}
+            torch.cuda.empty_cache()
 
     if args.table:
         rows = []
