@@ -221,8 +221,11 @@ const char* kmq_kernel_name_blockscaled(int64_t N, int64_t K, int bits, int M, i
  * backbone's projections one after another, with the activation function between them as extra
  * cost): y[n] = silu(Wgate[n] . x) * (Wup[n] . x), silu(t) = t / (1 + exp(-t)), both products
  * and the combination in fp32, one rounding to bf16.  Both matrices are N x K in the per-row-codebook
- * format, KMQ_LAYOUT_CANONICAL (else KMQ_ERR_LAYOUT), same bits; alignment as kmq_gemv; 2N <= 2^24.
- * One launch instead of two products and an elementwise pass. */
+ * format, same bits, same layout: KMQ_LAYOUT_CANONICAL, or KMQ_LAYOUT_ROWLANE for 1 and 2 bits where
+ * K / 256 splits into at most four tiles per wave times at most 16 waves (kmq_kernel_name_swiglu says
+ * "rowlane_pair_..."; every workgroup then decodes the same 16 rows of both matrices against one copy
+ * of the activations); any other layout or shape of it: KMQ_ERR_LAYOUT.  Alignment as kmq_gemv;
+ * 2N <= 2^24.  One launch instead of two products and an elementwise pass. */
 kmq_status kmq_gemv_swiglu(const uint32_t* Wgate, const uint16_t* codebook_gate,
                            const uint32_t* Wup, const uint16_t* codebook_up,
                            const uint16_t* x, uint16_t* y, int64_t N, int64_t K, int bits, int layout,

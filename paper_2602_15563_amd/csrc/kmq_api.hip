@@ -162,20 +162,24 @@ kmq_status kmq_gemv_swiglu(const uint32_t* Wgate, const uint16_t* codebook_gate,
     if (!Wgate || !codebook_gate || !Wup || !codebook_up || !x || !y) return KMQ_ERR_NULL;
     if (!kmq::bits_valid(bits)) return KMQ_ERR_BITS;
     if (!kmq::dims_valid(N, K) || 2 * N > kmq::kMaxDim) return KMQ_ERR_SHAPE;
-    if (layout != KMQ_LAYOUT_CANONICAL) return KMQ_ERR_LAYOUT;
+    const bool rowlane = layout == KMQ_LAYOUT_ROWLANE && kmq::rowlane_pair_has_kernel(K, bits);
+    if (layout != KMQ_LAYOUT_CANONICAL && !rowlane) return KMQ_ERR_LAYOUT;
     if (!kmq::aligned(Wgate, 16) || !kmq::aligned(Wup, 16) || !kmq::aligned(x, 16) ||
         !kmq::aligned(codebook_gate, 4) || !kmq::aligned(codebook_up, 4) || !kmq::aligned(y, 2)) return KMQ_ERR_ALIGN;
     kmq::GemmArgs a{Wgate, codebook_gate, x, y, N, K, 1, bits, layout, nullptr, 0};
     a.W2 = Wup;
     a.codebook2 = codebook_up;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (rowlane) return kmq::hip_status(kmq::launch_rowlane_pair(a, s));
     const int l = kmq::lut_find(2 * N, K, bits, layout, false);
     const hipError_t e = l >= 0 ? kmq::launch_lut_entry(l, a, s) : kmq::launch_pair_generic(a, s);
     return kmq::hip_status(e);
 }
 
 const char* kmq_kernel_name_swiglu(int64_t N, int64_t K, int bits, int layout) {
-    if (!kmq::bits_valid(bits) || !kmq::dims_valid(N, K) || layout != KMQ_LAYOUT_CANONICAL) return "invalid";
+    if (!kmq::bits_valid(bits) || !kmq::dims_valid(N, K)) return "invalid";
+    if (layout == KMQ_LAYOUT_ROWLANE && kmq::rowlane_pair_has_kernel(K, bits)) return bits == 1 ? "rowlane_pair_b1" : "rowlane_pair_b2";
+    if (layout != KMQ_LAYOUT_CANONICAL) return "invalid";
     const int l = kmq::lut_find(2 * N, K, bits, layout, false);
     return l >= 0 ? kmq::lut_name(l) : "pair_generic";
 }

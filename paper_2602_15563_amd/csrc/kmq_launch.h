@@ -79,6 +79,8 @@ int mfma_row_blocks(int64_t N, int64_t K, int bits);
 bool rowlane_has_kernel(int64_t K, int bits, int M);
 bool rowlane_loops(int64_t K);              // K served by the kernel that walks K in rounds
 hipError_t launch_rowlane(const GemmArgs& a, hipStream_t s);
+bool rowlane_pair_has_kernel(int64_t K, int bits);     // fused gate / up / SwiGLU on the row-lane layout
+hipError_t launch_rowlane_pair(const GemmArgs& a, hipStream_t s);
 
 // Hand-scheduled table kernels (1/2/4-bit): -1 if (bits, K, layout) has none.
 int lut_find(int64_t N, int64_t K, int bits, int layout, bool scaled = false);

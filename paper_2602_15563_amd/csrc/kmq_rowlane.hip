@@ -52,20 +52,23 @@ __device__ __forceinline__ void static_for(F&& f) {
 // (odd nibbles).  `a` holds lane*4 in byte 0; byte 1 receives the nibble: entry*256 + lane*4.
 #define KMQ_RL_SDWA(dst, src, dbyte, sbyte) \
     "v_and_b32_sdwa " dst ", " src ", %10 dst_sel:BYTE_" dbyte " dst_unused:UNUSED_PRESERVE src0_sel:BYTE_" sbyte " src1_sel:DWORD\n\t"
-template <int H>
+// OFF: byte offset of the table inside the workgroup's LDS (an immediate of the read: byte 1 of the
+// address register belongs to the nibble).
+template <int H, int OFF = 0>
 __device__ __forceinline__ void issue4_pair(uint32_t w, uint32_t ws, uint32_t (&a)[4], uint32_t* v, uint32_t mask) {
+    static_assert(OFF >= 0 && OFF < 65536, "16-bit offset field");
     if constexpr (H == 0) {
         asm volatile(
             KMQ_RL_SDWA("%4", "%8", "1", "0") KMQ_RL_SDWA("%5", "%9", "1", "0") KMQ_RL_SDWA("%6", "%8", "1", "1") KMQ_RL_SDWA("%7", "%9", "1", "1")
-            "ds_read_b32 %0, %4\n\tds_read_b32 %1, %5\n\tds_read_b32 %2, %6\n\tds_read_b32 %3, %7"
+            "ds_read_b32 %0, %4 offset:%c11\n\tds_read_b32 %1, %5 offset:%c11\n\tds_read_b32 %2, %6 offset:%c11\n\tds_read_b32 %3, %7 offset:%c11"
             : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3])
-            : "v"(w), "v"(ws), "v"(mask));
+            : "v"(w), "v"(ws), "v"(mask), "n"(OFF));
     } else {
         asm volatile(
             KMQ_RL_SDWA("%4", "%8", "1", "2") KMQ_RL_SDWA("%5", "%9", "1", "2") KMQ_RL_SDWA("%6", "%8", "1", "3") KMQ_RL_SDWA("%7", "%9", "1", "3")
-            "ds_read_b32 %0, %4\n\tds_read_b32 %1, %5\n\tds_read_b32 %2, %6\n\tds_read_b32 %3, %7"
+            "ds_read_b32 %0, %4 offset:%c11\n\tds_read_b32 %1, %5 offset:%c11\n\tds_read_b32 %2, %6 offset:%c11\n\tds_read_b32 %3, %7 offset:%c11"
             : "=&v"(v[0]), "=&v"(v[1]), "=&v"(v[2]), "=&v"(v[3]), "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3])
-            : "v"(w), "v"(ws), "v"(mask));
+            : "v"(w), "v"(ws), "v"(mask), "n"(OFF));
     }
 }
 
@@ -164,19 +167,25 @@ __device__ unsigned long long kmq_rowlane_ts[1024 * 16 * 8];
 // across rounds: the shapes with a kernel of their own do not take this path.)
 // DBG (instrumented builds only) takes parts of the kernel out, to time the rest: 1 no loads of
 // x, 2 no loads of the codebook, 16 no lookups, 32 no loads of the index words, 64 no store.
-template <int BITS, int CPW, int MB, int WPE, bool LOOP = false, int DBG = 0>
+// PAIR: the fused gate / up / SwiGLU call: the workgroup decodes the same 16 rows of TWO matrices (W, W2)
+// against the same activations -- a wave's tiles of W2 follow its tiles of W through the same pipeline,
+// with a second pair table -- and stores silu(W x) * (W2 x).
+template <int BITS, int CPW, int MB, int WPE, bool LOOP = false, int DBG = 0, bool PAIR = false>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
-                         const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int64_t N, int64_t K) {
+                         const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int64_t N, int64_t K,
+                         const uint32_t* __restrict__ W2 = nullptr, const uint16_t* __restrict__ codebook2 = nullptr) {
     using namespace rowlane;
     static_assert(BITS == 1 || BITS == 2, "bit-width");
+    static_assert(!PAIR || (MB == 1 && !LOOP), "the fused pair: one activation vector, shapes with a kernel of their own");
+    constexpr int NMAT = PAIR ? 2 : 1;
     constexpr int G = 2 * BITS;                     // index words per lane and tile
     constexpr int TILE_BYTES = 256 * G;
     struct alignas(256) Smem {
-        // 2-bit: [entry][lane] bf16 pairs (centroid of the even element, of the odd element);
+        // 2-bit: per matrix, [entry][lane] bf16 pairs (centroid of the even element, of the odd element);
         // 1-bit: per wave, at a 256-byte stride, 16 entries of four bf16 {0,1} masks
-        uint32_t lut[16 * 64];
-        float part[MB][16][64];         // [column][wave][lane] partial sums
+        uint32_t lut[NMAT * 16 * 64];
+        float part[NMAT * MB][16][64];  // [matrix, column][wave][lane] partial sums
         float sx[MB][16];               // 1-bit: per column and wave, the sum of the wave's activations
     };
     __shared__ Smem sm;
@@ -206,6 +215,7 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
     const char* const x_base = reinterpret_cast<const char*>(X) + static_cast<uint32_t>(wave) * 512;
     const char* const w_base = reinterpret_cast<const char*>(W) + (static_cast<uint64_t>(rb) * tiles + static_cast<uint32_t>(wave)) * TILE_BYTES;
     uint32_t cb[2];                                                            // 2-bit: four centroids; 1-bit: cb[0] = (c0, c1)
+    [[maybe_unused]] uint32_t cb2[2] = {0, 0};                                  // PAIR: the same row of the second matrix
     if constexpr (DBG & 2) {
         cb[0] = 0x3C003B00u + lane;
         cb[1] = 0x3E003D00u;
@@ -214,18 +224,24 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
         const u32x2_t c = *reinterpret_cast<const u32x2_a4_t*>(cb_base + off_c);
         cb[0] = c[0];
         cb[1] = c[1];
+        if constexpr (PAIR) {
+            const u32x2_t c2 = *reinterpret_cast<const u32x2_a4_t*>(reinterpret_cast<const char*>(codebook2) + static_cast<uint64_t>(rb) * (16 * CB_ROW) + off_c);
+            cb2[0] = c2[0];
+            cb2[1] = c2[1];
+        }
     } else {
         cb[0] = *reinterpret_cast<const uint32_t*>(cb_base + off_c);
         cb[1] = 0;
+        if constexpr (PAIR) cb2[0] = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(codebook2) + static_cast<uint64_t>(rb) * (16 * CB_ROW) + off_c);
     }
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);      // (left alone, the compiler sinks this load below the index loads)
     u32x2_t xv[MB][CPW];
     using wvec_t = typename WordVec<G>::type;
-    wvec_t wv[CPW];
-    float acc[MB][2];
+    wvec_t wv[NMAT * CPW];                                                      // PAIR: slots CPW .. 2 CPW - 1 hold the second matrix
+    float acc[NMAT * MB][2];
 #pragma unroll
-    for (int m = 0; m < MB; ++m) acc[m][0] = acc[m][1] = 0.f;
+    for (int m = 0; m < NMAT * MB; ++m) acc[m][0] = acc[m][1] = 0.f;
     [[maybe_unused]] float sxl[MB];                                            // LOOP, 1-bit: this lane's share of the sum of x
 #pragma unroll
     for (int m = 0; m < MB; ++m) sxl[m] = 0.f;
@@ -273,6 +289,14 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
             wv[j] = __builtin_nontemporal_load(reinterpret_cast<const __attribute__((address_space(1))) wvec_t*>(reinterpret_cast<global_cchar_t*>(wb) + off_w));
         }
     }
+    if constexpr (PAIR) {
+#pragma unroll
+        for (int j = 0; j < CPW; ++j) {
+            uint64_t wb = reinterpret_cast<uint64_t>(W2) + (static_cast<uint64_t>(rb) * tiles + static_cast<uint32_t>(wave) + static_cast<uint64_t>(j) * nwk) * TILE_BYTES;
+            asm volatile("" : "+s"(wb));
+            wv[CPW + j] = __builtin_nontemporal_load(reinterpret_cast<const __attribute__((address_space(1))) wvec_t*>(reinterpret_cast<global_cchar_t*>(wb) + off_w));
+        }
+    }
     if constexpr (LOOP) {
 #pragma unroll
         for (int j = 0; j < CPW; ++j)
@@ -293,6 +317,7 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
                 const uint32_t a = (e & 3) * 2, b = (e >> 2) * 2;
                 const uint32_t sel = a | ((a + 1) << 8) | (b << 16) | ((b + 1) << 24);
                 sm.lut[e * 64 + lane] = __builtin_amdgcn_perm(cb[1], cb[0], sel);
+                if constexpr (PAIR) sm.lut[1024 + e * 64 + lane] = __builtin_amdgcn_perm(cb2[1], cb2[0], sel);
                 e += nwk;
             } while (e < 16);
             KMQ_TS(2);
@@ -355,19 +380,20 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
 #endif
         issue4_pair<0>(wv[0][0], ws[0], ar, &v[0][0], mask);
         issue4_pair<1>(wv[0][0], ws[0], ar, &v[0][4], mask);
-        static_for<0, NW>([&](auto ic) {
+        // word n of the wave: slot n / 4 (tile j = slot % CPW of matrix slot / CPW), word n % 4 of the lane's chunk
+        static_for<0, NMAT * NW>([&](auto ic) {
             constexpr int n = decltype(ic)::value;
-            constexpr int j = n / 4, q = n % 4;
-            if constexpr (n + 1 < NW) {
-                constexpr int j1 = (n + 1) / 4, q1 = (n + 1) % 4;
-                ws[(n + 1) & 1] = wv[j1][q1] >> 4;
-                issue4_pair<0>(wv[j1][q1], ws[(n + 1) & 1], ar, &v[(n + 1) & 1][0], mask);
-                dot8_pair<4, 8 * (q % 2)>(v[n & 1], xv[0][j][q / 2], acc[0][0], acc[0][1]);
+            constexpr int slot = n / 4, q = n % 4, j = slot % CPW, mat = slot / CPW;
+            if constexpr (n + 1 < NMAT * NW) {
+                constexpr int slot1 = (n + 1) / 4, q1 = (n + 1) % 4, off1 = (slot1 / CPW) * 4096;
+                ws[(n + 1) & 1] = wv[slot1][q1] >> 4;
+                issue4_pair<0, off1>(wv[slot1][q1], ws[(n + 1) & 1], ar, &v[(n + 1) & 1][0], mask);
+                dot8_pair<4, 8 * (q % 2)>(v[n & 1], xv[0][j][q / 2], acc[mat * MB][0], acc[mat * MB][1]);
 #pragma unroll
                 for (int m = 1; m < MB; ++m) dot8_pair<-1, 8 * (q % 2)>(v[n & 1], xv[m][j][q / 2], acc[m][0], acc[m][1]);
-                issue4_pair<1>(wv[j1][q1], ws[(n + 1) & 1], ar, &v[(n + 1) & 1][4], mask);
+                issue4_pair<1, off1>(wv[slot1][q1], ws[(n + 1) & 1], ar, &v[(n + 1) & 1][4], mask);
             } else {
-                dot8_pair<0, 8 * (q % 2)>(v[n & 1], xv[0][j][q / 2], acc[0][0], acc[0][1]);
+                dot8_pair<0, 8 * (q % 2)>(v[n & 1], xv[0][j][q / 2], acc[mat * MB][0], acc[mat * MB][1]);
 #pragma unroll
                 for (int m = 1; m < MB; ++m) dot8_pair<-1, 8 * (q % 2)>(v[n & 1], xv[m][j][q / 2], acc[m][0], acc[m][1]);
             }
@@ -383,16 +409,17 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
         if (ts_on) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); KMQ_TS(4); asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 #endif
         issue4_mask<0>(wv[0][0], wr[0], ar, vv[0], mask);
-        static_for<0, NG>([&](auto ic) {
+        // group g of the wave: word g / 2 (slot word / 2: tile j = slot % CPW of matrix slot / CPW), half g % 2
+        static_for<0, NMAT * NG>([&](auto ic) {
             constexpr int g = decltype(ic)::value;
-            constexpr int n = g / 2, h = g % 2, j = n / 2, q = n % 2;
-            if constexpr (g + 1 < NG) {
-                constexpr int n1 = (g + 1) / 2, h1 = (g + 1) % 2, j1 = n1 / 2, q1 = n1 % 2;
-                if constexpr (h1 == 0) wr[n1 & 1] = __builtin_amdgcn_alignbit(wv[j1][q1], wv[j1][q1], 4);
-                issue4_mask<h1>(wv[j1][q1], wr[n1 & 1], ar, vv[(g + 1) & 1], mask);
-                dot8_mask<4, 8 * q + 4 * h>(vv[g & 1], xv[0][j][0], xv[0][j][1], acc[0][0], acc[0][1]);
+            constexpr int n = g / 2, h = g % 2, slot = n / 2, q = n % 2, j = slot % CPW, mat = slot / CPW;
+            if constexpr (g + 1 < NMAT * NG) {
+                constexpr int n1 = (g + 1) / 2, h1 = (g + 1) % 2, slot1 = n1 / 2, q1 = n1 % 2;
+                if constexpr (h1 == 0) wr[n1 & 1] = __builtin_amdgcn_alignbit(wv[slot1][q1], wv[slot1][q1], 4);
+                issue4_mask<h1>(wv[slot1][q1], wr[n1 & 1], ar, vv[(g + 1) & 1], mask);
+                dot8_mask<4, 8 * q + 4 * h>(vv[g & 1], xv[0][j][0], xv[0][j][1], acc[mat * MB][0], acc[mat * MB][1]);
             } else {
-                dot8_mask<0, 8 * q + 4 * h>(vv[g & 1], xv[0][j][0], xv[0][j][1], acc[0][0], acc[0][1]);
+                dot8_mask<0, 8 * q + 4 * h>(vv[g & 1], xv[0][j][0], xv[0][j][1], acc[mat * MB][0], acc[mat * MB][1]);
             }
 #pragma unroll
             for (int m = 1; m < MB; ++m) dot8_mask<-1, 8 * q + 4 * h>(vv[g & 1], xv[m][j][0], xv[m][j][1], acc[m][0], acc[m][1]);
@@ -412,7 +439,7 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
 
     // ---- K-reduction through LDS, fixed order ---------------------------------------------------------
 #pragma unroll
-    for (int m = 0; m < MB; ++m) {
+    for (int m = 0; m < NMAT * MB; ++m) {
         settle(acc[m][0], acc[m][1]);
         sm.part[m][wave][lane] = acc[m][0] + acc[m][1];
     }
@@ -421,19 +448,27 @@ void gemv_rowlane_kernel(const uint32_t* __restrict__ W, const uint16_t* __restr
     // wave m finishes batch column m: each lane adds its own column of partial sums over the waves, then the
     // four 16-lane rows (the four chunks of a tile) are added lane by lane with two half-swaps
     for (uint32_t m = wave; m < MB; m += nwk) {
-        float s = 0.f;
-        for (uint32_t w = 0; w < nwk; ++w) s += sm.part[m][w][lane];
-        const auto h16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(s), __float_as_uint(s), false, false);
-        s = __uint_as_float(h16[0]) + __uint_as_float(h16[1]);                 // rows 0+1 | 0+1 | 2+3 | 2+3
-        const auto h32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(s), __float_as_uint(s), false, false);
-        s = __uint_as_float(h32[0]) + __uint_as_float(h32[1]);                 // all four, in every lane
-        if constexpr (BITS == 1) {
-            float sx = 0.f;
-            for (uint32_t w = 0; w < nwk; ++w) sx += sm.sx[m][w];
-            // (every lane loaded the centroids of row lane % 16 of the block)
-            const float c0 = bf16_to_f32(cb[0] & 0xFFFFu), c1 = bf16_to_f32(cb[0] >> 16);
-            s = fmaf(c1 - c0, s, c0 * sx);
+        float res[NMAT];
+#pragma unroll
+        for (int mat = 0; mat < NMAT; ++mat) {
+            float s = 0.f;
+            for (uint32_t w = 0; w < nwk; ++w) s += sm.part[mat * MB + m][w][lane];
+            const auto h16 = __builtin_amdgcn_permlane16_swap(__float_as_uint(s), __float_as_uint(s), false, false);
+            s = __uint_as_float(h16[0]) + __uint_as_float(h16[1]);                 // rows 0+1 | 0+1 | 2+3 | 2+3
+            const auto h32 = __builtin_amdgcn_permlane32_swap(__float_as_uint(s), __float_as_uint(s), false, false);
+            s = __uint_as_float(h32[0]) + __uint_as_float(h32[1]);                 // all four, in every lane
+            if constexpr (BITS == 1) {
+                float sx = 0.f;
+                for (uint32_t w = 0; w < nwk; ++w) sx += sm.sx[m][w];
+                // (every lane loaded the centroids of row lane % 16 of the block)
+                const uint32_t c01 = mat == 0 ? cb[0] : cb2[0];
+                const float c0 = bf16_to_f32(c01 & 0xFFFFu), c1 = bf16_to_f32(c01 >> 16);
+                s = fmaf(c1 - c0, s, c0 * sx);
+            }
+            res[mat] = s;
         }
+        float s = res[0];
+        if constexpr (PAIR) s = res[0] / (1.f + __expf(-res[0])) * res[NMAT - 1];   // silu(gate) * up
         const uint32_t rr = lane & 15;
         const int64_t n0 = static_cast<int64_t>(rb) * 16 + rr;
         const uint32_t mine = f32_to_bf16(s);
@@ -541,6 +576,33 @@ static hipError_t launch_rowlane_bits(const GemmArgs& a, const RowlaneShape& s, 
 #undef KMQ_RL_CPW
 #undef KMQ_RL_LAUNCH
     return hipGetLastError();
+}
+
+// The fused gate / up / SwiGLU call: shapes with at most four tiles per wave (a wave then holds eight).
+bool rowlane_pair_has_kernel(int64_t K, int bits) {
+    RowlaneShape s;
+    return rowlane_valid(bits, K) && rowlane_shape(K, s) && !s.loop && s.cpw <= 4;
+}
+
+template <int BITS>
+static hipError_t launch_rowlane_pair_bits(const GemmArgs& a, const RowlaneShape& s, hipStream_t st) {
+    const dim3 grid(static_cast<unsigned>((a.N + 15) / 16)), block(64 * s.nwk);
+#define KMQ_RL_PAIR(CPW, WPE) \
+    hipLaunchKernelGGL((gemv_rowlane_kernel<BITS, CPW, 1, WPE, false, 0, true>), grid, block, 0, st, a.W, a.codebook, a.X, a.Y, a.N, a.K, a.W2, a.codebook2)
+    switch (s.cpw) {
+        case 1: KMQ_RL_PAIR(1, 8); break;
+        case 2: KMQ_RL_PAIR(2, 8); break;
+        case 3: KMQ_RL_PAIR(3, 4); break;
+        default: KMQ_RL_PAIR(4, 4); break;
+    }
+#undef KMQ_RL_PAIR
+    return hipGetLastError();
+}
+
+hipError_t launch_rowlane_pair(const GemmArgs& a, hipStream_t st) {
+    RowlaneShape s;
+    if (!rowlane_shape(a.K, s) || s.loop || s.cpw > 4 || !a.W2 || !a.codebook2) return hipErrorInvalidValue;
+    return a.bits == 1 ? launch_rowlane_pair_bits<1>(a, s, st) : launch_rowlane_pair_bits<2>(a, s, st);
 }
 
 // A launch decodes every weight once for up to four batch columns (the registers that hold the

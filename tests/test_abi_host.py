@@ -253,6 +253,9 @@ def test_heuristic_names():
     assert kmq.kernel_name(64, 11008, 1, 3, kmq.LAYOUT_ROWLANE) == "rowlane_loop_b1" and kmq.kernel_name(64, 65536, 2, 1, kmq.LAYOUT_ROWLANE) == "rowlane_loop_b2"
     assert kmq.kernel_name(64, 28672, 2, 1, kmq.LAYOUT_ROWLANE) == "rowlane_b2"              # 112 tiles = 7 x 16 waves
     assert kmq.kernel_name(64, 4000, 2, 1, kmq.LAYOUT_ROWLANE) == "invalid"                  # the layout needs whole tiles
+    assert kmq.kernel_name_swiglu(14336, 4096, 2, kmq.LAYOUT_ROWLANE) == "rowlane_pair_b2"
+    assert kmq.kernel_name_swiglu(8192, 3072, 1, kmq.LAYOUT_ROWLANE) == "rowlane_pair_b1"
+    assert kmq.kernel_name_swiglu(64, 256 * 17, 2, kmq.LAYOUT_ROWLANE) == "invalid" and kmq.kernel_name_swiglu(64, 4096, 3, kmq.LAYOUT_ROWLANE) == "invalid"
     assert kmq.workspace_bytes(14336, 4096, 2, 4, kmq.LAYOUT_ROWLANE) == 0
 
 

@@ -16,7 +16,7 @@ def gpu():
     return gpu_util
 
 
-def _check(gpu, bits, N, K, seed):
+def _check(gpu, bits, N, K, seed, layout=0):
     from paper_2602_15563_amd import kmq
     ig, iu = synth.make_indices(seed, 0, N, K, bits), synth.make_indices(seed, 1, N, K, bits)
     sym = bits == 1
@@ -24,7 +24,10 @@ def _check(gpu, bits, N, K, seed):
     # activations scaled so that the gate spans the interesting range of silu (|g| up to a few units)
     x = synth.f32_to_bf16((synth.bf16_to_f32(synth.make_x(seed, 0, 1, K)[0]) * np.float32(40.0 / np.sqrt(K))))
     y = torch.full((N,), 0x7FC1, dtype=torch.int16, device="cuda")
-    kmq.gemv_swiglu(gpu.dev(kmq.pack(ig, bits)), gpu.dev(cg), gpu.dev(kmq.pack(iu, bits)), gpu.dev(cu), gpu.dev(x), y, N, K, bits)
+    pg, pu = kmq.pack(ig, bits), kmq.pack(iu, bits)
+    if layout:
+        pg, pu = kmq.repack(pg, K, bits, layout), kmq.repack(pu, K, bits, layout)
+    kmq.gemv_swiglu(gpu.dev(pg), gpu.dev(cg), gpu.dev(pu), gpu.dev(cu), gpu.dev(x), y, N, K, bits, layout)
     torch.cuda.synchronize()
     yg = synth.bf16_to_f64(gpu.host_u16(y))
     G, Ag, _ = oracle.gemm(oracle.pack(ig, bits), cg, x, K, bits)
@@ -53,6 +56,29 @@ def test_fused_pair_on_the_table_kernels(gpu, bits, K, N):
     from paper_2602_15563_amd import kmq
     assert kmq.kernel_name_swiglu(N, K, bits).startswith("lut_"), kmq.kernel_name_swiglu(N, K, bits)
     _check(gpu, bits, N, K, 7 * bits + N + K)
+
+
+# row-lane layout: 1, 2, 3 and 4 tiles per wave (K / 256 = 1 .. 56 tiles)
+@pytest.mark.parametrize("bits", (1, 2))
+@pytest.mark.parametrize("K", (256, 1024, 1536, 2048, 3072, 4096, 6144, 8192, 12288, 14336))
+@pytest.mark.parametrize("N", (1, 16, 17, 64, 333))
+def test_fused_pair_on_the_rowlane_kernels(gpu, bits, K, N):
+    from paper_2602_15563_amd import kmq
+    assert kmq.kernel_name_swiglu(N, K, bits, kmq.LAYOUT_ROWLANE) == f"rowlane_pair_b{bits}"
+    _check(gpu, bits, N, K, 11 * bits + N + K, layout=kmq.LAYOUT_ROWLANE)
+
+
+def test_fused_pair_rowlane_rejections(gpu):
+    """3 and 4 bits have no row-lane layout; tile counts that need more than four tiles per wave or the round loop
+    have no fused kernel: KMQ_ERR_LAYOUT before any launch."""
+    from paper_2602_15563_amd import kmq
+    z = torch.zeros(1 << 16, dtype=torch.int32, device="cuda")
+    y = torch.zeros(64, dtype=torch.int16, device="cuda")
+    for bits, K in ((3, 4096), (4, 4096), (2, 256 * 17), (1, 256 * 96), (2, 4000)):
+        assert kmq.kernel_name_swiglu(16, K, bits, kmq.LAYOUT_ROWLANE) == "invalid"
+        with pytest.raises(kmq.KmqError) as e:
+            kmq.gemv_swiglu(z, z, z, z, z, y, 16, K, bits, kmq.LAYOUT_ROWLANE)
+        assert e.value.status == 7          # KMQ_ERR_LAYOUT
 
 
 @pytest.mark.parametrize("bits,N,K", [(3, 40, 1024), (2, 9, 515), (4, 100, 33), (1, 7, 1), (3, 130, 1000)])
