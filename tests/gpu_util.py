@@ -6,17 +6,8 @@ import torch
 import oracle
 from paper_2602_15563_amd import kmq, synth
 
-TOL = 2e-3   # |y_gpu - y_oracle| <= TOL * sum_k |w x|  (the benchmark contract's criterion)
-
-# What the arithmetic itself allows, for any shape: fp32 accumulation in any
-# order is within K * 2^-23 * A of the exact sum, and rounding the result to
-# bf16 (8 significant bits) adds at most half an ulp <= 2^-8 * |y|.  For short
-# or same-sign rows |y| is close to A and the rounding term alone exceeds TOL*A
-# (a single product, K = 1, can be off by 0.39 % of itself in ANY bf16 output),
-# so the contract's criterion is asserted where it is attainable (rows of the
-# benchmark configurations: long, mixed-sign sums) and this bound everywhere.
-def arithmetic_bound(A, Y, K):
-    return (K + 8) * 2.0 ** -23 * A + 2.0 ** -8 * (np.abs(Y) + (K + 8) * 2.0 ** -23 * A)
+# every acceptance bound lives in one module, shared with bench.py
+from paper_2602_15563_amd.tolerance import TOL, arithmetic_bound, rmsnorm_commute_bound, swiglu_bound, swiglu_contract_bound  # noqa: E402,F401
 
 
 def dev(a: np.ndarray) -> torch.Tensor:

@@ -43,13 +43,9 @@ def _check(gpu, yg, idx, cb, x, bits, g, res, label, unit=False):
     # fp32 sums in any order, the scalar in fp32 (a few roundings), one bf16 rounding of the result
     bound = gpu.arithmetic_bound(A, Y, K + 16)
     if g is not None or unit:
-        # The oracle rounds x*r*g to bf16; the kernels round x*g and apply the scalar r to the fp32 sum (it
-        # commutes with the sum).  Both roundings are within half an ulp (2^-8, relative) of the same exact
-        # value, so an activation differs by at most 2^-7 of itself and the sum by at most 2^-7 * sum |w xn|.
-        # That is the guarantee; independent rounding errors add in quadrature, so for long rows the
-        # difference stays far inside the contract's 2e-3 * A, which is asserted below as well.
+        # the oracle rounds x*r*g to bf16, the kernels round x*g and apply r to the sum (tolerance.py, item 4)
         Ap = A - (np.abs(synth.bf16_to_f64(res)) if res is not None else 0.0)
-        bound = bound + 2.0 ** -7 * Ap
+        bound = bound + gpu.rmsnorm_commute_bound(Ap)
     bad = err > bound
     if K >= 512:
         bad |= err > gpu.TOL * A + 2.0 ** -8 * np.abs(Y)

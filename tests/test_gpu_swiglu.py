@@ -33,12 +33,8 @@ def _check(gpu, bits, N, K, seed, layout=0):
     G, Ag, _ = oracle.gemm(oracle.pack(ig, bits), cg, x, K, bits)
     U, Au, _ = oracle.gemm(oracle.pack(iu, bits), cu, x, K, bits)
     want = oracle.swiglu(G, U)
-    # error propagation: fp32 sums of both products (any order), silu' in [-0.1, 1.1], a few fp32
-    # roundings in the combination, one bf16 rounding of the result
-    dg, du = (K + 8) * 2.0 ** -23 * Ag, (K + 8) * 2.0 ** -23 * Au
     silu = oracle.swiglu(G, np.ones_like(G))
-    inner = 1.1 * np.abs(U) * dg + np.abs(silu) * du + 1.1 * dg * du + 8 * 2.0 ** -23 * np.abs(want)
-    bound = inner + 2.0 ** -8 * (np.abs(want) + inner)
+    bound = gpu.swiglu_bound(G, U, Ag, Au, silu, want, K)
     err = np.abs(yg - want)
     assert np.all(err <= bound), f"b{bits} {N}x{K}: max err/bound {np.max(err / np.maximum(bound, 1e-300)):.2f}"
     if N >= 64:
