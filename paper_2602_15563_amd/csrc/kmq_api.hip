@@ -58,6 +58,7 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled) {
     if (layout == KMQ_LAYOUT_TILED && !tiled_valid(bits, K)) return p;
     if (layout == KMQ_LAYOUT_TILED) {
         static const char* const names[4] = {"mfma_b1", "mfma_b2", "mfma_b3", "mfma_b4"};
+        if (mfma_kslice_has_kernel(N, K, bits)) return Plan{kVariantMfma, -1, 0, bits == 2 ? "mfma_kslice_b2" : "mfma_kslice_b3"};
         return Plan{kVariantMfma, -1, 0, names[bits - 1]};
     }
     if (M == 1 || per_column_faster(M)) {

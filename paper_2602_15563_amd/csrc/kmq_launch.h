@@ -72,6 +72,9 @@ hipError_t launch_quantize_blockscaled(const uint16_t* W, int64_t N, int64_t K, 
 
 // Matrix-core kernel (tiled layout only).
 hipError_t launch_mfma(const GemmArgs& a, hipStream_t s);
+// 2- and 3-bit rows of at most 4096 columns: every wave keeps its slice of the activations in registers
+bool mfma_kslice_has_kernel(int64_t N, int64_t K, int bits);
+hipError_t launch_mfma_kslice(const GemmArgs& a, hipStream_t s);
 int mfma_waves_along_k(int64_t N, int64_t K, int bits);
 int mfma_row_blocks(int64_t N, int64_t K, int bits);
 

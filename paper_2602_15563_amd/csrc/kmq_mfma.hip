@@ -585,6 +585,8 @@ int mfma_row_blocks(int64_t N, int64_t K, int bits) {
 int mfma_waves_along_k(int64_t N, int64_t K, int bits) { return waves_along_k(K, bits, mfma_row_blocks(N, K, bits)); }
 
 hipError_t launch_mfma(const GemmArgs& a, hipStream_t s) {
+    // short 2- and 3-bit rows: the kernel whose waves keep their slice of the activations in registers
+    if (!a.scales && mfma_kslice_has_kernel(a.N, a.K, a.bits)) return launch_mfma_kslice(a, s);
     const int rbw = mfma_row_blocks(a.N, a.K, a.bits), nwk = waves_along_k(a.K, a.bits, rbw);
     const int spw = static_cast<int>(a.K / tiled_superblock_elems(a.bits) / nwk);
     switch (a.bits) {

@@ -246,6 +246,7 @@ def test_heuristic_names():
     assert kmq.kernel_name(77, 515, 2, 1) == "generic"
     assert kmq.kernel_name(4096, 4096, 3, 16, kmq.LAYOUT_TILED) == "mfma_b3"
     assert kmq.kernel_name(4096, 4000, 3, 16, kmq.LAYOUT_TILED) == "invalid"
+    assert kmq.kernel_name(14336, 4096, 3, 16, kmq.LAYOUT_TILED) == "mfma_kslice_b3" and kmq.kernel_name(14336, 8192, 3, 16, kmq.LAYOUT_TILED) == "mfma_b3"
     assert kmq.kernel_name(14336, 4096, 2, 1, kmq.LAYOUT_ROWLANE) == "rowlane_b2"
     assert kmq.kernel_name(9216, 3072, 1, 4, kmq.LAYOUT_ROWLANE) == "rowlane_b1"
     assert kmq.kernel_name(9216, 3072, 1, 16, kmq.LAYOUT_ROWLANE) == "rowlane_b1"     # four launches of four columns
