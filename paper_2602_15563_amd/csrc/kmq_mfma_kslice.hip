@@ -193,7 +193,9 @@ __global__ __launch_bounds__(1024) void gemm_mfma_kslice_kernel(
 
     // ---- K-reduction across the waves, fixed order: lane holds D[row 4q + i][batch column n] ----
     // (one output per thread, every thread busy: four rows per thread with 16-byte LDS accesses and 8-byte
-    // stores leaves three quarters of the waves idle behind a chain of 16 loads and measured 3 % slower)
+    // stores leaves three quarters of the waves idle behind a chain of 16 loads and measured 3 % slower; a
+    // reduction per row block, overlapped with the next block's decode, costs a barrier per block and
+    // measured 19 % slower)
 #pragma unroll
     for (int r = 0; r < RPW; ++r)
 #pragma unroll
