@@ -98,8 +98,8 @@ class Instances:
         bits, N, K, M = self.bits, self.N, self.K, self.M
         # Default layouts (the offline, reversible repack is outside the timed region), by what was measured
         # fastest within the contract's rule that the matrix cores serve batches of 8 and more:
-        #   batch 1: the row-lane layout for 2-bit matrices with many rows (14336 x 4096: 5.4 us against 6.0 us
-        #            canonical; 4096 x 14336, 256 row blocks: 6.7 against 6.5, stays canonical), else canonical;
+        #   batch 1: the row-lane layout for 2-bit matrices (14336 x 4096: 5.4 us against 6.0 us canonical;
+        #            4096 x 14336: 6.0 against 6.5), canonical for the rest (1-bit: both within 0.2 us);
         #   batch 2..7: the row-lane layout where it exists (1 and 2 bits: every weight decoded once, on the
         #            vector units), else tiled;
         #   batch >= 8: tiled (matrix-core kernel).
@@ -107,7 +107,7 @@ class Instances:
             from paper_2602_15563_amd import kmq as _k
             has_rowlane = not self.scaled and _k.kernel_name(N, K, bits, M, 2) != "invalid"
             if M == 1:
-                layout = 2 if (has_rowlane and bits == 2 and N >= 8192) else 0
+                layout = 2 if (has_rowlane and bits == 2) else 0
             elif M < 8:
                 layout = 2 if has_rowlane else 1
             else:

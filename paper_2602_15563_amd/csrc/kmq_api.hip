@@ -39,7 +39,7 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled) {
     if (layout == KMQ_LAYOUT_ROWLANE) {
         if (scaled || !rowlane_valid(bits, K) || !rowlane_has_kernel(K, bits, M)) return p;
         static const char* const names[2][2] = {{"rowlane_b1", "rowlane_b2"}, {"rowlane_loop_b1", "rowlane_loop_b2"}};
-        return Plan{kVariantRowlane, -1, 0, names[rowlane_loops(K) ? 1 : 0][bits - 1]};
+        return Plan{kVariantRowlane, -1, 0, names[rowlane_loops(K, bits) ? 1 : 0][bits - 1]};
     }
     if (scaled) {
         if (K % KMQ_BLOCK != 0) return p;

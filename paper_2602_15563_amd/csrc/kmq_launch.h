@@ -80,7 +80,7 @@ int mfma_row_blocks(int64_t N, int64_t K, int bits);
 
 // Row-lane layout kernels (batch 1..4).
 bool rowlane_has_kernel(int64_t K, int bits, int M);
-bool rowlane_loops(int64_t K);              // K served by the kernel that walks K in rounds
+bool rowlane_loops(int64_t K, int bits);              // K served by the kernel that walks K in rounds
 hipError_t launch_rowlane(const GemmArgs& a, hipStream_t s);
 bool rowlane_pair_has_kernel(int64_t K, int bits);     // fused gate / up / SwiGLU on the row-lane layout
 hipError_t launch_rowlane_pair(const GemmArgs& a, hipStream_t s);

@@ -505,8 +505,12 @@ struct RowlaneShape { int cpw, nwk; bool loop; };
 // K / 256 tiles = cpw * nwk with nwk <= 16 waves; many thin waves first (occupancy hides the LDS latency
 // of the lookups better than a deeper per-wave queue, which the 4-bit LGKM counter caps anyway).
 // A tile count with no such factorisation (17, 19, 34, 43, ... or beyond 128) takes the kernel that
-// walks K in rounds of 2 * nwk tiles.
-static bool rowlane_shape(int64_t K, RowlaneShape& s) {
+// walks K in rounds of 2 * nwk tiles -- and so does every 2-bit row of more than 32 tiles: three and
+// more 16-byte index loads per lane in flight at once measured slower than rounds of two (4096 x 14336:
+// 6.9 us with four tiles per wave, 6.1 us in two rounds; 8192 x 28672: 19.8 against 17.3 us; fetching a
+// round ahead: 6.7 us).  1-bit rows (8-byte loads) keep the instances with everything in flight
+// (4096 x 14336: 5.1 against 5.5 us in rounds).
+static bool rowlane_shape(int64_t K, int bits, RowlaneShape& s, bool pair = false) {
     const int64_t tiles = K / 256;
     static const int cpws[] = {2, 1, 3, 4, 6, 7, 8};
 #ifdef KMQ_TUNING
@@ -518,6 +522,7 @@ static bool rowlane_shape(int64_t K, RowlaneShape& s) {
     }
 #endif
     for (int c : cpws) {
+        if (bits == 2 && c > 2 && !pair) continue;       // (the fused pair has no round loop: it keeps the instances)
         if (tiles % c == 0 && tiles / c <= 16 && tiles / c >= 1) { s = {c, static_cast<int>(tiles / c), false}; return true; }
     }
     if (tiles < 1) return false;
@@ -529,12 +534,12 @@ static bool rowlane_shape(int64_t K, RowlaneShape& s) {
 
 bool rowlane_has_kernel(int64_t K, int bits, int M) {
     RowlaneShape s;
-    return rowlane_valid(bits, K) && M >= 1 && M <= KMQ_MAX_BATCH && rowlane_shape(K, s);
+    return rowlane_valid(bits, K) && M >= 1 && M <= KMQ_MAX_BATCH && rowlane_shape(K, bits, s);
 }
 
-bool rowlane_loops(int64_t K) {
+bool rowlane_loops(int64_t K, int bits) {
     RowlaneShape s;
-    return rowlane_shape(K, s) && s.loop;
+    return rowlane_shape(K, bits, s) && s.loop;
 }
 
 template <int BITS>
@@ -564,14 +569,18 @@ static hipError_t launch_rowlane_bits(const GemmArgs& a, const RowlaneShape& s, 
 #undef KMQ_RL_LOOP
         return hipGetLastError();
     }
-    switch (s.cpw) {
-        case 1: KMQ_RL_CPW(1, 8); break;
-        case 2: KMQ_RL_CPW(2, 8); break;
-        case 3: KMQ_RL_CPW(3, 6); break;
-        case 4: KMQ_RL_CPW(4, 4); break;
-        case 6: KMQ_RL_CPW(6, 4); break;
-        case 7: KMQ_RL_CPW(7, 4); break;
-        default: KMQ_RL_CPW(8, 4); break;
+    if (s.cpw == 1) { KMQ_RL_CPW(1, 8); }
+    else if (s.cpw == 2) { KMQ_RL_CPW(2, 8); }
+    else if constexpr (BITS == 1) {                 // (2-bit rows of more than two tiles per wave walk K in rounds)
+        switch (s.cpw) {
+            case 3: KMQ_RL_CPW(3, 6); break;
+            case 4: KMQ_RL_CPW(4, 4); break;
+            case 6: KMQ_RL_CPW(6, 4); break;
+            case 7: KMQ_RL_CPW(7, 4); break;
+            default: KMQ_RL_CPW(8, 4); break;
+        }
+    } else {
+        return hipErrorInvalidValue;
     }
 #undef KMQ_RL_CPW
 #undef KMQ_RL_LAUNCH
@@ -581,7 +590,7 @@ static hipError_t launch_rowlane_bits(const GemmArgs& a, const RowlaneShape& s, 
 // The fused gate / up / SwiGLU call: shapes with at most four tiles per wave (a wave then holds eight).
 bool rowlane_pair_has_kernel(int64_t K, int bits) {
     RowlaneShape s;
-    return rowlane_valid(bits, K) && rowlane_shape(K, s) && !s.loop && s.cpw <= 4;
+    return rowlane_valid(bits, K) && rowlane_shape(K, bits, s, true) && !s.loop && s.cpw <= 4;
 }
 
 template <int BITS>
@@ -601,7 +610,7 @@ static hipError_t launch_rowlane_pair_bits(const GemmArgs& a, const RowlaneShape
 
 hipError_t launch_rowlane_pair(const GemmArgs& a, hipStream_t st) {
     RowlaneShape s;
-    if (!rowlane_shape(a.K, s) || s.loop || s.cpw > 4 || !a.W2 || !a.codebook2) return hipErrorInvalidValue;
+    if (!rowlane_shape(a.K, a.bits, s, true) || s.loop || s.cpw > 4 || !a.W2 || !a.codebook2) return hipErrorInvalidValue;
     return a.bits == 1 ? launch_rowlane_pair_bits<1>(a, s, st) : launch_rowlane_pair_bits<2>(a, s, st);
 }
 
@@ -609,7 +618,7 @@ hipError_t launch_rowlane_pair(const GemmArgs& a, hipStream_t st) {
 // activation pairs and the sums set the limit); wider batches take one launch per four columns.
 hipError_t launch_rowlane(const GemmArgs& a, hipStream_t st) {
     RowlaneShape s;
-    if (!rowlane_shape(a.K, s)) return hipErrorInvalidValue;
+    if (!rowlane_shape(a.K, a.bits, s)) return hipErrorInvalidValue;
     for (int m0 = 0; m0 < a.M; m0 += 4) {
         GemmArgs b = a;
         b.M = a.M - m0 < 4 ? a.M - m0 : 4;

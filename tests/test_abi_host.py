@@ -252,7 +252,9 @@ def test_heuristic_names():
     assert kmq.kernel_name(9216, 3072, 1, 16, kmq.LAYOUT_ROWLANE) == "rowlane_b1"     # four launches of four columns
     assert kmq.kernel_name(64, 256 * 17, 2, 1, kmq.LAYOUT_ROWLANE) == "rowlane_loop_b2"      # 17 tiles: no even split over <= 16 waves
     assert kmq.kernel_name(64, 11008, 1, 3, kmq.LAYOUT_ROWLANE) == "rowlane_loop_b1" and kmq.kernel_name(64, 65536, 2, 1, kmq.LAYOUT_ROWLANE) == "rowlane_loop_b2"
-    assert kmq.kernel_name(64, 28672, 2, 1, kmq.LAYOUT_ROWLANE) == "rowlane_b2"              # 112 tiles = 7 x 16 waves
+    assert kmq.kernel_name(64, 28672, 1, 1, kmq.LAYOUT_ROWLANE) == "rowlane_b1"              # 112 tiles = 7 x 16 waves
+    assert kmq.kernel_name(64, 28672, 2, 1, kmq.LAYOUT_ROWLANE) == "rowlane_loop_b2"         # 2-bit rows beyond 32 tiles: rounds of two tiles
+    assert kmq.kernel_name(4096, 14336, 2, 1, kmq.LAYOUT_ROWLANE) == "rowlane_loop_b2" and kmq.kernel_name(4096, 8192, 2, 1, kmq.LAYOUT_ROWLANE) == "rowlane_b2"
     assert kmq.kernel_name(64, 4000, 2, 1, kmq.LAYOUT_ROWLANE) == "invalid"                  # the layout needs whole tiles
     assert kmq.kernel_name_swiglu(14336, 4096, 2, kmq.LAYOUT_ROWLANE) == "rowlane_pair_b2"
     assert kmq.kernel_name_swiglu(8192, 3072, 1, kmq.LAYOUT_ROWLANE) == "rowlane_pair_b1"
