@@ -14,8 +14,8 @@
 //     transposed through a wave-private LDS tile exactly as in the general kernel, and then stay in
 //     registers for all row blocks;
 //   * the grid is at most 256 workgroups (one per CU, 4 waves per SIMD with NWK = 16); workgroup b
-//     takes row blocks b, b + grid, b + 2 grid, ... (at most RPW); every index granule of all its row
-//     blocks is requested before the first one is decoded;
+//     takes the RPW adjacent row blocks b * RPW ..; every index granule of all its row blocks is
+//     requested before the first one is decoded;
 //   * the main loop is then nothing but decode (v_perm_b32 on the lane's codebook pools, as in the
 //     general kernel) and v_mfma_f32_16x16x32_bf16, with no memory or LDS instruction in it.
 // Partial 16x16 tiles of the waves are summed through LDS in a fixed order (deterministic).
@@ -80,7 +80,7 @@ constexpr int kKsliceMaxWaves = 16;
 #endif
 
 // BITS 2 or 3; SPW super-blocks per wave; RPW row blocks per workgroup at most.  blockDim.x = 64 * NWK with
-// NWK * SPW super-blocks = K; gridDim.x workgroups, workgroup b owns row blocks b + i * gridDim.x, i < RPW.
+// NWK * SPW super-blocks = K; workgroup b owns row blocks b * RPW + i, i < RPW.
 template <int BITS, int SPW, int RPW>
 __global__ __launch_bounds__(1024) void gemm_mfma_kslice_kernel(
     const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(1024) void gemm_mfma_kslice_kernel(
     int64_t rbs[RPW];
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
-        const int64_t rb = static_cast<int64_t>(blockIdx.x) + static_cast<int64_t>(r) * gridDim.x;
+        const int64_t rb = static_cast<int64_t>(blockIdx.x) * RPW + r;      // adjacent row blocks: a batch column's outputs of the workgroup are one run of RPW * 32 bytes
         if (rb < nrb) cnt = r + 1;
         rbs[r] = rb < nrb ? rb : nrb - 1;
     }
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(1024) void gemm_mfma_kslice_kernel(
         const int r = nl >> 4, nn = nl & 15;
         float s = 0.f;
         for (int k = 0; k < nwk; ++k) s += reinterpret_cast<const float*>(&sm.xstage[k][0])[(r * 16 + m) * 17 + nn];
-        const int64_t row = (static_cast<int64_t>(blockIdx.x) + static_cast<int64_t>(r) * gridDim.x) * 16 + nn;
+        const int64_t row = (static_cast<int64_t>(blockIdx.x) * RPW + r) * 16 + nn;
         if (r < cnt && m < M && row < N) Y[static_cast<int64_t>(m) * N + row] = f32_to_bf16(s);
     }
 }
