@@ -219,6 +219,11 @@ struct KsliceShape { int nwk, spw, rpw, grid; };
 // workgroup per CU at most, each with ceil(row blocks / grid) <= 4 row blocks.
 static bool kslice_shape(int64_t N, int64_t K, int bits, KsliceShape& s) {
     if (bits != 2 && bits != 3) return false;
+    // rows of 3072 and 4096 columns: 12 to 16 waves with eight matrix steps each.  Shorter rows leave a wave too
+    // little work per row block next to its share of the 16-way reduction (batch 8, 14336 rows, K = 2048:
+    // 5.9 us here against 5.2 us in the general kernel at 2 bits, 6.4 against 5.9 at 3 bits; K = 3072: 7.3 against
+    // 7.8 and 7.7 against 8.4).
+    if (K < 3072) return false;
     const int64_t sbe = tiled_superblock_elems(bits);
     if (K % sbe != 0) return false;
     const int64_t nsb = K / sbe;
@@ -226,7 +231,7 @@ static bool kslice_shape(int64_t N, int64_t K, int bits, KsliceShape& s) {
     int nwk = 0, spw = 0;
     for (int w = kKsliceMaxWaves; w >= 1; --w)
         if (nsb % w == 0 && nsb / w <= max_spw) { nwk = w; spw = static_cast<int>(nsb / w); break; }
-    if (!nwk) return false;
+    if (!nwk || spw != max_spw) return false;               // (eight steps per wave: the only instances built)
     const int64_t nrb = (N + 15) / 16;
     const int64_t grid = nrb < 256 ? nrb : 256;
     const int64_t rpw = (nrb + grid - 1) / grid;
@@ -260,9 +265,9 @@ static void launch_kslice_rpw(const GemmArgs& a, const KsliceShape& s, hipStream
 hipError_t launch_mfma_kslice(const GemmArgs& a, hipStream_t st) {
     KsliceShape s;
     if (!kslice_shape(a.N, a.K, a.bits, s) || a.scales) return hipErrorInvalidValue;
-    if (a.bits == 2) launch_kslice_rpw<2, 1>(a, s, st);
-    else if (s.spw == 1) launch_kslice_rpw<3, 1>(a, s, st);
-    else launch_kslice_rpw<3, 2>(a, s, st);
+    if (a.bits == 2 && s.spw == 1) launch_kslice_rpw<2, 1>(a, s, st);
+    else if (a.bits == 3 && s.spw == 2) launch_kslice_rpw<3, 2>(a, s, st);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 

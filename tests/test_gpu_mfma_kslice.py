@@ -29,7 +29,7 @@ def _case(seed, N, K, bits, M):
 
 # rows: 6144 (384 row blocks: 2 per workgroup, 192 workgroups), 8190 (ragged, 2 x 256), 9216 (3 x 192),
 # 12281 (ragged, 3 x 256), 14336 (4 x 224), 16377 (ragged, 4 x 256)
-@pytest.mark.parametrize("bits,K", [(2, 2048), (2, 4096), (3, 1024), (3, 2048), (3, 3072), (3, 4096)])
+@pytest.mark.parametrize("bits,K", [(2, 3072), (2, 3584), (2, 4096), (3, 3072), (3, 3584), (3, 4096)])
 @pytest.mark.parametrize("N,M", [(6144, 8), (8190, 16), (9216, 1), (12281, 5), (14336, 16), (16377, 8)])
 def test_kslice_vs_oracle(gpu, bits, K, N, M):
     idx, cb, X = _case(17 * bits + N + K + M, N, K, bits, M)
@@ -46,6 +46,7 @@ def test_kslice_is_chosen_only_where_it_pays(gpu):
     assert kmq.kernel_name(4096, 4096, 3, 8, T) == "mfma_b3"             # one row block per workgroup: the general kernel
     assert kmq.kernel_name(4800, 4096, 3, 8, T) == "mfma_b3"             # 300 row blocks: 150 workgroups would idle 106 CUs
     assert kmq.kernel_name(14336, 8192, 3, 8, T) == "mfma_b3"            # a wave's slice of X would not fit in registers
+    assert kmq.kernel_name(14336, 2048, 3, 8, T) == "mfma_b3" and kmq.kernel_name(14336, 2048, 2, 8, T) == "mfma_b2"   # too little work per wave
     assert kmq.kernel_name(14336, 4096, 1, 8, T) == "mfma_b1" and kmq.kernel_name(14336, 4096, 4, 8, T) == "mfma_b4"
     assert kmq.kernel_name(70000, 4096, 3, 8, T) == "mfma_b3"            # more than four row blocks per workgroup
     assert kmq.kernel_name(14336, 4096, 2, 16, T) == "mfma_kslice_b2"
