@@ -838,8 +838,18 @@ def main():
                          "us_per_call": round(s / n * 1e6, 3),
                          "pct_peak": round(100 * it.bytes / (s / n) / 1e9 / HBM_PEAK_GBS, 2),
                          "max_err_over_A": float(f"{w:.3e}")})
+            M_, lay_ = it.M, it.layout
             del it
             torch.cuda.empty_cache()
+            if 2 <= M_ < 8 and lay_ != 1:
+                # batches below 8 run on the vector units by the contract's rule; the matrix-core kernel on the
+                # tiled layout next to it, for comparison
+                it = Instances(name, layout=1)
+                it.check()
+                s, n = time_workload(it, 2000, 100)
+                rows[-1]["tiled_matrix_core"] = {"kernel": it.kernel, "us_per_call": round(s / n * 1e6, 3)}
+                del it
+                torch.cuda.empty_cache()
         out["config"]["contract_shapes"] = rows
         if not args.sweep:
             sw = run_sweep(1, 50)
