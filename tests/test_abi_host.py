@@ -326,3 +326,15 @@ def test_batches_on_the_canonical_layout_take_the_table_kernels():
     assert kmq.kernel_name(100, 515, 2, 2) == "generic"                     # no table kernel for this K
     assert kmq.kernel_name_blockscaled(8192, 8192, 4, 4).startswith("lut_sc_b4")
     assert kmq.kernel_name_blockscaled(8192, 8192, 4, 16).startswith("lut_sc_b4")
+
+
+def test_matrix_core_kernel_choice():
+    """The kernel whose waves keep their slice of the activations in registers is taken only where it was measured faster."""
+    T = kmq.LAYOUT_TILED
+    assert kmq.kernel_name(4096, 4096, 3, 8, T) == "mfma_b3"             # one row block per workgroup: the general kernel
+    assert kmq.kernel_name(4800, 4096, 3, 8, T) == "mfma_b3"             # 300 row blocks: 150 workgroups would idle 106 CUs
+    assert kmq.kernel_name(14336, 8192, 3, 8, T) == "mfma_b3"            # a wave's slice of X would not fit in registers
+    assert kmq.kernel_name(14336, 2048, 3, 8, T) == "mfma_b3" and kmq.kernel_name(14336, 2048, 2, 8, T) == "mfma_b2"   # too little work per wave
+    assert kmq.kernel_name(14336, 4096, 1, 8, T) == "mfma_b1" and kmq.kernel_name(14336, 4096, 4, 8, T) == "mfma_b4"
+    assert kmq.kernel_name(70000, 4096, 3, 8, T) == "mfma_b3"            # more than four row blocks per workgroup
+    assert kmq.kernel_name(14336, 4096, 2, 16, T) == "mfma_kslice_b2"

@@ -41,17 +41,6 @@ def test_kslice_vs_oracle(gpu, bits, K, N, M):
     gpu.check_against_oracle(Yg, oracle.pack(idx, bits), cb, X, K, bits, ranges, label=f"kslice b{bits} {N}x{K} M{M}")
 
 
-def test_kslice_is_chosen_only_where_it_pays(gpu):
-    T = kmq.LAYOUT_TILED
-    assert kmq.kernel_name(4096, 4096, 3, 8, T) == "mfma_b3"             # one row block per workgroup: the general kernel
-    assert kmq.kernel_name(4800, 4096, 3, 8, T) == "mfma_b3"             # 300 row blocks: 150 workgroups would idle 106 CUs
-    assert kmq.kernel_name(14336, 8192, 3, 8, T) == "mfma_b3"            # a wave's slice of X would not fit in registers
-    assert kmq.kernel_name(14336, 2048, 3, 8, T) == "mfma_b3" and kmq.kernel_name(14336, 2048, 2, 8, T) == "mfma_b2"   # too little work per wave
-    assert kmq.kernel_name(14336, 4096, 1, 8, T) == "mfma_b1" and kmq.kernel_name(14336, 4096, 4, 8, T) == "mfma_b4"
-    assert kmq.kernel_name(70000, 4096, 3, 8, T) == "mfma_b3"            # more than four row blocks per workgroup
-    assert kmq.kernel_name(14336, 4096, 2, 16, T) == "mfma_kslice_b2"
-
-
 @pytest.mark.parametrize("bits", (2, 3))
 def test_kslice_one_hot_batch16_probe_is_bit_exact(gpu, bits):
     """x = e_k in every batch column: a sum with one non-zero term, so Y[m][n] is the dequantised weight."""
