@@ -128,3 +128,67 @@ def test_graph_replays_of_the_multi_kernel_and_fused_calls(gpu):
         torch.cuda.synchronize()
         for i, (y, w) in enumerate(zip(captured, want)):
             assert torch.equal(y, w), f"replay {replay}, output {i}"
+
+
+def test_graph_replays_of_the_rowlane_and_kslice_calls(gpu):
+    """The lane-per-row kernels (batch 1, a batch of seven = two launches, the round loop, the fused pair), the
+    matrix-core kernel with register-resident activations and the call that allocates nothing, captured
+    together; every replay against the eager result."""
+    from paper_2602_15563_amd import kmq
+    dev = gpu.dev
+    RL, T = kmq.LAYOUT_ROWLANE, kmq.LAYOUT_TILED
+    g = np.random.default_rng(77)
+
+    def case(N, K, bits, M):
+        idx = g.integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
+        cb = synth.f32_to_bf16(g.normal(0, 0.02, size=(N, 1 << bits)).astype(np.float32))
+        X = synth.f32_to_bf16(g.standard_normal(size=(M, K)).astype(np.float32))
+        return kmq.pack(idx, bits), cb, X
+
+    p1, c1, x1 = case(330, 4096, 2, 1)                 # rowlane_b2
+    p2, c2, x2 = case(100, 3072, 1, 7)                 # rowlane_b1, 4 + 3 columns
+    p3, c3, x3 = case(50, 256 * 19, 2, 2)              # rowlane_loop_b2
+    p4, c4, x4 = case(64, 2048, 2, 1)                  # rowlane_pair_b2 (gate = up weights differ below)
+    p4u, c4u, _ = case(64, 2048, 2, 1)
+    p5, c5, x5 = case(6144 + 3, 3072, 3, 8)            # mfma_kslice_b3
+    p6, c6, x6 = case(40, 32768, 2, 2)                 # split over K: the static scratch of the no-allocation call
+    assert kmq.kernel_name(6147, 3072, 3, 8, T) == "mfma_kslice_b3" and kmq.kernel_name(40, 32768, 2, 2) == "generic_splitk"
+    W1, W2, W3 = dev(kmq.repack(p1, 4096, 2, RL)), dev(kmq.repack(p2, 3072, 1, RL)), dev(kmq.repack(p3, 256 * 19, 2, RL))
+    W4, W4u = dev(kmq.repack(p4, 2048, 2, RL)), dev(kmq.repack(p4u, 2048, 2, RL))
+    W5, W6 = dev(kmq.repack(p5, 3072, 3, T)), dev(p6)
+    C = [dev(c) for c in (c1, c2, c3, c4, c4u, c5, c6)]
+    Xd = [dev(x) for x in (x1, x2, x3, x4, x5, x6)]
+
+    def outputs():
+        shapes = ((1, 330), (7, 100), (2, 50), (1, 64), (8, 6147), (2, 40))
+        return [torch.full(s, 0x7FC1, dtype=torch.int16, device="cuda") for s in shapes]
+
+    def run(Y):
+        kmq.gemv(W1, C[0], Xd[0], Y[0], 330, 4096, 2, RL)
+        kmq.gemm_smallbatch(W2, C[1], Xd[1], Y[1], 100, 3072, 7, 1, RL)
+        kmq.gemm_smallbatch(W3, C[2], Xd[2], Y[2], 50, 256 * 19, 2, 2, RL)
+        kmq.gemv_swiglu(W4, C[3], W4u, C[4], Xd[3], Y[3], 64, 2048, 2, RL)
+        kmq.gemm_smallbatch(W5, C[5], Xd[4], Y[4], 6147, 3072, 8, 3, T)
+        kmq.gemm_smallbatch_noalloc(W6, C[6], Xd[5], Y[5], 40, 32768, 2, 2, 0)
+
+    eager = outputs()
+    run(eager)
+    torch.cuda.synchronize()
+    want = [y.clone() for y in eager]
+    captured = outputs()
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        run(captured)
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            run(captured)
+    for replay in range(4):
+        for y in captured:
+            y.fill_(0x7FC1)
+        run(eager)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (y, w) in enumerate(zip(captured, want)):
+            assert torch.equal(y, w), f"replay {replay}, call {i}"
