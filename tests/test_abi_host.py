@@ -338,3 +338,13 @@ def test_matrix_core_kernel_choice():
     assert kmq.kernel_name(14336, 4096, 1, 8, T) == "mfma_b1" and kmq.kernel_name(14336, 4096, 4, 8, T) == "mfma_b4"
     assert kmq.kernel_name(70000, 4096, 3, 8, T) == "mfma_b3"            # more than four row blocks per workgroup
     assert kmq.kernel_name(14336, 4096, 2, 16, T) == "mfma_kslice_b2"
+
+
+def test_the_built_library_is_not_an_instrumented_build():
+    """Launch-shape overrides read from the environment exist only in builds with -DKMQ_TUNING (used for sweeps);
+    the library in the tree must be an ordinary build, which never looks at the environment."""
+    import os
+    path = os.path.join(os.path.dirname(kmq.__file__), "libkmq.so")
+    blob = open(path, "rb").read()
+    for name in (b"KMQ_LUT_PICK", b"KMQ_RL_CPW", b"KMQ_RL_DBG", b"KMQ_MFMA_NWK", b"KMQ_MFMA_NO_KSLICE", b"kmq_debug_rowlane_timestamps"):
+        assert name not in blob, name.decode()
