@@ -61,13 +61,20 @@ Plan make_plan(int64_t N, int64_t K, int bits, int M, int layout, bool scaled) {
         if (mfma_kslice_has_kernel(N, K, bits)) return Plan{kVariantMfma, -1, 0, bits == 2 ? "mfma_kslice_b2" : "mfma_kslice_b3"};
         return Plan{kVariantMfma, -1, 0, names[bits - 1]};
     }
-    if (M == 1 || per_column_faster(M)) {
+    bool use_loop = true, use_table = true;
+#ifdef KMQ_TUNING
+    static const char* const loop_env = std::getenv("KMQ_LOOP");      // sweeps only: 0 = never, 2 = instead of the specialised kernels
+    if (loop_env) { use_loop = loop_env[0] != '0'; use_table = loop_env[0] != '2'; }
+#endif
+    if (use_table && (M == 1 || per_column_faster(M))) {
         const int l = lut_find(N, K, bits, layout);
         if (l >= 0) return Plan{M == 1 ? kVariantLut : kVariantPerColumn, l, 0, lut_name(l)};
     }
     const int slices = generic_splitk_slices(N, K, layout);
     if (slices > 1)
         return Plan{kVariantGeneric, slices, static_cast<size_t>(slices) * M * N * sizeof(float), "generic_splitk"};
+    if (use_loop && (M == 1 || per_column_faster(M)) && lut_loop_has_kernel(N, K, bits, layout))
+        return Plan{kVariantLutLoop, -1, 0, lut_loop_name(bits)};
     return Plan{kVariantGeneric, -1, 0, "generic"};
 }
 
@@ -117,6 +124,7 @@ static kmq_status check_and_run(const GemmArgs& a_in, void* stream, bool library
         case kVariantPerColumn:                               // one launch, a workgroup per (row group, column)
             e = launch_lut_entry(plan.table_index, a, s);   // K is a multiple of 8 for every table kernel: rows of X stay 16-byte aligned
             break;
+        case kVariantLutLoop: e = launch_lut_loop(a, s); break;
         case kVariantBlockGeneric: e = launch_blockscaled_generic(a, s); break;
         default: e = launch_generic(a, s); break;
     }

@@ -160,6 +160,8 @@ __global__ __launch_bounds__(1024) void gemm_mfma_kslice_kernel(
             load_granule<GW>(W + (rbs[r] * nsb + sb0 + s) * gstride + lane * GW, gran[r][s]);
 #endif
 
+    __builtin_amdgcn_sched_barrier(0);                      // every load is requested before anything waits for one
+
     // ---- B operands: through the wave's LDS tile, piece (q + 4i) of batch row n for step i of the chunk ----
     u32x4_t* xtile = &sm.xstage[wk][0];
 #pragma unroll
@@ -176,19 +178,19 @@ __global__ __launch_bounds__(1024) void gemm_mfma_kslice_kernel(
     for (int r = 0; r < RPW; ++r) acc[r] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
-        if (r < cnt) {                                       // workgroup-uniform
+        // no `r < cnt` test here: only the last workgroup has clamped copies to skip, and a load whose only use
+        // sits behind a branch is sunk into it by the compiler, i.e. requested a whole memory latency late
 #pragma unroll
-            for (int s = 0; s < SPW; ++s)
+        for (int s = 0; s < SPW; ++s)
 #pragma unroll
-                for (int j = 0; j < GPG; ++j) {
+            for (int j = 0; j < GPG; ++j) {
 #if KMQ_KS_DBG == 2
-                    if (j > 0) { acc[r][0] += __uint_as_float(gran[r][s][j % GW] & 0x3FFFFFFFu); continue; }
+                if (j > 0) { acc[r][0] += __uint_as_float(gran[r][s][j % GW] & 0x3FFFFFFFu); continue; }
 #endif
-                    const u32x4_t a = decode_step<BITS>(gran[r][s], j, lo0[r], lo1[r], hi0[r], hi1[r]);
-                    acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                                    __builtin_bit_cast(bf16x8_t, bfrag[s * GPG + j]), acc[r], 0, 0, 0);
-                }
-        }
+                const u32x4_t a = decode_step<BITS>(gran[r][s], j, lo0[r], lo1[r], hi0[r], hi1[r]);
+                acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                                __builtin_bit_cast(bf16x8_t, bfrag[s * GPG + j]), acc[r], 0, 0, 0);
+            }
     }
 
     // ---- K-reduction across the waves, fixed order: lane holds D[row 4q + i][batch column n] ----
@@ -220,9 +222,8 @@ struct KsliceShape { int nwk, spw, rpw, grid; };
 static bool kslice_shape(int64_t N, int64_t K, int bits, KsliceShape& s) {
     if (bits != 2 && bits != 3) return false;
     // rows of 3072 and 4096 columns: 12 to 16 waves with eight matrix steps each.  Shorter rows leave a wave too
-    // little work per row block next to its share of the 16-way reduction (batch 8, 14336 rows, K = 2048:
-    // 5.9 us here against 5.2 us in the general kernel at 2 bits, 6.4 against 5.9 at 3 bits; K = 3072: 7.3 against
-    // 7.8 and 7.7 against 8.4).
+    // little work per row block next to its share of the 16-way reduction (batch 8, 14336 rows, K = 2048,
+    // 2 bits: 5.4 us here against 5.25 us in the general kernel; at K = 3072 this kernel is ahead at 2 and 3 bits).
     if (K < 3072) return false;
     const int64_t sbe = tiled_superblock_elems(bits);
     if (K % sbe != 0) return false;
@@ -235,11 +236,11 @@ static bool kslice_shape(int64_t N, int64_t K, int bits, KsliceShape& s) {
     const int64_t nrb = (N + 15) / 16;
     const int64_t grid = nrb < 256 ? nrb : 256;
     const int64_t rpw = (nrb + grid - 1) / grid;
-    // one row block per workgroup is the general kernel's ground (3-bit 4096 x 4096, batch 8: 4.5 us there, 4.9 us here:
+    // one row block per workgroup is the general kernel's ground (3-bit 4096 x 4096, batch 8: 4.55 us there, 4.76 us here:
     // sixteen waves for eight matrix steps each); a grid that leaves a quarter of the CUs idle is not worth it either
     if (rpw < 2 || rpw > 4 || (nrb + rpw - 1) / rpw < 192) return false;
-    // no more workgroups than rpw row blocks each need: 14336 rows are 224 workgroups of four row blocks (8.9 us at
-    // batch 8 / 16 of the 3-bit 14336 x 4096 shape) rather than 256 of three or four (9.4 us) -- every workgroup
+    // no more workgroups than rpw row blocks each need: 14336 rows are 224 workgroups of four row blocks rather than 256 of
+    // three or four (5 % slower at batch 8 and 16 of the 3-bit 14336 x 4096 shape) -- every workgroup
     // fetches all of X
     s = {nwk, spw, static_cast<int>(rpw), static_cast<int>((nrb + rpw - 1) / rpw)};
     return true;

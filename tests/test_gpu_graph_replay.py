@@ -132,8 +132,8 @@ def test_graph_replays_of_the_multi_kernel_and_fused_calls(gpu):
 
 def test_graph_replays_of_the_rowlane_and_kslice_calls(gpu):
     """The lane-per-row kernels (batch 1, a batch of seven = two launches, the round loop, the fused pair), the
-    matrix-core kernel with register-resident activations and the call that allocates nothing, captured
-    together; every replay against the eager result."""
+    matrix-core kernel with register-resident activations, the call that allocates nothing and the canonical
+    layout's kernel that walks K in rounds, captured together; every replay against the eager result."""
     from paper_2602_15563_amd import kmq
     dev = gpu.dev
     RL, T = kmq.LAYOUT_ROWLANE, kmq.LAYOUT_TILED
@@ -152,15 +152,17 @@ def test_graph_replays_of_the_rowlane_and_kslice_calls(gpu):
     p4u, c4u, _ = case(64, 2048, 2, 1)
     p5, c5, x5 = case(6144 + 3, 3072, 3, 8)            # mfma_kslice_b3
     p6, c6, x6 = case(40, 32768, 2, 2)                 # split over K: the static scratch of the no-allocation call
+    p7, c7, x7 = case(1001, 2848, 3, 3)                # lut_loop_b3: rounds over K, a row that ends inside a round, batch as grid rows
     assert kmq.kernel_name(6147, 3072, 3, 8, T) == "mfma_kslice_b3" and kmq.kernel_name(40, 32768, 2, 2) == "generic_splitk"
+    assert kmq.kernel_name(1001, 2848, 3, 3) == "lut_loop_b3"
     W1, W2, W3 = dev(kmq.repack(p1, 4096, 2, RL)), dev(kmq.repack(p2, 3072, 1, RL)), dev(kmq.repack(p3, 256 * 19, 2, RL))
     W4, W4u = dev(kmq.repack(p4, 2048, 2, RL)), dev(kmq.repack(p4u, 2048, 2, RL))
-    W5, W6 = dev(kmq.repack(p5, 3072, 3, T)), dev(p6)
-    C = [dev(c) for c in (c1, c2, c3, c4, c4u, c5, c6)]
-    Xd = [dev(x) for x in (x1, x2, x3, x4, x5, x6)]
+    W5, W6, W7 = dev(kmq.repack(p5, 3072, 3, T)), dev(p6), dev(p7)
+    C = [dev(c) for c in (c1, c2, c3, c4, c4u, c5, c6, c7)]
+    Xd = [dev(x) for x in (x1, x2, x3, x4, x5, x6, x7)]
 
     def outputs():
-        shapes = ((1, 330), (7, 100), (2, 50), (1, 64), (8, 6147), (2, 40))
+        shapes = ((1, 330), (7, 100), (2, 50), (1, 64), (8, 6147), (2, 40), (3, 1001))
         return [torch.full(s, 0x7FC1, dtype=torch.int16, device="cuda") for s in shapes]
 
     def run(Y):
@@ -170,6 +172,7 @@ def test_graph_replays_of_the_rowlane_and_kslice_calls(gpu):
         kmq.gemv_swiglu(W4, C[3], W4u, C[4], Xd[3], Y[3], 64, 2048, 2, RL)
         kmq.gemm_smallbatch(W5, C[5], Xd[4], Y[4], 6147, 3072, 8, 3, T)
         kmq.gemm_smallbatch_noalloc(W6, C[6], Xd[5], Y[5], 40, 32768, 2, 2, 0)
+        kmq.gemm_smallbatch(W7, C[7], Xd[6], Y[6], 1001, 2848, 3, 3, 0)
 
     eager = outputs()
     run(eager)
