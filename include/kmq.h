@@ -154,8 +154,8 @@ size_t kmq_workspace_bytes(int64_t N, int64_t K, int bits, int M, int layout);
  * Equivalent to kmq_gemm_smallbatch with M = 1.
  * Kernels on the canonical layout (kmq_kernel_name tells which one a shape gets): bits 1..4 with K one of
  * the row lengths the library has a fully unrolled table kernel for ("lut_b..."), any other K % 32 == 0 up
- * to 16384 through the table kernel that walks a row in rounds ("lut_loop_b..."), everything else (K not a
- * multiple of 32 or beyond 16384, bits = 8) through the shape-agnostic kernel ("generic", "generic_splitk"). */
+ * to 24576 through the table kernel that walks a row in rounds ("lut_loop_b..."), everything else (K not a
+ * multiple of 32 or beyond 24576, bits = 8) through the shape-agnostic kernel ("generic", "generic_splitk"). */
 kmq_status kmq_gemv(const uint32_t* W, const uint16_t* codebook, const uint16_t* x, uint16_t* y,
                     int64_t N, int64_t K, int bits, int layout,
                     void* workspace, size_t workspace_bytes, void* hip_stream);

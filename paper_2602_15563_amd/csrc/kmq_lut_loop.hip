@@ -29,7 +29,8 @@ namespace kmq {
 
 namespace {
 
-constexpr int kLoopMaxK = 16384;          // the staged copy of x: 40 KB of LDS with its padding
+constexpr int kLoopMaxK = 24576;          // the staged copy of x: 60 KB of LDS with its padding (the launcher keeps tables + x within 64 KB)
+constexpr int kLoopUnrolledK = 16384;     // x up to here is staged with loads that are all in flight at once
 constexpr int kLoopThreads = 512;
 
 template <int BITS, int LPR, int NWK, int RS, int PF, int WPE>
@@ -50,7 +51,7 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
     constexpr int LUT_PASSES = (LUT_TOTAL + kLoopThreads - 1) / kLoopThreads;
     constexpr int TBL = RS * ENT < 64 ? 64 : RS * ENT;              // dwords per (wave across, row of the load): bases stay 256-byte aligned
     constexpr int XSTR = 5;                        // a lane slice of four 16-byte chunks takes five: reads spread over the banks
-    constexpr int XPT = kLoopMaxK / 8 / kLoopThreads;               // 16-byte chunks of x staged per thread (4)
+    constexpr int XPT = kLoopUnrolledK / 8 / kLoopThreads;          // 16-byte chunks of x staged per thread (4); longer rows: a loop for the rest
 
     struct alignas(256) Smem {
         uint32_t lut[NWR][RPL][TBL];               // per wave across and row of the load: RS tables (1-bit: lut[0][0] holds the mask table)
@@ -158,6 +159,14 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
 #pragma unroll
                 for (int j = 0; j < 4; ++j) sxl = dot2_bf16(0x3F803F80u, xt[i][j], sxl);
             }
+        }
+    }
+    for (int c = threadIdx.x + XPT * kLoopThreads; c < nch; c += kLoopThreads) {      // rows beyond 16384 elements
+        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(x + c * 8);
+        xs[(c >> 2) * XSTR + (c & 3)] = v;
+        if constexpr (BITS == 1) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sxl = dot2_bf16(0x3F803F80u, v[j], sxl);
         }
     }
     if (threadIdx.x < XSTR) xs[xslices * XSTR + threadIdx.x] = u32x4_t{0u, 0u, 0u, 0u};
@@ -375,6 +384,10 @@ LoopShape loop_shape(int64_t N, int64_t K, int bits) {
         const int64_t R = (K / 32 + lpr - 1) / lpr;
         for (int nwk = 1; nwk <= 8; nwk *= 2) {
             const int64_t rows_wg = 8 / nwk * (64 / lpr) * kRS;
+            // static LDS: the tables (256-byte aligned slots per wave across and row of the load) and the partial sums
+            const int64_t ent = bits == 3 ? 64 : 16, slot = kRS * ent < 64 ? 256 : kRS * ent * 4;
+            const int64_t static_bytes = (bits == 1 ? 256 : 8 / nwk * (64 / lpr) * slot) + 8 * rows_wg * 4 + 512;
+            if (static_bytes + static_cast<int64_t>(best.x_bytes) > 65536) continue;
             const int64_t wgs = (N + rows_wg - 1) / rows_wg;
             const int64_t per_cu_x100 = wgs * 100 / 256 < 100 ? 100 : wgs * 100 / 256;
             const int64_t rw = (R + nwk - 1) / nwk;

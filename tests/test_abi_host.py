@@ -243,12 +243,12 @@ def test_heuristic_names():
     assert kmq.kernel_name(2048, 2048, 1, 1).startswith("lut_b1")
     assert kmq.kernel_name(4096, 4096, 3, 1).startswith("lut_b3")
     assert kmq.kernel_name(4096, 1024, 3, 1) == "lut_loop_b3" and kmq.kernel_name(4096, 1000, 3, 1) == "generic"
-    # no row length that is a multiple of 32 (up to 16384) falls to the shape-agnostic kernel on the canonical layout
+    # no row length that is a multiple of 32 (up to 24576) falls to the shape-agnostic kernel on the canonical layout
     for bits in (1, 2, 3, 4):
-        for K in range(32, 16384 + 1, 32):
+        for K in range(32, 24576 + 1, 32):
             name = kmq.kernel_name(4096, K, bits, 1)
             assert name.startswith("lut_b") or name == f"lut_loop_b{bits}", (bits, K, name)
-    assert kmq.kernel_name(4096, 3072, 4, 1).startswith("lut_b4") and kmq.kernel_name(4096, 16384 + 256, 4, 1) == "generic"
+    assert kmq.kernel_name(4096, 3072, 4, 1).startswith("lut_b4") and kmq.kernel_name(4096, 24576 + 32, 4, 1) == "generic"
     assert kmq.kernel_name(4096, 11008, 4, 7) == "lut_loop_b4"                                # batches: grid rows
     assert kmq.kernel_name(77, 515, 2, 1) == "generic"
     assert kmq.kernel_name(4096, 4096, 3, 16, kmq.LAYOUT_TILED) == "mfma_b3"

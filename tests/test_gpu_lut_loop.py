@@ -1,4 +1,4 @@
-"""GPU parity of the table kernel that walks a row in rounds (canonical layout, any K % 32 == 0 up to 16384
+"""GPU parity of the table kernel that walks a row in rounds (canonical layout, any K % 32 == 0 up to 24576
 that has no kernel specialised on it): through the C ABI against the CPU oracle -- every bit-width, every
 number of lanes per row and split of K over the waves of a workgroup, rows that end inside a round, row counts
 that end inside a workgroup, ranges of rounds that end in padded rounds, batches as grid rows, one-hot probes
@@ -29,13 +29,14 @@ def _case(seed, N, K, bits, M):
 
 
 # K: a single slice (32), less than one round (96, 256), rows that end inside a round (1056 = 33 slices, 4000,
-# 11008, 12320), round counts the waves along K do not divide (2560, 5120, 7168), the longest row (16384)
+# 11008, 12320), round counts the waves along K do not divide (2560, 5120, 7168), the longest rows (16384; 21504 and
+# 24576, whose x is staged in two steps)
 # N: 1 and 7 rows (one partly filled wave), 250 (ragged), 1000 / 4099 (several waves along K), 20000 / 40001
 # (one wave along K)
 @pytest.mark.parametrize("bits", (1, 2, 3, 4))
 @pytest.mark.parametrize("N,K", [(1, 256), (7, 768), (250, 1280), (1000, 2560), (4099, 2816), (4096, 5120), (2048, 7168),
                                  (20000, 512), (40001, 1024), (4099, 11008), (513, 16384), (9000, 3584),
-                                 (300, 32), (5000, 96), (1000, 1056), (4097, 4000), (2000, 12320)])
+                                 (300, 32), (5000, 96), (1000, 1056), (4097, 4000), (2000, 12320), (1000, 21504), (600, 24576)])
 def test_loop_kernel_vs_oracle(gpu, bits, N, K):
     if kmq.kernel_name(N, K, bits, 1, kmq.LAYOUT_CANONICAL) != f"lut_loop_b{bits}":
         pytest.skip("this (bits, K) has a kernel specialised on K")
