@@ -50,6 +50,10 @@ WORKLOADS = {
     "cfg4_qkv_b1_9216x3072_m4": (1, 9216, 3072, 4, 4, 0, True),
     "cfg4_qkv_b1_9216x3072_m16": (1, 9216, 3072, 16, 4, 0, True),
     "cfg4_down_b1_3072x8192_m16": (1, 3072, 8192, 16, 4, 4, True),
+    # down projection of the largest architecture of App. A's table (d = 6144, SwiGLU width 1.3 * 8d/3 rounded to a
+    # multiple of 1024 = 21504) at 3 and 4 bits: a row length without a specialised kernel (not a contract row)
+    "arch_d6144_down_b3_6144x21504_m1": (3, 6144, 21504, 1, 8, 0, False),
+    "arch_d6144_down_b4_6144x21504_m1": (4, 6144, 21504, 1, 8, 1, False),
     # the paper's own format and micro-benchmark shape (App. E, table of m = 1, h = 8192):
     # tensor-wide codebook, one bf16 scale per 64 elements; 8th field = block-scaled
     "paper_b4s_8192x8192_m1": (4, 8192, 8192, 1, 5, 0, False, True),
