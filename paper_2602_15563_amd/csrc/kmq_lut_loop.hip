@@ -1,4 +1,4 @@
-// Batch-1 table kernel for rows of any length that is a multiple of 32 (up to 16384), canonical layout:
+// Batch-1 table kernel for rows of any length that is a multiple of 32 (up to 24576), canonical layout:
 // y = W x with w = codebook lookup (paper App. E, "Kernel implementations"; the hidden sizes of the
 // paper's models, App. A table of architectural hyperparameters, are only some of the lengths a caller
 // may bring).  The kernels specialised on K unroll a row completely; this one walks it in rounds.
@@ -17,7 +17,7 @@
 // last words and whose activations come from a slice of zeros.  The lookup tables of a workgroup's
 // rows are built once, by all of its waves together, and shared by the waves along K.
 //
-// K-reduction: DPP adds over the eight lanes of a row, then across the NWK waves through LDS in fixed
+// K-reduction: DPP adds over the lanes of a row, then across the NWK waves through LDS in fixed
 // order; fp32 -> bf16 round-to-nearest-even; one coalesced store per workgroup.
 #include <cstdlib>
 
