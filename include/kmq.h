@@ -264,7 +264,9 @@ kmq_status kmq_gemv_swiglu_rmsnorm(const uint32_t* Wgate, const uint16_t* codebo
                                    const uint32_t* Wup, const uint16_t* codebook_up,
                                    const uint16_t* x, const uint16_t* norm_weight, float eps, uint16_t* y,
                                    int64_t N, int64_t K, int bits, int layout, void* hip_stream);
-/* Kernel the two calls above use (pair != 0: the SwiGLU form); static string, "invalid" on bad arguments. */
+/* Kernel the two calls above use (pair != 0: the SwiGLU form); static string, "invalid" on bad arguments.
+ * "fused_generic" names the shape-agnostic path; kmq_gemv_fused with rmsnorm = 0 takes the kernel kmq_kernel_name
+ * reports instead where that is a table kernel (the residual is added in its epilogue). */
 const char* kmq_kernel_name_fused(int64_t N, int64_t K, int bits, int layout, int pair);
 
 /* Dense bf16 GEMV, y = W x with W N x K bf16 bit patterns, row-major: the unquantised

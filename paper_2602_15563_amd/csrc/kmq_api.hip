@@ -210,7 +210,10 @@ kmq_status kmq_gemv_fused(const uint32_t* W, const uint16_t* codebook, const uin
     a.residual = residual;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const int l = kmq::lut_find(N, K, bits, layout, false);
-    const hipError_t e = (l >= 0 && kmq::lut_has_fusions(l)) ? kmq::launch_lut_entry(l, a, s) : kmq::launch_fused_generic(a, s);
+    hipError_t e;
+    if (l >= 0 && kmq::lut_has_fusions(l)) e = kmq::launch_lut_entry(l, a, s);
+    else if (!rmsnorm && kmq::lut_loop_has_kernel(N, K, bits, layout)) e = kmq::launch_lut_loop(a, s);   // residual behind: the K-loop table kernel
+    else e = kmq::launch_fused_generic(a, s);
     return kmq::hip_status(e);
 }
 

@@ -36,7 +36,8 @@ constexpr int kLoopThreads = 512;
 template <int BITS, int LPR, int NWK, int RS, int PF, int WPE>
 __global__ __launch_bounds__(kLoopThreads) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
-                          const uint16_t* __restrict__ X, uint16_t* __restrict__ Y, int64_t N, int K) {
+                          const uint16_t* __restrict__ X, uint16_t* Y, int64_t N, int K, const uint16_t* residual) {
+    // (Y and residual carry no __restrict__: the fused call documents that they may be the same buffer)
     static_assert(BITS >= 1 && BITS <= 4 && 8 % NWK == 0 && (LPR == 8 || LPR == 16 || LPR == 32 || LPR == 64), "shape");
     constexpr int C = 1 << BITS;
     constexpr int G = BITS;                        // words per lane and round: 32 elements
@@ -102,6 +103,17 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
         c = c < nch ? c : nch - 1;
         xt[i] = *reinterpret_cast<const u32x4_t*>(x + c * 8);
     }
+    // residual behind the product (a decoder layer's down projection, paper App. E "Model benchmarks"): the two
+    // rows this thread stores, fetched with the first loads so that they are long there when the epilogue runs
+    uint32_t resv[2] = {0u, 0u};
+    if (residual) {                                // uniform
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            int64_t r2 = wg_row0 + (threadIdx.x * 2 + h) % ROWS_WG;
+            r2 = r2 < N ? r2 : N - 1;
+            resv[h] = residual[r2];
+        }
+    }
     [[maybe_unused]] uint32_t ccv[2];              // 1-bit: centroid pair of the two rows this thread stores
     if constexpr (BITS == 1) {
 #pragma unroll
@@ -150,6 +162,7 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
         // the value is pinned ahead of the branch: a load whose only use sits behind a branch is sunk into it
         asm volatile("" : "+v"(xt[i]));
     }
+    asm volatile("" : "+v"(resv[0]), "+v"(resv[1]));
 #pragma unroll
     for (int i = 0; i < XPT; ++i) {
         const int c = threadIdx.x + i * kLoopThreads;
@@ -345,6 +358,7 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
                 const float c0 = bf16_to_f32(ccv[h] & 0xFFFFu), c1 = bf16_to_f32(ccv[h] >> 16);
                 t = fmaf(c1 - c0, t, c0 * sx);
             }
+            if (residual) t += bf16_to_f32(resv[h]);
             out[h] = t;
         }
         const int64_t r2 = wg_row0 + threadIdx.x * 2;
@@ -404,7 +418,7 @@ void launch_loop_bits(const GemmArgs& a, hipStream_t s) {
     const int rows_wg = 8 / sh.nwk * (64 / sh.lpr) * kRS;
     const dim3 grid(static_cast<unsigned>((a.N + rows_wg - 1) / rows_wg), static_cast<unsigned>(a.M)), block(kLoopThreads);
 #define KMQ_LOOP(LPR, NWK) hipLaunchKernelGGL((gemv_lut_loop_kernel<BITS, LPR, NWK, kRS, kPF(BITS), WPE>), grid, block, sh.x_bytes, s, \
-                                              a.W, a.codebook, a.X, a.Y, a.N, static_cast<int>(a.K))
+                                              a.W, a.codebook, a.X, a.Y, a.N, static_cast<int>(a.K), a.residual)
 #define KMQ_LOOP_NWK(LPR) \
     switch (sh.nwk) { case 1: KMQ_LOOP(LPR, 1); break; case 2: KMQ_LOOP(LPR, 2); break; case 4: KMQ_LOOP(LPR, 4); break; default: KMQ_LOOP(LPR, 8); break; }
     switch (sh.lpr) {
@@ -428,7 +442,7 @@ const char* lut_loop_name(int bits) {
 }
 
 hipError_t launch_lut_loop(const GemmArgs& a, hipStream_t s) {
-    if (!lut_loop_has_kernel(a.N, a.K, a.bits, a.layout) || a.scales || a.W2 || a.norm || a.residual) return hipErrorInvalidValue;
+    if (!lut_loop_has_kernel(a.N, a.K, a.bits, a.layout) || a.scales || a.W2 || a.norm || (a.residual && a.M != 1)) return hipErrorInvalidValue;
     switch (a.bits) {
         case 1: launch_loop_bits<1, 4>(a, s); break;
         case 2: launch_loop_bits<2, 4>(a, s); break;

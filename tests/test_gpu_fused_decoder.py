@@ -75,7 +75,10 @@ def test_fused_on_the_table_kernels(gpu, bits, K, N, mode, use_g, use_r):
 
 
 @pytest.mark.parametrize("mode,use_g,use_r", MODES)
-@pytest.mark.parametrize("bits,N,K", [(3, 40, 1024), (3, 33, 515), (4, 100, 33), (1, 7, 1), (1, 9, 1000), (2, 64, 1024)])
+# (row lengths that are multiples of 32 without a specialised kernel: with no RMSNorm in front, the table kernel that
+# walks K in rounds takes the residual; 5120 and 21504 are SwiGLU widths of App. A's architectures)
+@pytest.mark.parametrize("bits,N,K", [(3, 40, 1024), (3, 33, 515), (4, 100, 33), (1, 7, 1), (1, 9, 1000), (2, 64, 1024),
+                                      (4, 1001, 5120), (3, 300, 21504), (1, 515, 7168)])
 def test_fused_any_shape(gpu, bits, N, K, mode, use_g, use_r):
     from paper_2602_15563_amd import kmq
     assert kmq.kernel_name_fused(N, K, bits) == "fused_generic"
