@@ -118,7 +118,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         // so that staging has no branch for the loads to be sunk into
         u32x4_t xs[(XSLOTS + C16 - 1) / C16 * XSTR];
         float part[NWK][ROWS_WG];                  // per-slice partial sums
-        float sxp[NWK];                            // 1-bit: per-slice sum of x
+        float sxp[NWK * NWR];                      // 1-bit: per-wave sum of the x the wave staged
         float ssq[NWK * NWR];                      // RMSNorm: per-wave sum of x^2 over the chunks the wave staged
     };
     __shared__ Smem sm;
@@ -131,17 +131,20 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     // K and N elements apart per column).  Workgroup ids go round-robin over the 8 XCDs, each with its own L2;
     // the id is cut so that the mcols workgroups that read the same rows of W sit on one XCD, one after the
     // other: the first fetches those rows from memory, the others find them in that L2.
-    int64_t wg = blockIdx.x;
+    // Row numbers are 32-bit (the library caps N at 2^24 rows, the fused pair at 2^25 virtual rows): clamps and
+    // comparisons on 64-bit values cost two to three vector instructions each, ahead of the first load.
+    const int Nr = static_cast<int>(N);
+    int wg = blockIdx.x;
     if (mcols > 1) {
-        const int64_t t = wg >> 3;
-        const int64_t col = t % mcols;
+        const int t = wg >> 3;
+        const int col = t % mcols;
         wg = (t / mcols) * 8 + (wg & 7);
-        if (wg * ROWS_WG >= N) return;                       // the grid is padded to a multiple of 8 row groups
-        x += col * K;
-        y += col * (PAIR ? N / 2 : N);
+        if (wg * ROWS_WG >= Nr) return;                      // the grid is padded to a multiple of 8 row groups
+        x += static_cast<int64_t>(col) * K;
+        y += static_cast<int64_t>(col) * (PAIR ? N / 2 : N);
     }
-    const int64_t wg_row0 = wg * ROWS_WG;
-    const int64_t wave_row0 = wg_row0 + wr * ROWS_WAVE;
+    const int wg_row0 = wg * ROWS_WG;
+    const int wave_row0 = wg_row0 + wr * ROWS_WAVE;
     // start of a row's packed words / codebook (PAIR: even virtual rows first matrix, odd rows second)
     // PAIR: even virtual rows come from the first matrix, odd rows from the second.  The choice
     // is plain integer arithmetic on the addresses: a select between two pointer arguments can
@@ -149,17 +152,17 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     // its set-up at every launch (measured: +15 us per call).
     const uintptr_t w_a = reinterpret_cast<uintptr_t>(W), w_d = PAIR ? reinterpret_cast<uintptr_t>(W2) - w_a : 0;
     const uintptr_t c_a = reinterpret_cast<uintptr_t>(codebook), c_d = PAIR ? reinterpret_cast<uintptr_t>(codebook2) - c_a : 0;
-    auto wrow = [=](int64_t row) -> const uint32_t* {
+    auto wrow = [=](int row) -> const uint32_t* {
         if constexpr (PAIR)
-            return reinterpret_cast<const uint32_t*>(w_a + (w_d & (uintptr_t(0) - uintptr_t(row & 1)))) + (row >> 1) * WPR;
+            return reinterpret_cast<const uint32_t*>(w_a + (w_d & (uintptr_t(0) - uintptr_t(row & 1)))) + static_cast<int64_t>(row >> 1) * WPR;
         else
-            return reinterpret_cast<const uint32_t*>(w_a) + row * WPR;
+            return reinterpret_cast<const uint32_t*>(w_a) + static_cast<int64_t>(row) * WPR;
     };
-    auto cbrow = [=](int64_t row) -> const uint16_t* {
+    auto cbrow = [=](int row) -> const uint16_t* {
         if constexpr (PAIR)
-            return reinterpret_cast<const uint16_t*>(c_a + (c_d & (uintptr_t(0) - uintptr_t(row & 1)))) + (row >> 1) * C;
+            return reinterpret_cast<const uint16_t*>(c_a + (c_d & (uintptr_t(0) - uintptr_t(row & 1)))) + static_cast<int64_t>(row >> 1) * C;
         else
-            return reinterpret_cast<const uint16_t*>(c_a) + row * C;
+            return reinterpret_cast<const uint16_t*>(c_a) + static_cast<int64_t>(row) * C;
     };
 
     // ---- 1. small operands first: x chunks, then the codebook rows of this wave's own rows ----
@@ -183,8 +186,10 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         if constexpr (RES) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {          // fetched with the first loads: long there when the epilogue runs
-                int64_t row = wg_row0 + (threadIdx.x * 2 + h) % ROWS_WG;
-                row = row < N ? row : N - 1;
+                int rl = threadIdx.x * 2 + h;          // (only threads below ROWS_WG / 2 store)
+                rl = rl < ROWS_WG ? rl : ROWS_WG - 1;
+                int row = wg_row0 + rl;
+                row = row < Nr ? row : Nr - 1;
                 resv[h] = residual[row];
             }
         }
@@ -193,8 +198,10 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
             // load issued there would put a whole memory latency behind the last reduction
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                int64_t row = wg_row0 + (threadIdx.x * 2 + h) % ROWS_WG;
-                row = row < N ? row : N - 1;
+                int rl = threadIdx.x * 2 + h;          // (only threads below ROWS_WG / 2 store)
+                rl = rl < ROWS_WG ? rl : ROWS_WG - 1;
+                int row = wg_row0 + rl;
+                row = row < Nr ? row : Nr - 1;
                 ccv[h] = *reinterpret_cast<const uint32_t*>(cbrow(row));
             }
         }
@@ -206,8 +213,8 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     for (int p = 0; p < LUT_PASSES; ++p) {
         int rw = (lane + p * 64) / ENT;                                // row inside the wave: t * RPL + sub
         rw = rw < ROWS_WAVE ? rw : ROWS_WAVE - 1;
-        int64_t row = wave_row0 + rw;
-        row = row < N ? row : N - 1;
+        int row = wave_row0 + rw;
+        row = row < Nr ? row : Nr - 1;
         if constexpr (SC) row = 0;                                     // one table for the whole tensor
         if constexpr (BITS == 2) {
             // (codebooks are 4-byte aligned by contract: the vector types say so)
@@ -236,8 +243,8 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     uint32_t w[RS][G];
 #pragma unroll
     for (int t = 0; t < RS; ++t) {
-        int64_t row = wave_row0 + t * RPL + sub;
-        row = row < N ? row : N - 1;                                   // clamped: loads stay unconditional
+        int row = wave_row0 + t * RPL + sub;
+        row = row < Nr ? row : Nr - 1;                                 // clamped: loads stay unconditional
         load_words<G>(wrow(row) + (wk * LPR + pos) * G, w[t]);
     }
     // block scales of this lane's slices: last in the queue, used after the lookups
@@ -246,10 +253,10 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         const int blk0 = ((wk * LPR + pos) * EL) / KMQ_BLOCK;
 #pragma unroll
         for (int t = 0; t < RS; ++t) {
-            int64_t row = wave_row0 + t * RPL + sub;
-            row = row < N ? row : N - 1;
+            int row = wave_row0 + t * RPL + sub;
+            row = row < Nr ? row : Nr - 1;
 #pragma unroll
-            for (int i = 0; i < NSC; ++i) sv[t][i] = __builtin_nontemporal_load(&scales[row * (K / KMQ_BLOCK) + blk0 + i]);
+            for (int i = 0; i < NSC; ++i) sv[t][i] = __builtin_nontemporal_load(&scales[static_cast<int64_t>(row) * (K / KMQ_BLOCK) + blk0 + i]);
         }
     }
     // where this lane will read its slice of x from: computed now, while the loads are in flight,
@@ -278,6 +285,16 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         ss = threadIdx.x * XPT < XCHUNKS ? ss : 0.f;       // threads past the end restaged a neighbour's chunks
         ss = group_sum<64>(ss);
         if (lane == 63) sm.ssq[wave] = ss;
+    }
+    if constexpr (BITS == 1 && !SC) {
+        // sum of the activations for the two-centroid closed form, taken here from the chunks every thread stages anyway
+        // (4 * XPT dots per thread) rather than from each wave's activation registers behind the lookups
+        float sxl = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4 * XPT; ++i) sxl = dot2_bf16(0x3F803F80u, xt[i], sxl);
+        sxl = threadIdx.x * XPT < XCHUNKS ? sxl : 0.f;     // threads past the end restaged a neighbour's chunks
+        sxl = group_sum<64>(sxl);
+        if (lane == 63) sm.sxp[wave] = sxl;
     }
 #pragma unroll
     for (int h = 0; h < XPT; ++h) {
@@ -433,12 +450,6 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
 #pragma unroll
             for (int t = 0; t < RS; ++t) acc[t] *= bf16_to_f32(sv[t][0]);
         }
-    } else if constexpr (BITS == 1) {
-        float sx = 0.f;
-#pragma unroll
-        for (int i = 0; i < XR; ++i) sx = dot2_bf16(0x3F803F80u, xr[i], sx);
-        sx = group_sum<LPR>(sx);
-        if (wr == 0 && lane == 63) sm.sxp[wk] = sx;
     }
 #pragma unroll
     for (int t = 0; t < RS; ++t) {
@@ -466,7 +477,7 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
             if constexpr (BITS == 1 && !SC) {
                 float sx = 0.f;
 #pragma unroll
-                for (int k = 0; k < NWK; ++k) sx += sm.sxp[k];
+                for (int k = 0; k < NWK * NWR; ++k) sx += sm.sxp[k];
                 const uint32_t cc = ccv[h];
                 const float c0 = bf16_to_f32(cc & 0xFFFFu), c1 = bf16_to_f32(cc >> 16);
                 s = fmaf(c1 - c0, s, c0 * sx);
@@ -475,18 +486,18 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
             if constexpr (RES) s += bf16_to_f32(resv[h]);
             out[h] = s;
         }
-        const int64_t r2 = wg_row0 + threadIdx.x * 2;
+        const int r2 = wg_row0 + threadIdx.x * 2;
         if constexpr (PAIR) {
             // out[0] = gate, out[1] = up of output element r2 / 2: silu(gate) * up in fp32
-            if (r2 < N) y[r2 >> 1] = f32_to_bf16(out[0] / (1.f + __expf(-out[0])) * out[1]);
+            if (r2 < Nr) y[r2 >> 1] = f32_to_bf16(out[0] / (1.f + __expf(-out[0])) * out[1]);
             return;
         }
         const uint32_t packed = static_cast<uint32_t>(f32_to_bf16(out[0])) | (static_cast<uint32_t>(f32_to_bf16(out[1])) << 16);
-        if (r2 + 1 < N && (reinterpret_cast<uintptr_t>(y) & 3u) == 0) {
+        if (r2 + 1 < Nr && (reinterpret_cast<uintptr_t>(y) & 3u) == 0) {
             *reinterpret_cast<uint32_t*>(y + r2) = packed;
         } else {
-            if (r2 < N) y[r2] = static_cast<uint16_t>(packed);
-            if (r2 + 1 < N) y[r2 + 1] = static_cast<uint16_t>(packed >> 16);
+            if (r2 < Nr) y[r2] = static_cast<uint16_t>(packed);
+            if (r2 + 1 < Nr) y[r2 + 1] = static_cast<uint16_t>(packed >> 16);
         }
     }
 }
