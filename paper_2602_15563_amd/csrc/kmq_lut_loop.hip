@@ -70,7 +70,8 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
     const int sub = lane / LPR, pos = lane % LPR;
     const uint16_t* x = X + static_cast<int64_t>(blockIdx.y) * K;   // batch: one grid row per column
     uint16_t* y = Y + static_cast<int64_t>(blockIdx.y) * N;
-    const int64_t wg_row0 = static_cast<int64_t>(blockIdx.x) * ROWS_WG;
+    const int Nr = static_cast<int>(N);            // row numbers fit 32 bits (the library caps N at 2^24)
+    const int wg_row0 = blockIdx.x * ROWS_WG;
     const int R = (xslices + LPR - 1) / LPR;       // rounds per row (the last one may be partly past the end)
     const int rw = (R + NWK - 1) / NWK;            // rounds per wave, contiguous
     const int r_begin = wk * rw;
@@ -80,9 +81,9 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
     const uint32_t* wlane[RS];
 #pragma unroll
     for (int t = 0; t < RS; ++t) {
-        int64_t row = wg_row0 + wr * ROWS_WAVE + t * RPL + sub;
-        row = row < N ? row : N - 1;               // clamped: loads stay unconditional
-        wlane[t] = W + row * wpr;
+        int row = wg_row0 + wr * ROWS_WAVE + t * RPL + sub;
+        row = row < Nr ? row : Nr - 1;             // clamped: loads stay unconditional
+        wlane[t] = W + static_cast<int64_t>(row) * wpr;
     }
     auto load_rounds = [&](int r0, uint32_t (&w)[PF][RS][G]) {
 #pragma unroll
@@ -109,8 +110,10 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
     if (residual) {                                // uniform
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            int64_t r2 = wg_row0 + (threadIdx.x * 2 + h) % ROWS_WG;
-            r2 = r2 < N ? r2 : N - 1;
+            int rl = threadIdx.x * 2 + h;          // (only threads below ROWS_WG / 2 store)
+            rl = rl < ROWS_WG ? rl : ROWS_WG - 1;
+            int r2 = wg_row0 + rl;
+            r2 = r2 < Nr ? r2 : Nr - 1;
             resv[h] = residual[r2];
         }
     }
@@ -118,9 +121,11 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
     if constexpr (BITS == 1) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            int64_t r2 = wg_row0 + (threadIdx.x * 2 + h) % ROWS_WG;
-            r2 = r2 < N ? r2 : N - 1;
-            ccv[h] = *reinterpret_cast<const uint32_t*>(codebook + r2 * C);
+            int rl = threadIdx.x * 2 + h;          // (only threads below ROWS_WG / 2 store)
+            rl = rl < ROWS_WG ? rl : ROWS_WG - 1;
+            int r2 = wg_row0 + rl;
+            r2 = r2 < Nr ? r2 : Nr - 1;
+            ccv[h] = *reinterpret_cast<const uint32_t*>(codebook + static_cast<int64_t>(r2) * C);
         }
     }
     asm volatile("" ::: "memory");
@@ -131,9 +136,9 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
     for (int p = 0; p < LUT_PASSES; ++p) {
         int q = threadIdx.x + p * kLoopThreads;
         q = q < LUT_TOTAL ? q : LUT_TOTAL - 1;
-        int64_t r2 = wg_row0 + q / ENT;
-        r2 = r2 < N ? r2 : N - 1;
-        const uint16_t* cb = codebook + r2 * C;
+        int r2 = wg_row0 + q / ENT;
+        r2 = r2 < Nr ? r2 : Nr - 1;
+        const uint16_t* cb = codebook + static_cast<int64_t>(r2) * C;
         if constexpr (BITS == 2) {
             typedef u32x2_t __attribute__((aligned(4))) u32x2_a4_t;
             const u32x2_t c = *reinterpret_cast<const u32x2_a4_t*>(cb);
@@ -361,13 +366,13 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
             if (residual) t += bf16_to_f32(resv[h]);
             out[h] = t;
         }
-        const int64_t r2 = wg_row0 + threadIdx.x * 2;
+        const int r2 = wg_row0 + threadIdx.x * 2;
         const uint32_t packed = static_cast<uint32_t>(f32_to_bf16(out[0])) | (static_cast<uint32_t>(f32_to_bf16(out[1])) << 16);
-        if (r2 + 1 < N && (reinterpret_cast<uintptr_t>(y + r2) & 3u) == 0) {
+        if (r2 + 1 < Nr && (reinterpret_cast<uintptr_t>(y + r2) & 3u) == 0) {
             *reinterpret_cast<uint32_t*>(y + r2) = packed;
         } else {
-            if (r2 < N) y[r2] = static_cast<uint16_t>(packed);
-            if (r2 + 1 < N) y[r2 + 1] = static_cast<uint16_t>(packed >> 16);
+            if (r2 < Nr) y[r2] = static_cast<uint16_t>(packed);
+            if (r2 + 1 < Nr) y[r2 + 1] = static_cast<uint16_t>(packed >> 16);
         }
     }
 }
