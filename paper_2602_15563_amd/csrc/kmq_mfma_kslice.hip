@@ -120,9 +120,9 @@ __global__ __launch_bounds__(1024) void gemm_mfma_kslice_kernel(
     uint32_t lo0[RPW], lo1[RPW], hi0[RPW], hi1[RPW];        // perm pools: low / high bytes of the lane's centroids
 #pragma unroll
     for (int r = 0; r < RPW; ++r) {
-        int64_t row = rbs[r] * 16 + n;
-        row = row < N ? row : N - 1;
-        const uint32_t* cw = reinterpret_cast<const uint32_t*>(codebook + row * C);
+        int row = static_cast<int>(rbs[r]) * 16 + n;         // (row numbers fit 32 bits: the library caps N at 2^24)
+        row = row < static_cast<int>(N) ? row : static_cast<int>(N) - 1;
+        const uint32_t* cw = reinterpret_cast<const uint32_t*>(codebook + static_cast<int64_t>(row) * C);
         // v_perm_b32(S0, S1, sel): selector values 0..3 pick bytes of S1, 4..7 bytes of S0
         lo0[r] = __builtin_amdgcn_perm(cw[1], cw[0], 0x06040200u);
         hi0[r] = __builtin_amdgcn_perm(cw[1], cw[0], 0x07050301u);
@@ -208,8 +208,8 @@ __global__ __launch_bounds__(1024) void gemm_mfma_kslice_kernel(
         const int r = nl >> 4, nn = nl & 15;
         float s = 0.f;
         for (int k = 0; k < nwk; ++k) s += reinterpret_cast<const float*>(&sm.xstage[k][0])[(r * 16 + m) * 17 + nn];
-        const int64_t row = (static_cast<int64_t>(blockIdx.x) * RPW + r) * 16 + nn;
-        if (r < cnt && m < M && row < N) Y[static_cast<int64_t>(m) * N + row] = f32_to_bf16(s);
+        const int row = (static_cast<int>(blockIdx.x) * RPW + r) * 16 + nn;
+        if (r < cnt && m < M && row < static_cast<int>(N)) Y[static_cast<int64_t>(m) * N + row] = f32_to_bf16(s);
     }
 }
 
