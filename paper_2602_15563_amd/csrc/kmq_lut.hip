@@ -331,6 +331,17 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
         }
     }
 
+    // 1-bit block-scaled: the sums of x over this lane's two blocks, taken now, while the index words are still in
+    // flight, rather than behind the lookups
+    [[maybe_unused]] float sx0 = 0.f, sx1 = 0.f;
+    if constexpr (SC && BITS == 1) {
+#pragma unroll
+        for (int i = 0; i < XR / 2; ++i) {
+            sx0 = dot2_bf16(0x3F803F80u, xr[i], sx0);
+            sx1 = dot2_bf16(0x3F803F80u, xr[XR / 2 + i], sx1);
+        }
+    }
+
     // ---- 4b. this wave's tables, once its codebook rows have arrived --------------------------------
     // (the wave reads back only what it wrote itself: LDS serves a wave's instructions in order)
     __builtin_amdgcn_sched_barrier(0);
@@ -436,12 +447,6 @@ void gemv_lut_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict_
     if constexpr (SC) {
         if constexpr (BITS == 1) {
             // two blocks per lane: s0*(c0*X0 + d*S0) + s1*(c0*X1 + d*S1), X = the block's sum of x
-            float sx0 = 0.f, sx1 = 0.f;
-#pragma unroll
-            for (int i = 0; i < XR / 2; ++i) {
-                sx0 = dot2_bf16(0x3F803F80u, xr[i], sx0);
-                sx1 = dot2_bf16(0x3F803F80u, xr[XR / 2 + i], sx1);
-            }
             const float c0 = bf16_to_f32(cpair & 0xFFFFu), d = bf16_to_f32(cpair >> 16) - c0;
 #pragma unroll
             for (int t = 0; t < RS; ++t)
