@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kLoopThreads) __attribute__((amdgpu_waves_per_eu(WP
 void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
                           const uint16_t* __restrict__ X, uint16_t* Y, int64_t N, int K, const uint16_t* residual) {
     // (Y and residual carry no __restrict__: the fused call documents that they may be the same buffer)
-    static_assert(BITS >= 1 && BITS <= 4 && 8 % NWK == 0 && (LPR == 8 || LPR == 16 || LPR == 32 || LPR == 64), "shape");
+    static_assert(BITS >= 1 && BITS <= 4 && 8 % NWK == 0 && (LPR == 16 || LPR == 32 || LPR == 64), "shape");
     constexpr int C = 1 << BITS;
     constexpr int G = BITS;                        // words per lane and round: 32 elements
     constexpr int NWR = 8 / NWK;
@@ -335,13 +335,7 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
     for (int t = 0; t < RS; ++t) {
         settle_dot(acc[t][0], acc[t][1]);
         float s = acc[t][0] + acc[t][1];
-        if constexpr (LPR == 8) {
-            s += dpp_move<0xB1>(s);    // quad_perm [1,0,3,2]
-            s += dpp_move<0x4E>(s);    // quad_perm [2,3,0,1]
-            s += dpp_move<0x141>(s);   // row_half_mirror: every lane of the eight holds their sum
-        } else {
-            s = group_sum<LPR>(s);     // valid in the last lane of the group
-        }
+        s = group_sum<LPR>(s);         // valid in the last lane of the group
         if (pos == LPR - 1) sm.part[wk][wr * ROWS_WAVE + t * RPL + sub] = s;
     }
     __syncthreads();
