@@ -24,10 +24,9 @@ __device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_floa
 
 // fp32 -> bf16 bit pattern, round to nearest even; NaN stays NaN.
 __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return static_cast<uint16_t>(u >> 16);
+    const uint32_t u = __float_as_uint(f);
+    const uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16, quiet = (u >> 16) | 0x40u;
+    return static_cast<uint16_t>((u & 0x7FFFFFFFu) > 0x7F800000u ? quiet : rounded);   // (a select, not a branch)
 }
 
 // acc + w.lo*x.lo + w.hi*x.hi on packed bf16 pairs, fp32 accumulate (v_dot2c_f32_bf16).
