@@ -105,6 +105,20 @@ def test_residual_may_alias_the_output(gpu):
     assert np.array_equal(a, b)
 
 
+def test_residual_may_alias_the_output_in_the_kernel_that_walks_k(gpu):
+    """No RMSNorm, a row length without a specialised kernel: the residual goes to the epilogue of the table kernel
+    that walks K in rounds; y = residual + product with the residual read from y itself."""
+    from paper_2602_15563_amd import kmq
+    bits, N, K = 3, 1001, 5120
+    assert kmq.kernel_name(N, K, bits, 1) == "lut_loop_b3"
+    idx, cb, x, _, res = _inputs(715, bits, N, K)
+    a = _run(gpu, idx, cb, x, bits, None, res)
+    b = _run(gpu, idx, cb, x, bits, None, res, alias=True)
+    assert np.array_equal(a, b)
+    plain = _run(gpu, idx, cb, x, bits)
+    assert not np.array_equal(a, plain)
+
+
 def test_unit_weights_reduce_to_a_scaled_product(gpu):
     """g = 1: the activations pass unchanged and the result is the plain product times r."""
     N, K = 128, 3072
