@@ -92,7 +92,7 @@ const char* lut_name(int table_index);
 bool lut_has_fusions(int table_index);   // RMSNorm in front / residual behind (GemmArgs::norm_w, residual)
 hipError_t launch_lut_entry(int table_index, const GemmArgs& a, hipStream_t s);
 
-// The table kernel that walks K in rounds of 256 elements (canonical layout, K % 256 == 0, K <= 16384, batch as grid rows).
+// The table kernel that walks K in rounds of 256 elements (canonical layout, K % 32 == 0, K <= 24576, batches in one launch).
 bool lut_loop_has_kernel(int64_t N, int64_t K, int bits, int layout);
 const char* lut_loop_name(int bits);
 hipError_t launch_lut_loop(const GemmArgs& a, hipStream_t s);

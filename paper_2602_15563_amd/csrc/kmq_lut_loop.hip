@@ -36,7 +36,7 @@ constexpr int kLoopThreads = 512;
 template <int BITS, int LPR, int NWK, int RS, int PF, int WPE>
 __global__ __launch_bounds__(kLoopThreads) __attribute__((amdgpu_waves_per_eu(WPE, WPE)))
 void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __restrict__ codebook,
-                          const uint16_t* __restrict__ X, uint16_t* Y, int64_t N, int K, const uint16_t* residual) {
+                          const uint16_t* __restrict__ X, uint16_t* Y, int64_t N, int K, const uint16_t* residual, int mcols) {
     // (Y and residual carry no __restrict__: the fused call documents that they may be the same buffer)
     static_assert(BITS >= 1 && BITS <= 4 && 8 % NWK == 0 && (LPR == 16 || LPR == 32 || LPR == 64), "shape");
     constexpr int C = 1 << BITS;
@@ -68,10 +68,20 @@ void gemv_lut_loop_kernel(const uint32_t* __restrict__ W, const uint16_t* __rest
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int wk = wave % NWK, wr = wave / NWK;
     const int sub = lane / LPR, pos = lane % LPR;
-    const uint16_t* x = X + static_cast<int64_t>(blockIdx.y) * K;   // batch: one grid row per column
-    uint16_t* y = Y + static_cast<int64_t>(blockIdx.y) * N;
+    // A batch of mcols activation rows is one launch, every workgroup one column.  Workgroup ids go round-robin over
+    // the 8 XCDs, each with its own L2; the id is cut so that the mcols workgroups that read the same rows of W sit on
+    // one XCD, one after the other: the first fetches those rows from memory, the others find them in that L2.
+    int wg = blockIdx.x, col = 0;
+    if (mcols > 1) {
+        const int t = wg >> 3;
+        col = t % mcols;
+        wg = (t / mcols) * 8 + (wg & 7);
+        if (static_cast<int64_t>(wg) * ROWS_WG >= N) return;    // the grid is padded to a multiple of 8 row groups
+    }
+    const uint16_t* x = X + static_cast<int64_t>(col) * K;
+    uint16_t* y = Y + static_cast<int64_t>(col) * N;
     const int Nr = static_cast<int>(N);            // row numbers fit 32 bits (the library caps N at 2^24)
-    const int wg_row0 = blockIdx.x * ROWS_WG;
+    const int wg_row0 = wg * ROWS_WG;
     const int R = (xslices + LPR - 1) / LPR;       // rounds per row (the last one may be partly past the end)
     const int rw = (R + NWK - 1) / NWK;            // rounds per wave, contiguous
     const int r_begin = wk * rw;
@@ -415,9 +425,10 @@ template <int BITS, int WPE>
 void launch_loop_bits(const GemmArgs& a, hipStream_t s) {
     const LoopShape sh = loop_shape(a.N, a.K, a.bits);
     const int rows_wg = 8 / sh.nwk * (64 / sh.lpr) * kRS;
-    const dim3 grid(static_cast<unsigned>((a.N + rows_wg - 1) / rows_wg), static_cast<unsigned>(a.M)), block(kLoopThreads);
+    const int64_t groups = (a.N + rows_wg - 1) / rows_wg;
+    const dim3 grid(static_cast<unsigned>(a.M > 1 ? (groups + 7) / 8 * 8 * a.M : groups)), block(kLoopThreads);
 #define KMQ_LOOP(LPR, NWK) hipLaunchKernelGGL((gemv_lut_loop_kernel<BITS, LPR, NWK, kRS, kPF(BITS), WPE>), grid, block, sh.x_bytes, s, \
-                                              a.W, a.codebook, a.X, a.Y, a.N, static_cast<int>(a.K), a.residual)
+                                              a.W, a.codebook, a.X, a.Y, a.N, static_cast<int>(a.K), a.residual, a.M)
 #define KMQ_LOOP_NWK(LPR) \
     switch (sh.nwk) { case 1: KMQ_LOOP(LPR, 1); break; case 2: KMQ_LOOP(LPR, 2); break; case 4: KMQ_LOOP(LPR, 4); break; default: KMQ_LOOP(LPR, 8); break; }
     switch (sh.lpr) {
