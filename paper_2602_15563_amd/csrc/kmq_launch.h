@@ -36,7 +36,7 @@ enum Variant {
     kVariantBlockGeneric,  // block-scaled format, any shape with K % 64 == 0
     kVariantPerColumn,     // canonical layout, batch > 1, shape with a batch-1 table kernel: that kernel over a (row group, column) grid
     kVariantRowlane,       // row-lane layout, batch 1..4: lane-per-row table kernel, activations through DPP broadcasts
-    kVariantLutLoop,       // canonical layout, K % 256 == 0 without a specialised table kernel: the table kernel that walks K in rounds
+    kVariantLutLoop,       // canonical layout, K % 32 == 0 (up to 24576) without a specialised table kernel: the table kernel that walks K in rounds
 };
 
 struct Plan {
@@ -92,7 +92,7 @@ const char* lut_name(int table_index);
 bool lut_has_fusions(int table_index);   // RMSNorm in front / residual behind (GemmArgs::norm_w, residual)
 hipError_t launch_lut_entry(int table_index, const GemmArgs& a, hipStream_t s);
 
-// The table kernel that walks K in rounds of 256 elements (canonical layout, K % 32 == 0, K <= 24576, batches in one launch).
+// The table kernel that walks K in rounds (canonical layout, K % 32 == 0, K <= 24576, batches in one launch).
 bool lut_loop_has_kernel(int64_t N, int64_t K, int bits, int layout);
 const char* lut_loop_name(int bits);
 hipError_t launch_lut_loop(const GemmArgs& a, hipStream_t s);
