@@ -47,6 +47,19 @@ def test_loop_kernel_vs_oracle(gpu, bits, N, K):
     gpu.check_against_oracle(Yg, oracle.pack(idx, bits), cb, X, K, bits, ranges, label=f"lut_loop b{bits} {N}x{K}")
 
 
+# the launcher's choice of lanes per row and waves along K depends on N as well as K, and long rows leave little LDS beside
+# the staged x: every bit-width at the longest row and just below, with few and with many rows
+@pytest.mark.parametrize("bits", (1, 2, 3, 4))
+@pytest.mark.parametrize("N,K", [(3, 24576), (2600, 24576), (2600, 24544), (700, 20512), (6000, 8224), (30000, 2080), (70000, 288)])
+def test_loop_kernel_launch_shapes(gpu, bits, N, K):
+    if kmq.kernel_name(N, K, bits, 1, kmq.LAYOUT_CANONICAL) != f"lut_loop_b{bits}":
+        pytest.skip("few long rows: split over K by the shape-agnostic kernel")
+    idx, cb, X = _case(3 * bits + N + K, N, K, bits, 1)
+    Yg = gpu.run_gemm(gpu.dev(kmq.pack(idx, bits)), gpu.dev(cb), X, N, K, bits)
+    gpu.check_against_oracle(Yg, oracle.pack(idx, bits), cb, X, K, bits, gpu.sample_ranges(N, N + K, nblocks=3),
+                             label=f"lut_loop b{bits} {N}x{K}")
+
+
 @pytest.mark.parametrize("bits,N,K,M", [(3, 1000, 2560, 3), (4, 4099, 5120, 2), (2, 513, 7168, 16), (1, 2048, 1280, 5)])
 def test_loop_kernel_batches(gpu, bits, N, K, M):
     assert kmq.kernel_name(N, K, bits, M, kmq.LAYOUT_CANONICAL) == f"lut_loop_b{bits}"
